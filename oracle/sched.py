@@ -1,0 +1,134 @@
+"""The paper's two scheduling algorithms, step by step (test oracle; not used by
+the product path).
+
+  * assign_streams : stream allocation, paper Algorithm 1 (Sec. 3.1) and the four
+    placement rules of the appendix example.
+  * order_launch   : operator launch order, paper Algorithm 2 (Sec. 3.3).
+  * sync_edges     : the dependencies that need a synchronisation operator
+    (Sec. 3.1 "synchronization operators", Sec. 4 event record / wait).
+  * check_schedule : validity of (stream map, launch queue, sync list).
+
+Readings where the paper is silent (all repeated in the design notes):
+  - topological order = Kahn with the smallest operator id first;
+  - predecessors are visited in argument order, duplicates dropped keeping the first;
+  - streams get dense ids in creation order and are never reused;
+  - external tensors are not operators;
+  - "alternately choose": preference starts at the memory list; the preferred list
+    is used when non-empty, otherwise the other; after a pick the preference is the
+    class opposite to the one just picked;
+  - "least amount of GPU resources": demand = grid_blocks * share, where share is the
+    largest of the workgroup's fractions of a compute unit's thread slots, LDS and
+    vector registers, each in units of 2^-16, rounded up;
+  - argmin ties: smaller topological index first.
+"""
+from .executor import kahn_order
+
+MEM, COMP = 0, 1
+
+
+def dedup_preds(inputs_per_op):
+    """Operator predecessors in argument order, externals (<0) and repeats dropped."""
+    preds = []
+    for ins in inputs_per_op:
+        seen, lst = set(), []
+        for u in ins:
+            if u >= 0 and u not in seen:
+                seen.add(u)
+                lst.append(u)
+        preds.append(lst)
+    return preds
+
+
+def _edges(preds):
+    return [(u, v) for v, ps in enumerate(preds) for u in ps]
+
+
+def assign_streams(preds):
+    """Algorithm 1.  Returns (stream_of, n_streams)."""
+    n = len(preds)
+    topo = kahn_order(n, _edges(preds))
+    sync_flag = [False] * n
+    stream_of = [None] * n
+    n_streams = 0
+    for v in topo:
+        for p in preds[v]:
+            if not sync_flag[p]:
+                stream_of[v] = stream_of[p]
+                sync_flag[p] = True
+                break
+        if stream_of[v] is None:
+            stream_of[v] = n_streams
+            n_streams += 1
+    return stream_of, n_streams
+
+
+def _ceil_div(a, b):
+    return -(-a // b)
+
+
+def demand_scalar(rec, limits):
+    """rec = (grid_blocks, block_threads, lds_bytes, vgprs); limits = dict with
+    threads_per_cu, lds_bytes_per_cu, vgpr_lanes_per_cu.  One integer in units of
+    2^-16 of a compute unit."""
+    g, t, lds, vg = rec
+    share = max(_ceil_div(65536 * t, limits["threads_per_cu"]),
+                _ceil_div(65536 * lds, limits["lds_bytes_per_cu"]),
+                _ceil_div(65536 * t * vg, limits["vgpr_lanes_per_cu"]))
+    return g * share
+
+
+def order_launch(preds, op_class, demand):
+    """Algorithm 2.  op_class[v] in {MEM, COMP}; demand[v] integer.  Returns Q."""
+    n = len(preds)
+    topo = kahn_order(n, _edges(preds))
+    tindex = [0] * n
+    for i, v in enumerate(topo):
+        tindex[v] = i
+    succ = [[] for _ in range(n)]
+    indeg = [0] * n
+    for v, ps in enumerate(preds):
+        for u in ps:
+            succ[u].append(v)
+            indeg[v] += 1
+    lists = {MEM: [], COMP: []}
+    for v in topo:
+        if indeg[v] == 0:
+            lists[op_class[v]].append(v)
+    q = []
+    pref = MEM
+    while lists[MEM] or lists[COMP]:
+        cls = pref if lists[pref] else (COMP if pref == MEM else MEM)
+        lst = lists[cls]
+        vmin = min(lst, key=lambda u: (demand[u], tindex[u]))
+        lst.remove(vmin)
+        q.append(vmin)
+        pref = COMP if cls == MEM else MEM
+        for s in succ[vmin]:
+            indeg[s] -= 1
+            if indeg[s] == 0:
+                lists[op_class[s]].append(s)
+    return q
+
+
+def sync_edges(preds, stream_of):
+    """All dependencies whose endpoints sit on different streams, sorted by (v, arg position)."""
+    return [(u, v) for v, ps in enumerate(preds) for u in ps if stream_of[u] != stream_of[v]]
+
+
+def check_schedule(preds, stream_of, q, syncs):
+    """Raise AssertionError unless q is a topological permutation and every edge is
+    either same-stream (ordered by q) or listed in syncs."""
+    n = len(preds)
+    assert sorted(q) == list(range(n)), "Q is not a permutation"
+    pos = [0] * n
+    for i, v in enumerate(q):
+        pos[v] = i
+    sset = set(syncs)
+    for v, ps in enumerate(preds):
+        for u in ps:
+            assert pos[u] < pos[v], f"edge {u}->{v} violates launch order"
+            if stream_of[u] != stream_of[v]:
+                assert (u, v) in sset, f"cross-stream edge {u}->{v} has no sync"
+    for (u, v) in syncs:
+        assert u in preds[v] and stream_of[u] != stream_of[v], f"spurious sync {u}->{v}"
+    return True
