@@ -1,0 +1,226 @@
+/*
+ * opara.h - C ABI of the operator-parallel DAG executor for AMD MI355X (gfx950).
+ *
+ * The library executes one batch-1 DNN operator DAG G=(V,E) (paper Sec. 3.1,
+ * "Definition of a model DAG") with independent operators running concurrently
+ * on several HIP streams, replayed from a single captured hipGraph (paper
+ * Sec. 3.4, Graph Capturer).
+ *
+ * General conventions
+ *   - Every call returns an opara_status; on failure opara_last_error() gives a
+ *     thread-local text valid until the next call on that thread.
+ *   - Result arrays are allocated by the CALLER (host memory) with the stated
+ *     length; the library only fills them.
+ *   - The library never allocates device memory and never creates streams.  All
+ *     tensor pointers in opara_op_desc and ext_inputs are DEVICE pointers owned by
+ *     the caller; they must stay valid and fixed for the life of every opara_exec
+ *     captured from the DAG (replay uses the addresses baked in at capture, the
+ *     static-buffer semantics of graph replay in paper Sec. 4).
+ *   - opara_build_dag / opara_assign_streams / opara_order_launch /
+ *     opara_sync_edges / opara_get_demands / opara_topo_order make no HIP call
+ *     and work on a machine without a GPU.
+ *   - The library owns only its opaque handles (and the hipGraph, hipGraphExec and
+ *     events inside an opara_exec).
+ *
+ * Physical tensor layouts (device memory)
+ *   - image activations: [H][W][C], C fastest (batch 1)
+ *   - matrices: [rows][cols] row-major
+ *   - convolution weight: [C_out][kh][kw][C_in]; GEMM weight: [N][K] (K fastest)
+ *   - bias: fp32 [C_out] / [N] regardless of the tensor dtype; may be NULL
+ *   - element type of activations and weights: opara_op_desc.dtype
+ */
+#ifndef OPARA_H
+#define OPARA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OPARA_MAX_INPUTS 8
+
+typedef struct opara_dag  opara_dag;   /* created by opara_build_dag, freed by opara_dag_destroy   */
+typedef struct opara_exec opara_exec;  /* created by opara_capture,  freed by opara_exec_destroy   */
+
+enum opara_status {
+  OPARA_OK = 0,
+  OPARA_EINVAL = -1,       /* bad argument (null pointer, id out of range, bad shape ...)   */
+  OPARA_ECYCLE = -2,       /* the operator graph has a cycle or a self-loop                 */
+  OPARA_ENOMEM = -3,
+  OPARA_ESTATE = -4,       /* call made out of order (e.g. capture before assign + order)   */
+  OPARA_EHIP = -5,         /* a HIP call failed; text via opara_last_error()                */
+  OPARA_EUNSUPPORTED = -6  /* operator / shape has no kernel                                */
+};
+
+enum opara_op_type {
+  OPARA_CONV2D = 0, OPARA_GEMM, OPARA_BGEMM, OPARA_MAXPOOL, OPARA_AVGPOOL, OPARA_GAVGPOOL,
+  OPARA_CONCAT, OPARA_LAYERNORM, OPARA_SOFTMAX, OPARA_GELU, OPARA_RELU, OPARA_ADD,
+  OPARA_N_OP_TYPES
+};
+
+/* Operator table of paper Sec. 3.3 (memory- vs compute-intensive operators). */
+enum opara_class { OPARA_CLASS_DEFAULT = -1, OPARA_MEM = 0, OPARA_COMP = 1 };
+enum opara_dtype { OPARA_F32 = 0, OPARA_F16 = 1 };
+enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1 };
+
+enum opara_flags {
+  OPARA_FLAG_RELU     = 1u,  /* CONV2D / GEMM: clamp the result at zero                    */
+  OPARA_FLAG_B_KMAJOR = 2u   /* BGEMM: second operand stored [K][N] (N fastest), else [N][K] */
+};
+
+/* Per-compute-unit limits that turn a demand record into one integer
+ * (paper Sec. 2.1: an SM/CU is limited in threads, shared memory and registers). */
+typedef struct {
+  uint32_t num_cus;            /* informational                                            */
+  uint32_t threads_per_cu;     /* resident work-items per CU (MI355X: 2048)                */
+  uint32_t lds_bytes_per_cu;   /* MI355X: 163840                                           */
+  uint32_t vgpr_lanes_per_cu;  /* vector registers x lanes per CU (MI355X: 4*512*64)       */
+} opara_limits;
+
+/*
+ * Shape parameters.  Which fields an operator reads:
+ *   CONV2D            h_in,w_in,c_in, h_out,w_out,c_out, kh,kw,sh,sw,ph,pw, flags(RELU).
+ *                     y[oh][ow][co] = bias[co] + sum x[oh*sh+i-ph][ow*sw+j-pw][ci]*w[co][i][j][ci],
+ *                     zero padding, cross-correlation, floor output size.
+ *   GEMM              m,n,k, flags(RELU).  Y[m][n] = X[m][k].W + bias + sum of inputs[1..] viewed [m][n].
+ *   BGEMM             batch,m,n,k, alpha, the six strides (in elements), flags(B_KMAJOR).
+ *                     C_b[m][n] = alpha * A_b[m][k] . B_b ; A = inputs[0], B = inputs[1].
+ *   MAXPOOL/AVGPOOL   h_in,w_in,c_in,h_out,w_out, kh,kw,sh,sw,ph,pw.  Max pads with -inf;
+ *                     average pads with zero and always divides by kh*kw.
+ *   GAVGPOOL          h_in,w_in,c_in -> [c_in].
+ *   CONCAT            m rows; in_cols[i] columns from input i; n = sum of in_cols.
+ *   LAYERNORM/SOFTMAX m rows, n cols, eps (LayerNorm: biased variance, gamma 1, beta 0),
+ *                     applied to the SUM of all inputs, each viewed [m][n].
+ *   GELU/RELU/ADD     m*n elements; f(sum of all inputs).  GELU is the exact erf form.
+ * Every input is read as the leading prefix of its producer's buffer in the shape above.
+ */
+typedef struct {
+  int32_t h_in, w_in, c_in;
+  int32_t h_out, w_out, c_out;
+  int32_t kh, kw, sh, sw, ph, pw;
+  int32_t m, n, k;
+  int32_t batch;
+  int64_t a_batch_stride, a_row_stride;
+  int64_t b_batch_stride, b_row_stride;
+  int64_t c_batch_stride, c_row_stride;
+  int32_t in_cols[OPARA_MAX_INPUTS];
+  float   alpha, eps;
+  uint32_t flags;
+} opara_op_params;
+
+/* One operator v in V with its resource-demand record (paper Sec. 3.2, Model Profiler). */
+typedef struct {
+  int32_t  op_type;                    /* enum opara_op_type                                */
+  int32_t  op_class;                   /* enum opara_class; DEFAULT = by op_type: CONV2D,
+                                          GEMM, BGEMM are COMP, everything else MEM         */
+  int32_t  dtype;                      /* enum opara_dtype                                  */
+  int32_t  n_inputs;                   /* 1..OPARA_MAX_INPUTS                               */
+  int32_t  inputs[OPARA_MAX_INPUTS];   /* producer operator ids in ARGUMENT ORDER;
+                                          id < 0 means external tensor slot -(id+1)         */
+  uint32_t grid_blocks, block_threads, lds_bytes, vgprs;
+                                       /* demand record used for ordering only.  All four 0:
+                                          take it from the library's kernel table           */
+  opara_op_params params;
+  const void *weight;                  /* device, caller-owned (CONV2D, GEMM), else NULL    */
+  const float *bias;                   /* device fp32, caller-owned, may be NULL            */
+  void *out;                           /* device, caller-owned, distinct per operator       */
+} opara_op_desc;
+
+/* What opara_get_demands reports per operator. */
+typedef struct {
+  uint32_t grid_blocks, block_threads, lds_bytes, vgprs;
+  int32_t  op_class;                   /* resolved class: OPARA_MEM or OPARA_COMP           */
+  int32_t  kernel_id;                  /* index into the kernel table, see opara_kernel_info */
+  uint64_t demand;                     /* scalar used by opara_order_launch                 */
+} opara_demand;
+
+/*
+ * Build the DAG (paper Sec. 3.1).  Validates ids and shapes, drops repeated
+ * producers keeping the first, computes the topological order (ready operator with
+ * the smallest id first), selects a kernel and launch shape per operator and
+ * derives its demand record.  ops/ext_inputs are copied; nothing is retained.
+ * Errors: EINVAL (null, n_ops <= 0, id out of range, bad n_inputs, bad shape),
+ * ECYCLE, EUNSUPPORTED, ENOMEM.  lim == NULL selects the MI355X limits.
+ */
+int opara_build_dag(const opara_op_desc *ops, int32_t n_ops,
+                    void *const *ext_inputs, int32_t n_ext,
+                    const opara_limits *lim, opara_dag **out);
+
+/*
+ * Stream allocation, paper Algorithm 1: operators are visited in topological
+ * order; an operator joins the stream of its first predecessor (argument order)
+ * that no successor has joined yet, otherwise it opens a new stream.  Stream ids are
+ * dense in creation order.  stream_of: host int32[n_ops]; n_streams: host int32.
+ */
+int opara_assign_streams(opara_dag *g, int32_t *stream_of, int32_t *n_streams);
+
+/*
+ * Launch order, paper Algorithm 2: two ready lists (memory- and compute-intensive),
+ * chosen alternately starting with the memory list (the other one when the
+ * preferred list is empty); from the chosen list the operator with the least
+ * demand goes next (ties: topological index).  order: host int32[n_ops].
+ */
+int opara_order_launch(opara_dag *g, int32_t *order);
+
+/*
+ * Dependencies that need a synchronisation operator (paper Sec. 3.1, Eq. 3; Sec. 4):
+ * every edge (u,v) whose endpoints are on different streams, sorted by (v, argument
+ * position of u).  uv: host int32[2*cap] filled with pairs u,v up to cap pairs;
+ * n_edges always receives the full count.  Needs opara_assign_streams first (ESTATE).
+ */
+int opara_sync_edges(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges);
+
+/* Demand records (paper Sec. 3.2) and default topological order; host arrays [n_ops]. */
+int opara_get_demands(const opara_dag *g, opara_demand *out);
+int opara_topo_order(const opara_dag *g, int32_t *order);
+int32_t opara_num_ops(const opara_dag *g);
+
+/*
+ * Graph capture (paper Sec. 3.4): puts hip_streams[0..n_streams) (hipStream_t
+ * handles supplied by the caller, at least as many as opara_assign_streams
+ * reported) into capture, launches every operator on its stream in launch-queue
+ * order, records one event after each producer that has a cross-stream consumer,
+ * makes each consumer's stream wait once per such producer, joins all streams
+ * back into hip_streams[0] and instantiates ONE executable graph.  Nothing
+ * executes.  mode OPARA_SEQUENTIAL captures the same kernels with the same launch
+ * shapes on hip_streams[0] alone in default topological order (the baseline:
+ * paper Sec. 5.1, default sequential graph).  Errors: ESTATE if assign/order were
+ * not called (PARALLEL), EINVAL, EHIP (capture is ended and the partial graph
+ * destroyed before returning).
+ */
+int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams,
+                  int32_t mode, opara_exec **out);
+
+/* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
+int opara_replay(opara_exec *e, void *hip_stream);
+
+/* Nodes and dependency edges of the captured graph (host int32 each). */
+int opara_exec_info(const opara_exec *e, int32_t *n_nodes, int32_t *n_edges);
+
+/*
+ * Launch ONE operator's kernel, or all operators in topological order, eagerly on a
+ * stream (no graph).  Used for profiling an operator in isolation (paper Sec. 3.2:
+ * profile once) and for debugging.
+ */
+int opara_launch_op(opara_dag *g, int32_t op, void *hip_stream);
+int opara_run_eager(opara_dag *g, void *hip_stream);
+
+/*
+ * Kernel table: static resources of every kernel in the library, read from the
+ * compiled code objects at build time (vgprs = vector + accumulation registers per
+ * lane; lds_bytes = static LDS per workgroup).  opara_kernel_device_attrs asks the
+ * HIP runtime for the same figures (needs a GPU).
+ */
+int32_t opara_kernel_count(void);
+int opara_kernel_info(int32_t kernel_id, const char **name, uint32_t *vgprs, uint32_t *lds_bytes);
+int opara_kernel_device_attrs(int32_t kernel_id, uint32_t *vgprs, uint32_t *lds_bytes);
+
+void opara_exec_destroy(opara_exec *e);
+void opara_dag_destroy(opara_dag *g);
+const char *opara_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPARA_H */

@@ -1,0 +1,211 @@
+"""ctypes binding of include/opara.h: same names, argument marshalling only."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libopara.so")
+MAX_INPUTS = 8
+
+OK, EINVAL, ECYCLE, ENOMEM, ESTATE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+(CONV2D, GEMM, BGEMM, MAXPOOL, AVGPOOL, GAVGPOOL, CONCAT, LAYERNORM, SOFTMAX, GELU, RELU,
+ ADD) = range(12)
+OP_TYPE_IDS = dict(conv2d=CONV2D, gemm=GEMM, bgemm=BGEMM, maxpool=MAXPOOL, avgpool=AVGPOOL,
+                   gavgpool=GAVGPOOL, concat=CONCAT, layernorm=LAYERNORM, softmax=SOFTMAX,
+                   gelu=GELU, relu=RELU, add=ADD)
+CLASS_DEFAULT, MEM, COMP = -1, 0, 1
+F32, F16 = 0, 1
+PARALLEL, SEQUENTIAL = 0, 1
+FLAG_RELU, FLAG_B_KMAJOR = 1, 2
+
+
+class OparaError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"opara status {status}: {text}")
+        self.status = status
+
+
+class Limits(C.Structure):
+    _fields_ = [("num_cus", C.c_uint32), ("threads_per_cu", C.c_uint32),
+                ("lds_bytes_per_cu", C.c_uint32), ("vgpr_lanes_per_cu", C.c_uint32)]
+
+
+class OpParams(C.Structure):
+    _fields_ = [("h_in", C.c_int32), ("w_in", C.c_int32), ("c_in", C.c_int32),
+                ("h_out", C.c_int32), ("w_out", C.c_int32), ("c_out", C.c_int32),
+                ("kh", C.c_int32), ("kw", C.c_int32), ("sh", C.c_int32), ("sw", C.c_int32),
+                ("ph", C.c_int32), ("pw", C.c_int32),
+                ("m", C.c_int32), ("n", C.c_int32), ("k", C.c_int32), ("batch", C.c_int32),
+                ("a_batch_stride", C.c_int64), ("a_row_stride", C.c_int64),
+                ("b_batch_stride", C.c_int64), ("b_row_stride", C.c_int64),
+                ("c_batch_stride", C.c_int64), ("c_row_stride", C.c_int64),
+                ("in_cols", C.c_int32 * MAX_INPUTS),
+                ("alpha", C.c_float), ("eps", C.c_float), ("flags", C.c_uint32)]
+
+
+class OpDesc(C.Structure):
+    _fields_ = [("op_type", C.c_int32), ("op_class", C.c_int32), ("dtype", C.c_int32),
+                ("n_inputs", C.c_int32), ("inputs", C.c_int32 * MAX_INPUTS),
+                ("grid_blocks", C.c_uint32), ("block_threads", C.c_uint32),
+                ("lds_bytes", C.c_uint32), ("vgprs", C.c_uint32),
+                ("params", OpParams),
+                ("weight", C.c_void_p), ("bias", C.c_void_p), ("out", C.c_void_p)]
+
+
+class Demand(C.Structure):
+    _fields_ = [("grid_blocks", C.c_uint32), ("block_threads", C.c_uint32),
+                ("lds_bytes", C.c_uint32), ("vgprs", C.c_uint32),
+                ("op_class", C.c_int32), ("kernel_id", C.c_int32), ("demand", C.c_uint64)]
+
+
+EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_sync_edges",
+           "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
+           "opara_replay", "opara_exec_info", "opara_launch_op", "opara_run_eager",
+           "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
+           "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
+
+_lib = None
+
+
+def load():
+    """Load libopara.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+    lib.opara_build_dag.argtypes = [C.POINTER(OpDesc), C.c_int32, C.POINTER(C.c_void_p), C.c_int32,
+                                    C.POINTER(Limits), C.POINTER(vp)]
+    lib.opara_assign_streams.argtypes = [vp, i32p, i32p]
+    lib.opara_order_launch.argtypes = [vp, i32p]
+    lib.opara_sync_edges.argtypes = [vp, i32p, C.c_int32, i32p]
+    lib.opara_get_demands.argtypes = [vp, C.POINTER(Demand)]
+    lib.opara_topo_order.argtypes = [vp, i32p]
+    lib.opara_num_ops.argtypes = [vp]
+    lib.opara_capture.argtypes = [vp, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(vp)]
+    lib.opara_replay.argtypes = [vp, vp]
+    lib.opara_exec_info.argtypes = [vp, i32p, i32p]
+    lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
+    lib.opara_run_eager.argtypes = [vp, vp]
+    lib.opara_kernel_count.argtypes = []
+    lib.opara_kernel_info.argtypes = [C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.opara_kernel_device_attrs.argtypes = [C.c_int32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.opara_exec_destroy.argtypes = [vp]
+    lib.opara_exec_destroy.restype = None
+    lib.opara_dag_destroy.argtypes = [vp]
+    lib.opara_dag_destroy.restype = None
+    lib.opara_last_error.argtypes = []
+    lib.opara_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != OK:
+        raise OparaError(rc, load().opara_last_error().decode())
+
+
+def opara_last_error():
+    return load().opara_last_error().decode()
+
+
+def opara_build_dag(descs, ext_ptrs, limits=None):
+    """descs: list[OpDesc]; ext_ptrs: list[int] device addresses.  Returns the dag handle."""
+    arr = (OpDesc * max(len(descs), 1))(*descs)
+    ext = (C.c_void_p * max(len(ext_ptrs), 1))(*ext_ptrs)
+    out = C.c_void_p()
+    lim = C.byref(limits) if limits is not None else None
+    _check(load().opara_build_dag(arr, len(descs), ext, len(ext_ptrs), lim, C.byref(out)))
+    return out
+
+
+def opara_num_ops(dag):
+    return load().opara_num_ops(dag)
+
+
+def opara_assign_streams(dag):
+    n = opara_num_ops(dag)
+    so = (C.c_int32 * n)()
+    ns = C.c_int32()
+    _check(load().opara_assign_streams(dag, so, C.byref(ns)))
+    return list(so), ns.value
+
+
+def opara_order_launch(dag):
+    n = opara_num_ops(dag)
+    q = (C.c_int32 * n)()
+    _check(load().opara_order_launch(dag, q))
+    return list(q)
+
+
+def opara_sync_edges(dag):
+    ne = C.c_int32()
+    _check(load().opara_sync_edges(dag, None, 0, C.byref(ne)))
+    uv = (C.c_int32 * max(2 * ne.value, 1))()
+    _check(load().opara_sync_edges(dag, uv, ne.value, C.byref(ne)))
+    return [(uv[2 * i], uv[2 * i + 1]) for i in range(ne.value)]
+
+
+def opara_get_demands(dag):
+    n = opara_num_ops(dag)
+    d = (Demand * n)()
+    _check(load().opara_get_demands(dag, d))
+    return list(d)
+
+
+def opara_topo_order(dag):
+    n = opara_num_ops(dag)
+    q = (C.c_int32 * n)()
+    _check(load().opara_topo_order(dag, q))
+    return list(q)
+
+
+def opara_capture(dag, stream_handles, mode):
+    arr = (C.c_void_p * len(stream_handles))(*stream_handles)
+    out = C.c_void_p()
+    _check(load().opara_capture(dag, arr, len(stream_handles), mode, C.byref(out)))
+    return out
+
+
+def opara_replay(exe, stream_handle):
+    _check(load().opara_replay(exe, C.c_void_p(stream_handle)))
+
+
+def opara_exec_info(exe):
+    a, b = C.c_int32(), C.c_int32()
+    _check(load().opara_exec_info(exe, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def opara_launch_op(dag, op, stream_handle):
+    _check(load().opara_launch_op(dag, op, C.c_void_p(stream_handle)))
+
+
+def opara_run_eager(dag, stream_handle):
+    _check(load().opara_run_eager(dag, C.c_void_p(stream_handle)))
+
+
+def opara_kernel_count():
+    return load().opara_kernel_count()
+
+
+def opara_kernel_info(kernel_id):
+    name, v, l = C.c_char_p(), C.c_uint32(), C.c_uint32()
+    _check(load().opara_kernel_info(kernel_id, C.byref(name), C.byref(v), C.byref(l)))
+    return name.value.decode(), v.value, l.value
+
+
+def opara_kernel_device_attrs(kernel_id):
+    v, l = C.c_uint32(), C.c_uint32()
+    _check(load().opara_kernel_device_attrs(kernel_id, C.byref(v), C.byref(l)))
+    return v.value, l.value
+
+
+def opara_exec_destroy(exe):
+    load().opara_exec_destroy(exe)
+
+
+def opara_dag_destroy(dag):
+    load().opara_dag_destroy(dag)

@@ -1,0 +1,137 @@
+// Plain-data kernel argument records and the kernel list, shared by the host-side
+// planner (which fills them at DAG build time) and the HIP translation unit (which
+// launches them).  No HIP types here: the planner builds without a GPU toolchain.
+#pragma once
+#include <stdint.h>
+
+namespace opara {
+
+// Implicit-GEMM convolution / GEMM / strided batched GEMM.
+//   D[n][m] = alpha * sum_k Wt[n][k] * Xg[m][k]   (n: output channel/column, m: pixel/row)
+// Xg is either a plain matrix (gather == 0, row stride lda) or an on-the-fly patch
+// gather from an [H][W][Cin] image with k = (i*kw + j)*Cin + ci (gather == 1).
+struct IgemmArgs {
+  const void *x, *w;
+  const float *bias;
+  void *y;
+  const void *extra[3];
+  int32_t n_extra;
+  int32_t M, N, K;
+  int32_t gather;
+  int32_t H, W, Cin, Wo, kh, kw, sh, sw, ph, pw;
+  int64_t lda, ldb, ldy;        // row strides in elements
+  int64_t a_bs, b_bs, y_bs;     // batch strides in elements (blockIdx.z)
+  int32_t b_kmajor;             // second operand stored [K][N]
+  int32_t relu;
+  float alpha;
+};
+
+struct PoolArgs {
+  const void *x;
+  void *y;
+  int32_t H, W, C, Ho, Wo, kh, kw, sh, sw, ph, pw;
+  int32_t is_avg;
+};
+
+struct GapArgs {
+  const void *x;
+  void *y;
+  int32_t HW, C;
+};
+
+struct RowArgs {               // LayerNorm / softmax over rows of the summed inputs
+  const void *in[8];
+  void *y;
+  int32_t n_in, rows, cols;
+  float eps;
+};
+
+struct EltArgs {               // f(sum of inputs), f in {identity, relu, gelu}
+  const void *in[8];
+  void *y;
+  int32_t n_in, op;            // op: 0 add, 1 relu, 2 gelu
+  int64_t n;
+};
+
+struct ConcatArgs {
+  const void *in[8];
+  void *y;
+  int32_t cols[8], col_off[8];
+  int32_t n_in, rows, out_cols;
+};
+
+// X(name, ArgsType).  Order defines kernel ids.
+#define OPARA_KERNEL_LIST(X)            \
+  X(igemm_f16_t128x128, IgemmArgs)      \
+  X(igemm_f16_t64x64, IgemmArgs)        \
+  X(igemm_f16_t32x32, IgemmArgs)        \
+  X(igemm_f16_t64x64_scalar, IgemmArgs) \
+  X(igemm_f32_t128x128, IgemmArgs)      \
+  X(igemm_f32_t64x64, IgemmArgs)        \
+  X(igemm_f32_t32x32, IgemmArgs)        \
+  X(igemm_f32_t64x64_scalar, IgemmArgs) \
+  X(gemv_f16, IgemmArgs)                \
+  X(gemv_f32, IgemmArgs)                \
+  X(pool_f16_vec, PoolArgs)             \
+  X(pool_f16_scalar, PoolArgs)          \
+  X(pool_f32_vec, PoolArgs)             \
+  X(pool_f32_scalar, PoolArgs)          \
+  X(gap_f16, GapArgs)                   \
+  X(gap_f32, GapArgs)                   \
+  X(layernorm_f16_wave, RowArgs)        \
+  X(layernorm_f16_block, RowArgs)       \
+  X(layernorm_f16_generic, RowArgs)     \
+  X(layernorm_f32_wave, RowArgs)        \
+  X(layernorm_f32_block, RowArgs)       \
+  X(layernorm_f32_generic, RowArgs)     \
+  X(softmax_f16_wave, RowArgs)          \
+  X(softmax_f16_block, RowArgs)         \
+  X(softmax_f16_generic, RowArgs)       \
+  X(softmax_f32_wave, RowArgs)          \
+  X(softmax_f32_block, RowArgs)         \
+  X(softmax_f32_generic, RowArgs)       \
+  X(elt_f16_vec, EltArgs)               \
+  X(elt_f16_scalar, EltArgs)            \
+  X(elt_f32_vec, EltArgs)               \
+  X(elt_f32_scalar, EltArgs)            \
+  X(concat_f16_vec, ConcatArgs)         \
+  X(concat_f16_scalar, ConcatArgs)      \
+  X(concat_f32_vec, ConcatArgs)         \
+  X(concat_f32_scalar, ConcatArgs)
+
+enum KernelId : int32_t {
+#define X(name, T) K_##name,
+  OPARA_KERNEL_LIST(X)
+#undef X
+  K_COUNT
+};
+
+union KernelArgs {
+  IgemmArgs igemm;
+  PoolArgs pool;
+  GapArgs gap;
+  RowArgs row;
+  EltArgs elt;
+  ConcatArgs concat;
+};
+
+// One planned launch: which kernel, its grid and its arguments.
+struct KernelPlan {
+  int32_t kernel;
+  uint32_t gx, gy, gz;
+  uint32_t block;
+  KernelArgs args;
+};
+
+// Tile geometry of the implicit-GEMM kernels (output columns x rows per workgroup).
+struct IgemmTile { int bn, bm, threads; };
+constexpr IgemmTile kTile128{128, 128, 256};
+constexpr IgemmTile kTile64{64, 64, 256};
+constexpr IgemmTile kTile32{32, 32, 64};
+
+constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)
+constexpr int kRowGroupBlock = 256;   // block variant
+constexpr int kRowCacheChunks = 4;    // 16-byte chunks a thread keeps in registers
+constexpr int kGemvMaxM = 4;
+
+}  // namespace opara

@@ -1,0 +1,593 @@
+// Operator kernels for gfx950 (CDNA4) and their launcher.
+//
+// The paper runs vendor-library kernels (Sec. 5.1); these are this library's own.
+// Dense contractions (convolution as implicit GEMM, GEMM, batched GEMM) use the
+// matrix cores; everything else is a coalesced 16-byte-per-lane streaming kernel
+// with wavefront (64-lane) reductions where rows are reduced.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "kernel_args.h"
+#include "launch.h"
+
+namespace opara {
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct Vec16;
+template <> struct Vec16<half_t> { typedef half8 type; typedef half4 quad; static constexpr int N = 8; };
+template <> struct Vec16<float> { typedef floatx4 type; typedef floatx4 quad; static constexpr int N = 4; };
+
+// ---------------------------------------------------------------------------------
+// Implicit GEMM on the matrix cores.
+//
+// Workgroup tile: BN output columns (channels) x BM output rows (pixels); K is walked
+// in slices of 64 bytes per row (32 halves / 16 floats).  Both operands are staged in
+// LDS with K fastest and an 80-byte row pitch, so that the 16-byte fragment reads of
+// 16 consecutive rows fall into distinct banks.  Weights feed the MFMA "A" side and
+// pixels the "B" side: each lane then owns four consecutive output channels of one
+// pixel, which is a contiguous 8/16-byte store in the [row][channel] output.
+// The mapping of K positions onto MFMA K slots is the same for both operands, which is
+// all a dot product needs, so the same 16-byte fragment load serves fp16 and fp32.
+// ---------------------------------------------------------------------------------
+template <typename T> __device__ __forceinline__ floatx4 mma16(typename Vec16<T>::type a, typename Vec16<T>::type b, floatx4 c);
+template <> __device__ __forceinline__ floatx4 mma16<half_t>(half8 a, half8 b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ floatx4 mma16<float>(floatx4 a, floatx4 b, floatx4 c) {
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], c, 0, 0, 0);
+  return c;
+}
+
+template <typename T, int BN, int BM, int WN, int WM, bool VEC>
+__device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
+  typedef typename Vec16<T>::type V;
+  typedef typename Vec16<T>::quad Q;
+  constexpr int VE = Vec16<T>::N;
+  constexpr int BKE = 4 * VE;              // K elements per slice
+  constexpr int NT = WN * WM * 64;
+  constexpr int ROWB = 80;                 // LDS row pitch in bytes (64 data + 16 pad)
+  constexpr int CHW = BN * 4 / NT;         // 16-byte chunks of the weight tile per thread
+  constexpr int CHX = BM * 4 / NT;
+  constexpr int FN = BN / WN / 16, FM = BM / WM / 16;
+  static_assert((BN * 4) % NT == 0 && (BM * 4) % NT == 0, "tile/threads mismatch");
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][(BN + BM) * ROWB];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wn0 = (wave % WN) * (BN / WN), wm0 = (wave / WN) * (BM / WM);
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+  const int kc = t & 3;                    // which 16-byte chunk of a 64-byte K slice
+  const int row0 = t >> 2;                 // first tile row this thread moves
+  constexpr int RSTEP = NT / 4;
+
+  int ih0[CHX], iw0[CHX];
+  if (a.gather) {
+#pragma unroll
+    for (int i = 0; i < CHX; ++i) {
+      const int m = m0 + row0 + i * RSTEP;
+      const int oh = m / a.Wo, ow = m - oh * a.Wo;
+      ih0[i] = oh * a.sh - a.ph;
+      iw0[i] = ow * a.sw - a.pw;
+    }
+  }
+  // running decomposition of this thread's K position (vector path, gather only)
+  int g_ci = 0, g_s = 0, g_r = 0;
+  if (VEC && a.gather) {
+    const int k = kc * VE;
+    g_ci = k % a.Cin;
+    const int rs = k / a.Cin;
+    g_s = rs % a.kw;
+    g_r = rs / a.kw;
+  }
+
+  V wreg[CHW], xreg[CHX];
+  const V vzero = {};
+
+  auto load_global = [&](int kt) {
+    const int kbase = kt * BKE + kc * VE;
+    // ---- pixel (im2col / matrix row) chunks
+#pragma unroll
+    for (int i = 0; i < CHX; ++i) {
+      const int m = m0 + row0 + i * RSTEP;
+      V v = vzero;
+      if (VEC) {
+        if (m < a.M && kbase < a.K) {
+          if (!a.gather) {
+            v = *(const V *)(x + (int64_t)m * a.lda + kbase);
+          } else {
+            const int ih = ih0[i] + g_r, iw = iw0[i] + g_s;
+            if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+              v = *(const V *)(x + ((int64_t)ih * a.W + iw) * a.Cin + g_ci);
+          }
+        }
+      } else {
+        if (m < a.M) {
+#pragma unroll
+          for (int e = 0; e < VE; ++e) {
+            const int k = kbase + e;
+            if (k < a.K) {
+              if (!a.gather) {
+                v[e] = x[(int64_t)m * a.lda + k];
+              } else {
+                const int ci = k % a.Cin, rs = k / a.Cin;
+                const int ih = ih0[i] + rs / a.kw, iw = iw0[i] + rs % a.kw;
+                if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+                  v[e] = x[((int64_t)ih * a.W + iw) * a.Cin + ci];
+              }
+            }
+          }
+        }
+      }
+      xreg[i] = v;
+    }
+    // ---- weight chunks
+#pragma unroll
+    for (int i = 0; i < CHW; ++i) {
+      V v = vzero;
+      if (!a.b_kmajor) {
+        const int n = n0 + row0 + i * RSTEP;
+        if (VEC) {
+          if (n < a.N && kbase < a.K) v = *(const V *)(w + (int64_t)n * a.ldb + kbase);
+        } else if (n < a.N) {
+#pragma unroll
+          for (int e = 0; e < VE; ++e)
+            if (kbase + e < a.K) v[e] = w[(int64_t)n * a.ldb + kbase + e];
+        }
+      } else {
+        // operand stored [K][N]: a chunk runs along N at one K position
+        const int c = t + i * NT;
+        const int krow = c / (BN / VE), nch = c % (BN / VE);
+        const int k = kt * BKE + krow, n = n0 + nch * VE;
+        if (k < a.K) {
+          if (VEC) {
+            if (n < a.N) v = *(const V *)(w + (int64_t)k * a.ldb + n);
+          } else {
+#pragma unroll
+            for (int e = 0; e < VE; ++e)
+              if (n + e < a.N) v[e] = w[(int64_t)k * a.ldb + n + e];
+          }
+        }
+      }
+      wreg[i] = v;
+    }
+    if (VEC && a.gather) {  // advance the running K decomposition by one slice
+      g_ci += BKE;
+      while (g_ci >= a.Cin) {
+        g_ci -= a.Cin;
+        if (++g_s == a.kw) { g_s = 0; ++g_r; }
+      }
+    }
+  };
+
+  auto store_lds = [&](int buf) {
+    unsigned char *Wb = smem[buf];
+    unsigned char *Xb = Wb + BN * ROWB;
+#pragma unroll
+    for (int i = 0; i < CHX; ++i) *(V *)(Xb + (row0 + i * RSTEP) * ROWB + kc * 16) = xreg[i];
+#pragma unroll
+    for (int i = 0; i < CHW; ++i) {
+      if (!a.b_kmajor) {
+        *(V *)(Wb + (row0 + i * RSTEP) * ROWB + kc * 16) = wreg[i];
+      } else {
+        const int c = t + i * NT;
+        const int krow = c / (BN / VE), nch = c % (BN / VE);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) *(T *)(Wb + (nch * VE + e) * ROWB + krow * (int)sizeof(T)) = wreg[i][e];
+      }
+    }
+  };
+
+  floatx4 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int nk = (a.K + BKE - 1) / BKE;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  int buf = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const bool more = kt + 1 < nk;
+    if (more) load_global(kt + 1);
+    {
+      const unsigned char *Wb = smem[buf];
+      const unsigned char *Xb = Wb + BN * ROWB;
+      V af[FN], bf[FM];
+#pragma unroll
+      for (int i = 0; i < FN; ++i) af[i] = *(const V *)(Wb + (wn0 + i * 16 + (lane & 15)) * ROWB + (lane >> 4) * 16);
+#pragma unroll
+      for (int j = 0; j < FM; ++j) bf[j] = *(const V *)(Xb + (wm0 + j * 16 + (lane & 15)) * ROWB + (lane >> 4) * 16);
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j) acc[i][j] = mma16<T>(af[i], bf[j], acc[i][j]);
+    }
+    if (more) store_lds(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue: alpha, bias, residual inputs, ReLU, convert, store
+#pragma unroll
+  for (int i = 0; i < FN; ++i) {
+    const int n = n0 + wn0 + i * 16 + (lane >> 4) * 4;
+#pragma unroll
+    for (int j = 0; j < FM; ++j) {
+      const int m = m0 + wm0 + j * 16 + (lane & 15);
+      if (m >= a.M || n >= a.N) continue;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float r = acc[i][j][e] * a.alpha;
+        if (n + e < a.N) {
+          if (a.bias) r += a.bias[n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
+        }
+        if (a.relu) r = fmaxf(r, 0.f);
+        v[e] = r;
+      }
+      T *dst = y + (int64_t)m * a.ldy + n;
+      if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+        Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+        *(Q *)dst = q4;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < a.N) dst[e] = (T)v[e];
+      }
+    }
+  }
+}
+
+// Matrix-vector shaped GEMM (M <= kGemvMaxM rows): one wavefront per output column,
+// 16-byte loads along K, shuffle reduction.  Weight-bandwidth bound by construction.
+template <typename T>
+__device__ __forceinline__ void gemv_body(const IgemmArgs &a) {
+  typedef typename Vec16<T>::type V;
+  constexpr int VE = Vec16<T>::N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave;
+  if (n >= a.N) return;
+  const T *__restrict__ x = (const T *)a.x;
+  const T *__restrict__ wr = (const T *)a.w + (int64_t)n * a.ldb;
+  float acc[kGemvMaxM] = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = lane * VE; k0 < a.K; k0 += 64 * VE) {
+    const V wv = *(const V *)(wr + k0);
+#pragma unroll
+    for (int m = 0; m < kGemvMaxM; ++m) {
+      if (m < a.M) {
+        const V xv = *(const V *)(x + (int64_t)m * a.lda + k0);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) acc[m] += (float)wv[e] * (float)xv[e];
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < kGemvMaxM; ++m)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[m] += __shfl_xor(acc[m], off, 64);
+  if (lane == 0) {
+    T *y = (T *)a.y;
+    for (int m = 0; m < a.M; ++m) {
+      float r = acc[m] * a.alpha;
+      if (a.bias) r += a.bias[n];
+      for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n];
+      if (a.relu) r = fmaxf(r, 0.f);
+      y[(int64_t)m * a.ldy + n] = (T)r;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Pooling over [H][W][C]: one thread per output pixel and channel chunk.
+// ---------------------------------------------------------------------------------
+template <typename T, int VE>
+__device__ __forceinline__ void pool_body(const PoolArgs &a) {
+  const int cch = a.C / VE;
+  const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (item >= (int64_t)a.Ho * a.Wo * cch) return;
+  const int cc = (int)(item % cch);
+  const int pix = (int)(item / cch);
+  const int ow = pix % a.Wo, oh = pix / a.Wo;
+  const T *__restrict__ x = (const T *)a.x;
+  float acc[VE];
+#pragma unroll
+  for (int e = 0; e < VE; ++e) acc[e] = a.is_avg ? 0.f : -INFINITY;
+  for (int i = 0; i < a.kh; ++i) {
+    const int ih = oh * a.sh - a.ph + i;
+    if ((unsigned)ih >= (unsigned)a.H) continue;
+    for (int j = 0; j < a.kw; ++j) {
+      const int iw = ow * a.sw - a.pw + j;
+      if ((unsigned)iw >= (unsigned)a.W) continue;
+      const T *src = x + ((int64_t)ih * a.W + iw) * a.C + cc * VE;
+      T v[VE];
+      if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
+      else v[0] = src[0];
+#pragma unroll
+      for (int e = 0; e < VE; ++e) acc[e] = a.is_avg ? acc[e] + (float)v[e] : fmaxf(acc[e], (float)v[e]);
+    }
+  }
+  const float scale = a.is_avg ? 1.0f / (float)(a.kh * a.kw) : 1.0f;
+  T o[VE];
+#pragma unroll
+  for (int e = 0; e < VE; ++e) o[e] = (T)(a.is_avg ? acc[e] * scale : acc[e]);
+  T *dst = (T *)a.y + (int64_t)pix * a.C + cc * VE;
+  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)o;
+  else dst[0] = o[0];
+}
+
+template <typename T>
+__device__ __forceinline__ void gap_body(const GapArgs &a) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= a.C) return;
+  const T *__restrict__ x = (const T *)a.x;
+  float s = 0.f;
+  for (int p = 0; p < a.HW; ++p) s += (float)x[(int64_t)p * a.C + c];
+  ((T *)a.y)[c] = (T)(s / (float)a.HW);
+}
+
+// ---------------------------------------------------------------------------------
+// Row-wise LayerNorm / softmax of the summed inputs.  G lanes share a row (a
+// wavefront, or the 256-thread workgroup); the row lives in registers between the
+// statistics passes, so HBM sees one read per input and one write.
+// ---------------------------------------------------------------------------------
+template <int G, bool IS_MAX>
+__device__ __forceinline__ float group_reduce(float v, float *scratch) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float o = __shfl_xor(v, off, 64);
+    v = IS_MAX ? fmaxf(v, o) : v + o;
+  }
+  if (G > 64) {
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();                    // scratch may still be read from a previous reduction
+    if ((threadIdx.x & 63) == 0) scratch[wave] = v;
+    __syncthreads();
+    v = scratch[0];
+#pragma unroll
+    for (int i = 1; i < G / 64; ++i) v = IS_MAX ? fmaxf(v, scratch[i]) : v + scratch[i];
+  }
+  return v;
+}
+
+template <typename T, bool IS_LN, int G, int MAXCH>
+__device__ __forceinline__ void row_cached_body(const RowArgs &a) {
+  typedef typename Vec16<T>::type V;
+  constexpr int VE = Vec16<T>::N;
+  __shared__ float scratch[4];
+  const int gl = threadIdx.x % G;
+  const int row = blockIdx.x * (256 / G) + threadIdx.x / G;
+  if (G == 64 && row >= a.rows) return;          // whole wavefront leaves together
+  float v[MAXCH][VE];
+  const int64_t base = (int64_t)row * a.cols;
+#pragma unroll
+  for (int c = 0; c < MAXCH; ++c) {
+    const int col = (c * G + gl) * VE;
+#pragma unroll
+    for (int e = 0; e < VE; ++e) v[c][e] = 0.f;
+    if (col < a.cols) {
+      for (int q = 0; q < a.n_in; ++q) {
+        const V t = *(const V *)((const T *)a.in[q] + base + col);
+#pragma unroll
+        for (int e = 0; e < VE; ++e) v[c][e] += (float)t[e];
+      }
+    }
+  }
+  if (IS_LN) {
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+      if ((c * G + gl) * VE < a.cols)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) s += v[c][e];
+    const float mean = group_reduce<G, false>(s, scratch) / (float)a.cols;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+      if ((c * G + gl) * VE < a.cols)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) { const float d = v[c][e] - mean; q += d * d; }
+    const float var = group_reduce<G, false>(q, scratch) / (float)a.cols;
+    const float rstd = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+#pragma unroll
+      for (int e = 0; e < VE; ++e) v[c][e] = (v[c][e] - mean) * rstd;
+  } else {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+      if ((c * G + gl) * VE < a.cols)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) mx = fmaxf(mx, v[c][e]);
+    mx = group_reduce<G, true>(mx, scratch);
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+      if ((c * G + gl) * VE < a.cols)
+#pragma unroll
+        for (int e = 0; e < VE; ++e) { v[c][e] = expf(v[c][e] - mx); s += v[c][e]; }
+    const float inv = 1.0f / group_reduce<G, false>(s, scratch);
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+#pragma unroll
+      for (int e = 0; e < VE; ++e) v[c][e] *= inv;
+  }
+#pragma unroll
+  for (int c = 0; c < MAXCH; ++c) {
+    const int col = (c * G + gl) * VE;
+    if (col < a.cols) {
+      V o;
+#pragma unroll
+      for (int e = 0; e < VE; ++e) o[e] = (T)v[c][e];
+      *(V *)((T *)a.y + base + col) = o;
+    }
+  }
+}
+
+// Any width / alignment: one workgroup per row, scalar accesses, inputs re-read per pass.
+template <typename T, bool IS_LN>
+__device__ __forceinline__ void row_generic_body(const RowArgs &a) {
+  __shared__ float scratch[4];
+  const int64_t base = (int64_t)blockIdx.x * a.cols;
+  auto value = [&](int col) {
+    float s = 0.f;
+    for (int q = 0; q < a.n_in; ++q) s += (float)((const T *)a.in[q])[base + col];
+    return s;
+  };
+  float p1 = IS_LN ? 0.f : -INFINITY;
+  for (int col = threadIdx.x; col < a.cols; col += 256) p1 = IS_LN ? p1 + value(col) : fmaxf(p1, value(col));
+  const float r1 = IS_LN ? group_reduce<256, false>(p1, scratch) / (float)a.cols : group_reduce<256, true>(p1, scratch);
+  float p2 = 0.f;
+  for (int col = threadIdx.x; col < a.cols; col += 256) {
+    const float d = value(col) - r1;
+    p2 += IS_LN ? d * d : expf(d);
+  }
+  const float r2 = group_reduce<256, false>(p2, scratch);
+  const float k = IS_LN ? 1.0f / sqrtf(r2 / (float)a.cols + a.eps) : 1.0f / r2;
+  for (int col = threadIdx.x; col < a.cols; col += 256) {
+    const float d = value(col) - r1;
+    ((T *)a.y)[base + col] = (T)(IS_LN ? d * k : expf(d) * k);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Element-wise f(sum of inputs) and channel/column concatenation.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float elt_apply(int op, float x) {
+  if (op == 1) return fmaxf(x, 0.f);
+  if (op == 2) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+  return x;
+}
+
+template <typename T, int VE>
+__device__ __forceinline__ void elt_body(const EltArgs &a) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VE;
+  if (i >= a.n) return;
+  float s[VE];
+#pragma unroll
+  for (int e = 0; e < VE; ++e) s[e] = 0.f;
+  for (int q = 0; q < a.n_in; ++q) {
+    T v[VE];
+    const T *src = (const T *)a.in[q] + i;
+    if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
+    else v[0] = src[0];
+#pragma unroll
+    for (int e = 0; e < VE; ++e) s[e] += (float)v[e];
+  }
+  T o[VE];
+#pragma unroll
+  for (int e = 0; e < VE; ++e) o[e] = (T)elt_apply(a.op, s[e]);
+  T *dst = (T *)a.y + i;
+  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)o;
+  else dst[0] = o[0];
+}
+
+template <typename T, int VE>
+__device__ __forceinline__ void concat_body(const ConcatArgs &a) {
+  const int q = blockIdx.y;
+  const int cch = a.cols[q] / VE;
+  const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (item >= (int64_t)a.rows * cch) return;
+  const int64_t r = item / cch;
+  const int c = (int)(item % cch) * VE;
+  const T *src = (const T *)a.in[q] + r * a.cols[q] + c;
+  T *dst = (T *)a.y + r * a.out_cols + a.col_off[q] + c;
+  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)src;
+  else dst[0] = src[0];
+}
+
+}  // namespace opara
+
+using namespace opara;
+
+#define KDEF(name, threads, Args, call) \
+  extern "C" __global__ void __launch_bounds__(threads) opara_k_##name(Args a) { call; }
+
+KDEF(igemm_f16_t128x128, 256, IgemmArgs, (igemm_body<half_t, 128, 128, 2, 2, true>(a)))
+KDEF(igemm_f16_t64x64, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true>(a)))
+KDEF(igemm_f16_t32x32, 64, IgemmArgs, (igemm_body<half_t, 32, 32, 1, 1, true>(a)))
+KDEF(igemm_f16_t64x64_scalar, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false>(a)))
+KDEF(igemm_f32_t128x128, 256, IgemmArgs, (igemm_body<float, 128, 128, 2, 2, true>(a)))
+KDEF(igemm_f32_t64x64, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true>(a)))
+KDEF(igemm_f32_t32x32, 64, IgemmArgs, (igemm_body<float, 32, 32, 1, 1, true>(a)))
+KDEF(igemm_f32_t64x64_scalar, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false>(a)))
+KDEF(gemv_f16, 256, IgemmArgs, (gemv_body<half_t>(a)))
+KDEF(gemv_f32, 256, IgemmArgs, (gemv_body<float>(a)))
+KDEF(pool_f16_vec, 256, PoolArgs, (pool_body<half_t, 8>(a)))
+KDEF(pool_f16_scalar, 256, PoolArgs, (pool_body<half_t, 1>(a)))
+KDEF(pool_f32_vec, 256, PoolArgs, (pool_body<float, 4>(a)))
+KDEF(pool_f32_scalar, 256, PoolArgs, (pool_body<float, 1>(a)))
+KDEF(gap_f16, 64, GapArgs, (gap_body<half_t>(a)))
+KDEF(gap_f32, 64, GapArgs, (gap_body<float>(a)))
+KDEF(layernorm_f16_wave, 256, RowArgs, (row_cached_body<half_t, true, 64, 2>(a)))
+KDEF(layernorm_f16_block, 256, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks>(a)))
+KDEF(layernorm_f16_generic, 256, RowArgs, (row_generic_body<half_t, true>(a)))
+KDEF(layernorm_f32_wave, 256, RowArgs, (row_cached_body<float, true, 64, 2>(a)))
+KDEF(layernorm_f32_block, 256, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks>(a)))
+KDEF(layernorm_f32_generic, 256, RowArgs, (row_generic_body<float, true>(a)))
+KDEF(softmax_f16_wave, 256, RowArgs, (row_cached_body<half_t, false, 64, 2>(a)))
+KDEF(softmax_f16_block, 256, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks>(a)))
+KDEF(softmax_f16_generic, 256, RowArgs, (row_generic_body<half_t, false>(a)))
+KDEF(softmax_f32_wave, 256, RowArgs, (row_cached_body<float, false, 64, 2>(a)))
+KDEF(softmax_f32_block, 256, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks>(a)))
+KDEF(softmax_f32_generic, 256, RowArgs, (row_generic_body<float, false>(a)))
+KDEF(elt_f16_vec, 256, EltArgs, (elt_body<half_t, 8>(a)))
+KDEF(elt_f16_scalar, 256, EltArgs, (elt_body<half_t, 1>(a)))
+KDEF(elt_f32_vec, 256, EltArgs, (elt_body<float, 4>(a)))
+KDEF(elt_f32_scalar, 256, EltArgs, (elt_body<float, 1>(a)))
+KDEF(concat_f16_vec, 256, ConcatArgs, (concat_body<half_t, 8>(a)))
+KDEF(concat_f16_scalar, 256, ConcatArgs, (concat_body<half_t, 1>(a)))
+KDEF(concat_f32_vec, 256, ConcatArgs, (concat_body<float, 4>(a)))
+KDEF(concat_f32_scalar, 256, ConcatArgs, (concat_body<float, 1>(a)))
+
+namespace opara {
+
+namespace {
+template <typename A> const A &arg_of(const KernelArgs &u);
+template <> const IgemmArgs &arg_of<IgemmArgs>(const KernelArgs &u) { return u.igemm; }
+template <> const PoolArgs &arg_of<PoolArgs>(const KernelArgs &u) { return u.pool; }
+template <> const GapArgs &arg_of<GapArgs>(const KernelArgs &u) { return u.gap; }
+template <> const RowArgs &arg_of<RowArgs>(const KernelArgs &u) { return u.row; }
+template <> const EltArgs &arg_of<EltArgs>(const KernelArgs &u) { return u.elt; }
+template <> const ConcatArgs &arg_of<ConcatArgs>(const KernelArgs &u) { return u.concat; }
+}  // namespace
+
+hipError_t launch_plan(const KernelPlan &p, hipStream_t s) {
+  const dim3 grid(p.gx, p.gy, p.gz), block(p.block);
+  switch (p.kernel) {
+#define X(name, A)                                                                     \
+  case K_##name:                                                                       \
+    hipLaunchKernelGGL(opara_k_##name, grid, block, 0, s, arg_of<A>(p.args));          \
+    break;
+    OPARA_KERNEL_LIST(X)
+#undef X
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+const void *kernel_symbol(int id) {
+  switch (id) {
+#define X(name, A) \
+  case K_##name:   \
+    return (const void *)opara_k_##name;
+    OPARA_KERNEL_LIST(X)
+#undef X
+    default:
+      return nullptr;
+  }
+}
+
+}  // namespace opara

@@ -1,0 +1,35 @@
+// Internal representation behind the C ABI handles.
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "../../include/opara.h"
+#include "kernel_args.h"
+
+struct opara_dag {
+  int32_t n = 0;
+  std::vector<opara_op_desc> ops;
+  std::vector<void *> ext;
+  opara_limits lim{};
+  // CSR adjacency over operator ids; predecessors in argument order, deduplicated.
+  std::vector<int32_t> pred_off, pred, succ_off, succ;
+  std::vector<int32_t> topo, tindex;
+  std::vector<opara::KernelPlan> plan;
+  std::vector<opara_demand> dem;
+  std::vector<int32_t> stream_of;   // empty until opara_assign_streams
+  int32_t n_streams = 0;
+  std::vector<int32_t> order;       // empty until opara_order_launch
+};
+
+namespace opara {
+
+struct KernelResource { const char *name; uint32_t vgprs, agprs, lds_bytes; };
+extern const KernelResource kKernelResources[K_COUNT];
+
+void set_error(const char *fmt, ...);
+
+// Chooses the kernel, grid and arguments for operator `v`; `in[i]` are the resolved
+// device pointers of its inputs.  Returns an opara_status.
+int plan_op(const opara_op_desc &op, const void *const *in, KernelPlan *out);
+
+}  // namespace opara

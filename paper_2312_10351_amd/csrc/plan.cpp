@@ -1,0 +1,242 @@
+// Kernel table and per-operator launch planning (host only, no HIP calls).
+// The demand record of an operator (paper Sec. 3.2: threads, shared memory and
+// registers of one block; Sec. 2.3: number of blocks) follows from the plan made
+// here plus the static resources of the chosen kernel.
+#include <cstring>
+#include "opara_internal.h"
+
+namespace opara {
+
+// Generated at build time from the compiler's per-kernel resource report of
+// kernels.hip; one row per entry of OPARA_KERNEL_LIST, same order.
+const KernelResource kKernelResources[K_COUNT] = {
+#include "kernel_resources.inc"
+};
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline uint32_t cdiv(int64_t a, int64_t b) { return (uint32_t)((a + b - 1) / b); }
+
+int fail(const char *what, const opara_op_desc &op) {
+  set_error("operator type %d: %s", op.op_type, what);
+  return OPARA_EINVAL;
+}
+
+int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  const bool f16 = op.dtype == OPARA_F16;
+  const int ve = f16 ? 8 : 4;
+  IgemmArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.x = in[0];
+  a.bias = op.bias;
+  a.y = op.out;
+  a.alpha = 1.0f;
+  a.relu = (p.flags & OPARA_FLAG_RELU) ? 1 : 0;
+  int64_t batch = 1;
+  bool vec;
+  if (op.op_type == OPARA_CONV2D) {
+    if (op.n_inputs != 1 || !op.weight) return fail("convolution needs one input and a weight", op);
+    if (p.h_in <= 0 || p.w_in <= 0 || p.c_in <= 0 || p.c_out <= 0 || p.kh <= 0 || p.kw <= 0 ||
+        p.sh <= 0 || p.sw <= 0 || p.ph < 0 || p.pw < 0)
+      return fail("bad convolution geometry", op);
+    if (p.h_out != (p.h_in + 2 * p.ph - p.kh) / p.sh + 1 || p.w_out != (p.w_in + 2 * p.pw - p.kw) / p.sw + 1 ||
+        p.h_out <= 0 || p.w_out <= 0)
+      return fail("convolution output size does not match floor((in + 2*pad - k)/stride) + 1", op);
+    a.w = op.weight;
+    a.M = p.h_out * p.w_out;
+    a.N = p.c_out;
+    a.K = p.kh * p.kw * p.c_in;
+    a.gather = !(p.kh == 1 && p.kw == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0);
+    a.H = p.h_in; a.W = p.w_in; a.Cin = p.c_in; a.Wo = p.w_out;
+    a.kh = p.kh; a.kw = p.kw; a.sh = p.sh; a.sw = p.sw; a.ph = p.ph; a.pw = p.pw;
+    a.lda = p.c_in; a.ldb = a.K; a.ldy = p.c_out;
+    vec = (p.c_in % ve == 0);
+  } else if (op.op_type == OPARA_GEMM) {
+    if (!op.weight || op.n_inputs > 4) return fail("GEMM needs a weight and at most 3 extra inputs", op);
+    if (p.m <= 0 || p.n <= 0 || p.k <= 0) return fail("bad GEMM shape", op);
+    a.w = op.weight;
+    a.M = p.m; a.N = p.n; a.K = p.k;
+    a.lda = p.k; a.ldb = p.k; a.ldy = p.n;
+    a.n_extra = op.n_inputs - 1;
+    for (int i = 0; i < a.n_extra; ++i) a.extra[i] = in[i + 1];
+    vec = (p.k % ve == 0);
+  } else {  // BGEMM
+    if (op.n_inputs != 2) return fail("batched GEMM needs two inputs", op);
+    if (p.m <= 0 || p.n <= 0 || p.k <= 0 || p.batch <= 0 || p.batch > 65535) return fail("bad batched GEMM shape", op);
+    if (p.a_row_stride < p.k || p.c_row_stride < p.n || p.a_batch_stride < 0 || p.b_batch_stride < 0 ||
+        p.c_batch_stride < 0)
+      return fail("bad batched GEMM strides", op);
+    a.w = in[1];
+    a.M = p.m; a.N = p.n; a.K = p.k;
+    a.lda = p.a_row_stride; a.ldb = p.b_row_stride; a.ldy = p.c_row_stride;
+    a.a_bs = p.a_batch_stride; a.b_bs = p.b_batch_stride; a.y_bs = p.c_batch_stride;
+    a.b_kmajor = (p.flags & OPARA_FLAG_B_KMAJOR) ? 1 : 0;
+    if (a.b_kmajor ? p.b_row_stride < p.n : p.b_row_stride < p.k) return fail("bad batched GEMM strides", op);
+    a.alpha = p.alpha;
+    batch = p.batch;
+    vec = (p.k % ve == 0) && (a.lda % ve == 0) && (a.ldb % ve == 0) && (a.a_bs % ve == 0) && (a.b_bs % ve == 0) &&
+          (!a.b_kmajor || p.n % ve == 0);
+  }
+  vec = vec && aligned16(a.x) && aligned16(a.w);
+  int kernel;
+  IgemmTile t = kTile64;
+  if (vec && op.op_type == OPARA_GEMM && a.M <= kGemvMaxM) {
+    kernel = f16 ? K_gemv_f16 : K_gemv_f32;
+    out->kernel = kernel;
+    out->gx = cdiv(a.N, 4);            // one wave per output column, four waves per workgroup
+    out->gy = out->gz = 1;
+    out->block = 256;
+    out->args.igemm = a;
+    return OPARA_OK;
+  }
+  if (!vec) {
+    kernel = f16 ? K_igemm_f16_t64x64_scalar : K_igemm_f32_t64x64_scalar;
+  } else {
+    const int64_t n128 = (int64_t)cdiv(a.M, 128) * cdiv(a.N, 128) * batch;
+    const int64_t n64 = (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * batch;
+    if (n128 >= 128) { t = kTile128; kernel = f16 ? K_igemm_f16_t128x128 : K_igemm_f32_t128x128; }
+    else if (n64 >= 48) { t = kTile64; kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64; }
+    else { t = kTile32; kernel = f16 ? K_igemm_f16_t32x32 : K_igemm_f32_t32x32; }
+  }
+  out->kernel = kernel;
+  out->gx = cdiv(a.M, t.bm);
+  out->gy = cdiv(a.N, t.bn);
+  out->gz = (uint32_t)batch;
+  out->block = t.threads;
+  out->args.igemm = a;
+  return OPARA_OK;
+}
+
+int plan_pool(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  const bool f16 = op.dtype == OPARA_F16;
+  const int ve = f16 ? 8 : 4;
+  if (op.n_inputs != 1) return fail("pooling takes one input", op);
+  if (p.h_in <= 0 || p.w_in <= 0 || p.c_in <= 0 || p.kh <= 0 || p.kw <= 0 || p.sh <= 0 || p.sw <= 0 ||
+      p.ph < 0 || p.pw < 0 || p.ph >= p.kh || p.pw >= p.kw)
+    return fail("bad pooling geometry", op);
+  if (p.h_out != (p.h_in + 2 * p.ph - p.kh) / p.sh + 1 || p.w_out != (p.w_in + 2 * p.pw - p.kw) / p.sw + 1 ||
+      p.h_out <= 0 || p.w_out <= 0)
+    return fail("pooling output size does not match floor((in + 2*pad - k)/stride) + 1", op);
+  PoolArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.x = in[0]; a.y = op.out;
+  a.H = p.h_in; a.W = p.w_in; a.C = p.c_in; a.Ho = p.h_out; a.Wo = p.w_out;
+  a.kh = p.kh; a.kw = p.kw; a.sh = p.sh; a.sw = p.sw; a.ph = p.ph; a.pw = p.pw;
+  a.is_avg = op.op_type == OPARA_AVGPOOL;
+  const bool vec = (p.c_in % ve == 0) && aligned16(a.x) && aligned16(a.y);
+  out->kernel = f16 ? (vec ? K_pool_f16_vec : K_pool_f16_scalar) : (vec ? K_pool_f32_vec : K_pool_f32_scalar);
+  const int64_t items = (int64_t)p.h_out * p.w_out * (vec ? p.c_in / ve : p.c_in);
+  out->gx = cdiv(items, 256); out->gy = out->gz = 1; out->block = 256;
+  out->args.pool = a;
+  return OPARA_OK;
+}
+
+int plan_gap(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  if (op.n_inputs != 1 || p.h_in <= 0 || p.w_in <= 0 || p.c_in <= 0) return fail("bad global pooling shape", op);
+  GapArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.x = in[0]; a.y = op.out; a.HW = p.h_in * p.w_in; a.C = p.c_in;
+  out->kernel = op.dtype == OPARA_F16 ? K_gap_f16 : K_gap_f32;
+  out->gx = cdiv(p.c_in, 64); out->gy = out->gz = 1; out->block = 64;
+  out->args.gap = a;
+  return OPARA_OK;
+}
+
+int plan_row(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  const bool f16 = op.dtype == OPARA_F16;
+  const int ve = f16 ? 8 : 4;
+  if (p.m <= 0 || p.n <= 0) return fail("bad row-wise shape", op);
+  RowArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.y = op.out; a.n_in = op.n_inputs; a.rows = p.m; a.cols = p.n; a.eps = p.eps;
+  bool vec = (p.n % ve == 0) && aligned16(a.y);
+  for (int i = 0; i < op.n_inputs; ++i) { a.in[i] = in[i]; vec = vec && aligned16(in[i]); }
+  const bool ln = op.op_type == OPARA_LAYERNORM;
+  int variant;  // 0 wave, 1 block, 2 generic
+  if (vec && p.n <= kRowGroupWave * ve * 2) variant = 0;
+  else if (vec && p.n <= kRowGroupBlock * ve * kRowCacheChunks) variant = 1;
+  else variant = 2;
+  static const int ids[2][2][3] = {
+      {{K_softmax_f32_wave, K_softmax_f32_block, K_softmax_f32_generic},
+       {K_softmax_f16_wave, K_softmax_f16_block, K_softmax_f16_generic}},
+      {{K_layernorm_f32_wave, K_layernorm_f32_block, K_layernorm_f32_generic},
+       {K_layernorm_f16_wave, K_layernorm_f16_block, K_layernorm_f16_generic}}};
+  out->kernel = ids[ln][f16][variant];
+  out->block = 256;
+  out->gx = variant == 0 ? cdiv(p.m, 256 / kRowGroupWave) : (uint32_t)p.m;
+  out->gy = out->gz = 1;
+  out->args.row = a;
+  return OPARA_OK;
+}
+
+int plan_elt(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  const bool f16 = op.dtype == OPARA_F16;
+  const int ve = f16 ? 8 : 4;
+  if (p.m <= 0 || p.n <= 0) return fail("bad element-wise shape", op);
+  EltArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.y = op.out; a.n_in = op.n_inputs; a.n = (int64_t)p.m * p.n;
+  a.op = op.op_type == OPARA_ADD ? 0 : op.op_type == OPARA_RELU ? 1 : 2;
+  bool vec = (a.n % ve == 0) && aligned16(a.y);
+  for (int i = 0; i < op.n_inputs; ++i) { a.in[i] = in[i]; vec = vec && aligned16(in[i]); }
+  out->kernel = f16 ? (vec ? K_elt_f16_vec : K_elt_f16_scalar) : (vec ? K_elt_f32_vec : K_elt_f32_scalar);
+  out->gx = cdiv(vec ? a.n / ve : a.n, 256); out->gy = out->gz = 1; out->block = 256;
+  out->args.elt = a;
+  return OPARA_OK;
+}
+
+int plan_concat(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  const opara_op_params &p = op.params;
+  const bool f16 = op.dtype == OPARA_F16;
+  const int ve = f16 ? 8 : 4;
+  if (p.m <= 0) return fail("bad concat shape", op);
+  ConcatArgs a;
+  std::memset(&a, 0, sizeof a);
+  a.y = op.out; a.n_in = op.n_inputs; a.rows = p.m;
+  bool vec = aligned16(a.y);
+  int32_t off = 0, widest = 0;
+  for (int i = 0; i < op.n_inputs; ++i) {
+    if (p.in_cols[i] <= 0) return fail("concat input with no columns", op);
+    a.in[i] = in[i]; a.cols[i] = p.in_cols[i]; a.col_off[i] = off;
+    off += p.in_cols[i];
+    if (p.in_cols[i] > widest) widest = p.in_cols[i];
+    vec = vec && (p.in_cols[i] % ve == 0) && aligned16(in[i]);
+  }
+  if (p.n != off) return fail("concat: n must equal the sum of in_cols", op);
+  a.out_cols = off;
+  out->kernel = f16 ? (vec ? K_concat_f16_vec : K_concat_f16_scalar) : (vec ? K_concat_f32_vec : K_concat_f32_scalar);
+  out->gx = cdiv((int64_t)p.m * (vec ? widest / ve : widest), 256);
+  out->gy = (uint32_t)op.n_inputs; out->gz = 1; out->block = 256;
+  out->args.concat = a;
+  return OPARA_OK;
+}
+
+}  // namespace
+
+int plan_op(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+  std::memset(out, 0, sizeof *out);
+  int rc;
+  switch (op.op_type) {
+    case OPARA_CONV2D: case OPARA_GEMM: case OPARA_BGEMM: rc = plan_igemm(op, in, out); break;
+    case OPARA_MAXPOOL: case OPARA_AVGPOOL: rc = plan_pool(op, in, out); break;
+    case OPARA_GAVGPOOL: rc = plan_gap(op, in, out); break;
+    case OPARA_LAYERNORM: case OPARA_SOFTMAX: rc = plan_row(op, in, out); break;
+    case OPARA_GELU: case OPARA_RELU: case OPARA_ADD: rc = plan_elt(op, in, out); break;
+    case OPARA_CONCAT: rc = plan_concat(op, in, out); break;
+    default: set_error("unknown operator type %d", op.op_type); return OPARA_EINVAL;
+  }
+  if (rc != OPARA_OK) return rc;
+  if (out->gx == 0 || out->gy == 0 || out->gz == 0 || out->gy > 65535u || out->gz > 65535u) {
+    set_error("operator type %d: launch grid out of range", op.op_type);
+    return OPARA_EUNSUPPORTED;
+  }
+  return OPARA_OK;
+}
+
+}  // namespace opara

@@ -1,0 +1,221 @@
+"""Marshalling between a workload description and the C ABI.
+
+Allocates device buffers through PyTorch (memory and streams are the only things
+PyTorch provides), converts logical tensors to the library's physical layouts
+([H][W][C] images, [N][K] GEMM weights, [C_out][kh][kw][C_in] convolution weights),
+fills opara_op_desc records and drives the library.  No operator arithmetic and no
+scheduling decision happens here.
+"""
+import ctypes as C
+import numpy as np
+from . import binding as B
+
+_IMAGE_TYPES = ("conv2d", "maxpool", "avgpool", "gavgpool")
+
+
+def _is_image(op):
+    return op.type in _IMAGE_TYPES or (op.type == "concat" and op.params.get("axis") == 0)
+
+
+def _hip():
+    import torch  # noqa: F401  (makes sure the HIP runtime PyTorch uses is the one loaded)
+    return C.CDLL("libamdhip64.so.7") if not hasattr(_hip, "lib") else _hip.lib
+
+
+class StreamSet:
+    """n distinct non-blocking HIP streams (PyTorch's own pool holds only 32 handles,
+    fewer than Alg. 1 may open), wrapped as torch ExternalStream objects."""
+
+    def __init__(self, n, device):
+        import torch
+        self.lib = C.CDLL("libamdhip64.so.7")
+        self.lib.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        self.lib.hipStreamDestroy.argtypes = [C.c_void_p]
+        self.handles = []
+        torch.cuda.set_device(device)
+        for _ in range(n):
+            h = C.c_void_p()
+            rc = self.lib.hipStreamCreateWithFlags(C.byref(h), 1)  # hipStreamNonBlocking
+            if rc != 0:
+                raise RuntimeError(f"hipStreamCreateWithFlags failed with {rc}")
+            self.handles.append(h.value)
+        self.torch_streams = [torch.cuda.ExternalStream(h, device=device) for h in self.handles]
+
+    def close(self):
+        for h in self.handles:
+            self.lib.hipStreamDestroy(C.c_void_p(h))
+        self.handles = []
+
+
+class Session:
+    """One workload bound to device buffers and a built DAG handle."""
+
+    def __init__(self, wl, device="cuda:0", demand_override=None, class_override=None):
+        self.wl = wl
+        self.device = device
+        self.dag = None
+        self.execs = []
+        self.streams = None
+        self._fake = 0x10000
+        self._keep = []
+        self.dtype_id = B.F32 if wl.dtype == "f32" else B.F16
+        self.ext_dev = [self._upload(self._to_physical_input(a)) for a in wl.ext_inputs]
+        self.out_dev = []
+        self.w_dev, self.b_dev = {}, {}
+        descs = []
+        for op in wl.ops:
+            d = B.OpDesc()
+            d.op_type = B.OP_TYPE_IDS[op.type]
+            d.op_class = B.CLASS_DEFAULT if class_override is None else class_override[op.id]
+            d.dtype = self.dtype_id
+            d.n_inputs = len(op.inputs)
+            for i, u in enumerate(op.inputs):
+                d.inputs[i] = u
+            if demand_override is not None:
+                d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs = demand_override[op.id]
+            self._fill_params(op, d.params)
+            if op.id in wl.weights:
+                w, b = wl.weights[op.id]["w"], wl.weights[op.id]["b"]
+                if op.type == "conv2d":
+                    wp = np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))
+                else:
+                    wp = np.ascontiguousarray(w.T)
+                self.w_dev[op.id] = self._upload(wp)
+                self.b_dev[op.id] = self._upload(b.astype(np.float32))
+                d.weight = self._ptr(self.w_dev[op.id])
+                d.bias = self._ptr(self.b_dev[op.id])
+            out = self._alloc(int(np.prod(op.out_shape)))
+            self.out_dev.append(out)
+            d.out = self._ptr(out)
+            descs.append(d)
+        self.descs = descs
+        self.dag = B.opara_build_dag(descs, [self._ptr(t) for t in self.ext_dev])
+
+    # ---- device memory (PyTorch) or fake addresses when there is no device
+    def _upload(self, arr):
+        if self.device is None:
+            return self._fake_ptr(arr.nbytes)
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(arr)).to(self.device)
+
+    def _alloc(self, numel):
+        if self.device is None:
+            return self._fake_ptr(numel * (4 if self.wl.dtype == "f32" else 2))
+        import torch
+        return torch.zeros(numel, dtype=torch.float32 if self.wl.dtype == "f32" else torch.float16,
+                           device=self.device)
+
+    def _fake_ptr(self, nbytes):
+        p = self._fake
+        self._fake += (nbytes + 255) // 256 * 256
+        return p
+
+    def _ptr(self, t):
+        return t if isinstance(t, int) else t.data_ptr()
+
+    @staticmethod
+    def _to_physical_input(a):
+        return np.ascontiguousarray(np.transpose(a, (1, 2, 0))) if a.ndim == 3 else a
+
+    def _fill_params(self, op, p):
+        q, t = op.params, op.type
+        if t in ("conv2d", "maxpool", "avgpool", "gavgpool"):
+            p.c_in, p.h_in, p.w_in = op.in_shapes[0]
+            p.c_out, p.h_out, p.w_out = op.out_shape
+            for k in ("kh", "kw", "sh", "sw", "ph", "pw"):
+                if k in q:
+                    setattr(p, k, q[k])
+            if q.get("relu"):
+                p.flags |= B.FLAG_RELU
+        elif t == "gemm":
+            p.m, p.n, p.k = q["m"], q["n"], q["k"]
+            if q.get("relu"):
+                p.flags |= B.FLAG_RELU
+        elif t == "bgemm":
+            h, s, d = q["heads"], q["seq"], q["dhead"]
+            p.batch, p.alpha = h, q["alpha"]
+            if q["mode"] == "qk":      # scores_h = alpha * Q_h . K_h^T
+                p.m, p.n, p.k = s, s, d
+                p.a_batch_stride, p.a_row_stride = d, h * d
+                p.b_batch_stride, p.b_row_stride = d, h * d
+                p.c_batch_stride, p.c_row_stride = s * s, s
+            else:                      # context_h = P_h . V_h, V read in place ([K][N])
+                p.m, p.n, p.k = s, d, s
+                p.a_batch_stride, p.a_row_stride = s * s, s
+                p.b_batch_stride, p.b_row_stride = d, h * d
+                p.c_batch_stride, p.c_row_stride = d, h * d
+                p.flags |= B.FLAG_B_KMAJOR
+        elif t == "concat":
+            if q["axis"] == 0:
+                p.m = op.out_shape[1] * op.out_shape[2]
+                cols = [s[0] for s in op.in_shapes]
+            else:
+                p.m = op.out_shape[0]
+                cols = [s[1] for s in op.in_shapes]
+            for i, c in enumerate(cols):
+                p.in_cols[i] = c
+            p.n = sum(cols)
+        else:                          # layernorm, softmax, gelu, relu, add
+            p.m, p.n = op.in_shapes[0]
+            p.eps = q.get("eps", 0.0)
+
+    # ---- the path
+    def schedule(self):
+        so, ns = B.opara_assign_streams(self.dag)
+        order = B.opara_order_launch(self.dag)
+        return so, ns, order, B.opara_sync_edges(self.dag)
+
+    def make_streams(self, n):
+        if self.streams is None or len(self.streams.handles) < n:
+            if self.streams is not None:
+                self.streams.close()
+            self.streams = StreamSet(n, self.device)
+        return self.streams
+
+    def capture(self, mode):
+        if mode == B.PARALLEL:
+            _, ns, _, _ = self.schedule()
+        else:
+            ns = 1
+        st = self.make_streams(max(ns, 1))
+        exe = B.opara_capture(self.dag, st.handles[:ns], mode)
+        self.execs.append(exe)
+        return exe
+
+    def replay(self, exe, sync=True):
+        import torch
+        st = self.make_streams(1)
+        B.opara_replay(exe, st.handles[0])
+        if sync:
+            st.torch_streams[0].synchronize()
+
+    def run_eager(self):
+        st = self.make_streams(1)
+        B.opara_run_eager(self.dag, st.handles[0])
+        st.torch_streams[0].synchronize()
+
+    def clear_outputs(self):
+        for t in self.out_dev:
+            t.zero_()
+        import torch
+        torch.cuda.synchronize()
+
+    def output(self, op_id):
+        """Operator output as a numpy array in the logical layout of the workload."""
+        op = self.wl.ops[op_id]
+        a = self.out_dev[op_id].cpu().numpy()
+        if _is_image(op):
+            c, h, w = op.out_shape
+            return np.ascontiguousarray(np.transpose(a.reshape(h, w, c), (2, 0, 1)))
+        return a.reshape(op.out_shape)
+
+    def close(self):
+        for e in self.execs:
+            B.opara_exec_destroy(e)
+        self.execs = []
+        if self.dag is not None:
+            B.opara_dag_destroy(self.dag)
+            self.dag = None
+        if self.streams is not None:
+            self.streams.close()
+            self.streams = None
