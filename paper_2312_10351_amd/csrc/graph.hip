@@ -40,13 +40,14 @@ void destroy_exec(opara_exec *e) {
 
 extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams, int32_t mode,
                              opara_exec **out) {
-  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL)) {
+  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_EXPLICIT)) {
     set_error("opara_capture: bad argument");
     return OPARA_EINVAL;
   }
   *out = nullptr;
   const int32_t n = g->n;
-  if (mode == OPARA_PARALLEL) {
+  const bool parallel = mode != OPARA_SEQUENTIAL;
+  if (parallel) {
     if (g->stream_of.empty() || g->order.empty()) {
       set_error("opara_capture: call opara_assign_streams and opara_order_launch first");
       return OPARA_ESTATE;
@@ -56,31 +57,70 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
       return OPARA_EINVAL;
     }
   }
-  const int32_t ns = mode == OPARA_PARALLEL ? g->n_streams : 1;
+  const int32_t ns = parallel ? g->n_streams : 1;
   for (int32_t s = 1; s < ns; ++s)
     for (int32_t r = 0; r < s; ++r)
       if (hip_streams[s] == hip_streams[r]) {
         set_error("opara_capture: streams %d and %d are the same handle", r, s);
         return OPARA_EINVAL;
       }
-  const std::vector<int32_t> &q = mode == OPARA_PARALLEL ? g->order : g->topo;
+  const std::vector<int32_t> &q = parallel ? g->order : g->topo;
   opara_exec *e = new (std::nothrow) opara_exec();
   if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
   hipStream_t origin = (hipStream_t)hip_streams[0];
   bool capturing = false;
+  int32_t n_roots = 0, n_sinks = 0;
+  for (int32_t v = 0; v < n; ++v) {
+    n_roots += (g->pred_off[v + 1] == g->pred_off[v]);
+    n_sinks += (g->succ_off[v + 1] == g->succ_off[v]);
+  }
+  // Stream capture serves DAGs with one root and one sink.  Any other DAG, or an
+  // explicit request, is built node by node with the very same dependencies: the
+  // previous operator of the same stream in launch-queue order plus every
+  // cross-stream predecessor, under one root and one leaf node without work.
+  if (mode == OPARA_PARALLEL_EXPLICIT || (mode == OPARA_PARALLEL && (n_roots > 1 || n_sinks > 1))) {
+    std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(ns, nullptr), deps;
+    hipGraphNode_t root = nullptr, leaf = nullptr;
+    HIP_TRY(hipGraphCreate(&e->graph, 0));
+    if (n_roots > 1) HIP_TRY(add_noop_node(e->graph, nullptr, 0, &root));
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = q[i], sv = g->stream_of[v];
+      deps.clear();
+      if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
+      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+        const int32_t u = g->pred[j];
+        if (g->stream_of[u] != sv) deps.push_back(node_of[u]);
+      }
+      if (deps.empty() && root) deps.push_back(root);
+      HIP_TRY(add_plan_node(e->graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
+      last_on_stream[sv] = node_of[v];
+    }
+    if (n_sinks > 1) {
+      deps.clear();
+      for (int32_t v = 0; v < n; ++v)
+        if (g->succ_off[v + 1] == g->succ_off[v]) deps.push_back(node_of[v]);
+      HIP_TRY(add_noop_node(e->graph, deps.data(), deps.size(), &leaf));
+    }
+    HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+    size_t nn = 0, ne = 0;
+    HIP_TRY(hipGraphGetNodes(e->graph, nullptr, &nn));
+    HIP_TRY(hipGraphGetEdges(e->graph, nullptr, nullptr, &ne));
+    e->n_nodes = (int32_t)nn;
+    e->n_edges = (int32_t)ne;
+    *out = e;
+    return OPARA_OK;
+  }
   {
-    // Event plan: one per producer with a consumer on another stream, one fork event,
-    // one join event per non-origin stream.
+    // Event plan: one per producer with a consumer on another stream, one join event
+    // per non-origin stream.
     std::vector<int32_t> ev_of(n, -1);
-    std::vector<uint8_t> entered(ns, 0);
     int32_t n_ev = 0;
-    if (mode == OPARA_PARALLEL)
+    if (parallel)
       for (int32_t v = 0; v < n; ++v)
         for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
           const int32_t u = g->pred[j];
           if (g->stream_of[u] != g->stream_of[v] && ev_of[u] < 0) ev_of[u] = n_ev++;
         }
-    const int32_t fork_ev = n_ev++;
     const int32_t join_ev0 = n_ev;
     n_ev += ns;
     e->events.reserve(n_ev);
@@ -89,19 +129,16 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
       HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
       e->events.push_back(ev);
     }
+    // A stream enters the capture when it first waits on an event recorded inside it:
+    // with a single root, the first operator of every other stream has cross-stream
+    // predecessors only, so its own waits bring the stream in.
     HIP_TRY(hipStreamBeginCapture(origin, hipStreamCaptureModeRelaxed));
     capturing = true;
-    entered[0] = 1;
-    if (ns > 1) HIP_TRY(hipEventRecord(e->events[fork_ev], origin));
     for (int32_t i = 0; i < n; ++i) {
       const int32_t v = q[i];
-      const int32_t sv = mode == OPARA_PARALLEL ? g->stream_of[v] : 0;
+      const int32_t sv = parallel ? g->stream_of[v] : 0;
       hipStream_t st = (hipStream_t)hip_streams[sv];
-      if (!entered[sv]) {   // first operator of this stream: fork it off the origin
-        HIP_TRY(hipStreamWaitEvent(st, e->events[fork_ev], 0));
-        entered[sv] = 1;
-      }
-      if (mode == OPARA_PARALLEL)
+      if (parallel)
         for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
           const int32_t u = g->pred[j];
           if (g->stream_of[u] != sv) HIP_TRY(hipStreamWaitEvent(st, e->events[ev_of[u]], 0));
@@ -110,12 +147,15 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
       if (ev_of[v] >= 0) HIP_TRY(hipEventRecord(e->events[ev_of[v]], st));
     }
     for (int32_t s = 1; s < ns; ++s) {   // join every stream back into the origin
-      if (!entered[s]) continue;
       HIP_TRY(hipEventRecord(e->events[join_ev0 + s], (hipStream_t)hip_streams[s]));
       HIP_TRY(hipStreamWaitEvent(origin, e->events[join_ev0 + s], 0));
     }
     capturing = false;
-    HIP_TRY(hipStreamEndCapture(origin, &e->graph));
+    {
+      hipGraph_t captured = nullptr;
+      HIP_TRY(hipStreamEndCapture(origin, &captured));   // on failure the runtime keeps ownership
+      e->graph = captured;
+    }
     HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
     size_t nn = 0, ne = 0;
     HIP_TRY(hipGraphGetNodes(e->graph, nullptr, &nn));
@@ -128,8 +168,7 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
 fail:
   if (capturing) {
     hipGraph_t partial = nullptr;
-    (void)hipStreamEndCapture(origin, &partial);
-    if (partial) (void)hipGraphDestroy(partial);
+    if (hipStreamEndCapture(origin, &partial) == hipSuccess && partial) (void)hipGraphDestroy(partial);
   }
   (void)hipGetLastError();
   destroy_exec(e);

@@ -551,7 +551,15 @@ KDEF(concat_f16_scalar, 256, ConcatArgs, (concat_body<half_t, 1>(a)))
 KDEF(concat_f32_vec, 256, ConcatArgs, (concat_body<float, 4>(a)))
 KDEF(concat_f32_scalar, 256, ConcatArgs, (concat_body<float, 1>(a)))
 
+// Kernel without work: a pure dependency node (common root / common leaf of a capture).
+extern "C" __global__ void opara_k_noop(int) {}
+
 namespace opara {
+
+hipError_t launch_noop(hipStream_t s) {
+  hipLaunchKernelGGL(opara_k_noop, dim3(1), dim3(64), 0, s, 0);
+  return hipGetLastError();
+}
 
 namespace {
 template <typename A> const A &arg_of(const KernelArgs &u);
@@ -576,6 +584,33 @@ hipError_t launch_plan(const KernelPlan &p, hipStream_t s) {
       return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+hipError_t add_plan_node(hipGraph_t graph, const KernelPlan &p, const hipGraphNode_t *deps, size_t n_deps,
+                         hipGraphNode_t *node) {
+  void *func = const_cast<void *>(kernel_symbol(p.kernel));
+  if (!func) return hipErrorInvalidValue;
+  KernelArgs args = p.args;              // every kernel takes one by-value record at offset 0
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = func;
+  np.gridDim = dim3(p.gx, p.gy, p.gz);
+  np.blockDim = dim3(p.block);
+  np.sharedMemBytes = 0;
+  np.kernelParams = kparams;
+  np.extra = nullptr;
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
+  int zero = 0;
+  void *kparams[1] = {&zero};
+  hipKernelNodeParams np = {};
+  np.func = (void *)opara_k_noop;
+  np.gridDim = dim3(1);
+  np.blockDim = dim3(64);
+  np.kernelParams = kparams;
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
 }
 
 const void *kernel_symbol(int id) {

@@ -173,7 +173,7 @@ class Session:
         return self.streams
 
     def capture(self, mode):
-        if mode == B.PARALLEL:
+        if mode != B.SEQUENTIAL:
             _, ns, _, _ = self.schedule()
         else:
             ns = 1

@@ -1,0 +1,194 @@
+"""Host-side tests of the C ABI (no GPU needed): the library loads and exports every
+declared symbol, rejects malformed graphs, and its scheduler agrees bit for bit with
+the oracle scheduler on the configs and on thousands of random tiny DAGs."""
+import ctypes as C
+import os
+import re
+import numpy as np
+import pytest
+from oracle import sched
+from paper_2312_10351_amd import binding as B
+from paper_2312_10351_amd.runtime import Session
+from workloads import (Builder, inception_block, googlenet_like, inception_v3_like, bert_base_like,
+                       random_small_dag)
+from util import LIMITS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "opara.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(opara_\w+)\s*\(", header))
+    assert {"opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_capture",
+            "opara_replay"} <= declared
+    lib = B.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in opara.h but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+def test_struct_layouts_match_header():
+    # sizes the C compiler gives the same records (natural alignment, no packing)
+    assert C.sizeof(B.OpParams) == 16 * 4 + 6 * 8 + 8 * 4 + 3 * 4 + 4
+    assert C.sizeof(B.Demand) == 32
+    assert C.sizeof(B.Limits) == 16
+
+
+def chain_descs(n, inputs):
+    descs = []
+    for v in range(n):
+        d = B.OpDesc()
+        d.op_type, d.op_class, d.dtype = B.ADD, B.CLASS_DEFAULT, B.F16
+        d.n_inputs = len(inputs[v])
+        for i, u in enumerate(inputs[v]):
+            d.inputs[i] = u
+        d.params.m, d.params.n = 4, 64
+        d.out = 0x10000 + 0x1000 * v
+        descs.append(d)
+    return descs
+
+
+def build_status(descs, ext=(0x1000,)):
+    try:
+        dag = B.opara_build_dag(descs, list(ext))
+    except B.OparaError as e:
+        return e.status, str(e)
+    B.opara_dag_destroy(dag)
+    return B.OK, ""
+
+
+def test_error_paths():
+    assert build_status(chain_descs(3, [[-1], [0], [1]]))[0] == B.OK
+    st, msg = build_status(chain_descs(3, [[2], [0], [1]]))
+    assert st == B.ECYCLE and "cycle" in msg
+    assert build_status(chain_descs(2, [[-1], [1]]))[0] == B.ECYCLE          # self-loop
+    assert build_status(chain_descs(2, [[-1], [5]]))[0] == B.EINVAL          # producer out of range
+    assert build_status(chain_descs(2, [[-2], [0]]))[0] == B.EINVAL          # external slot out of range
+    assert build_status([])[0] == B.EINVAL                                   # n_ops == 0
+    d = chain_descs(1, [[-1]]); d[0].n_inputs = 0
+    assert build_status(d)[0] == B.EINVAL
+    d = chain_descs(1, [[-1]]); d[0].out = None
+    assert build_status(d)[0] == B.EINVAL
+    d = chain_descs(1, [[-1]]); d[0].op_type = 99
+    assert build_status(d)[0] == B.EINVAL
+    d = chain_descs(1, [[-1]]); d[0].params.m = 0
+    assert build_status(d)[0] == B.EINVAL
+    lib = B.load()
+    assert lib.opara_build_dag(None, 1, None, 0, None, None) == B.EINVAL
+    assert lib.opara_assign_streams(None, None, None) == B.EINVAL
+    assert lib.opara_replay(None, None) == B.EINVAL
+    # calls out of order
+    dag = B.opara_build_dag(chain_descs(2, [[-1], [0]]), [0x1000])
+    with pytest.raises(B.OparaError) as e:
+        B.opara_sync_edges(dag)
+    assert e.value.status == B.ESTATE
+    handles = (C.c_void_p * 1)(0x1)
+    out = C.c_void_p()
+    assert lib.opara_capture(dag, handles, 1, B.PARALLEL, C.byref(out)) == B.ESTATE
+    assert b"opara_assign_streams" in lib.opara_last_error()
+    B.opara_dag_destroy(dag)
+
+
+def test_bad_shapes_rejected():
+    b = Builder("bad", "f16")
+    x = b.ext((8, 6, 6))
+    b.conv(x, 8, 3, pad=1)
+    wl = b.build(0)
+    wl.ops[0].out_shape = (8, 5, 6)          # does not match the floor formula
+    with pytest.raises(B.OparaError) as e:
+        Session(wl, device=None)
+    assert e.value.status == B.EINVAL
+
+
+def oracle_schedule(wl, dem):
+    preds = sched.dedup_preds([o.inputs for o in wl.ops])
+    so, ns = sched.assign_streams(preds)
+    scal = [sched.demand_scalar((d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs), LIMITS) for d in dem]
+    q = sched.order_launch(preds, [d.op_class for d in dem], scal)
+    return preds, so, ns, q, sched.sync_edges(preds, so), scal
+
+
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like])
+def test_scheduler_matches_oracle_on_configs(builder):
+    wl = builder()
+    s = Session(wl, device=None)
+    try:
+        so, ns, q, syncs = s.schedule()
+        dem = B.opara_get_demands(s.dag)
+        preds, oso, ons, oq, osync, scal = oracle_schedule(wl, dem)
+        assert (so, ns) == (oso, ons)
+        assert [d.demand for d in dem] == scal
+        assert q == oq
+        assert syncs == osync
+        assert sched.check_schedule(preds, so, q, syncs)
+        from oracle.executor import kahn_order
+        assert B.opara_topo_order(s.dag) == kahn_order(len(wl.ops), wl.edges())
+        # operator table: contractions are compute-intensive, the rest memory-intensive
+        for op, d in zip(wl.ops, dem):
+            assert d.op_class == (B.COMP if op.type in ("conv2d", "gemm", "bgemm") else B.MEM)
+            name, vg, lds = B.opara_kernel_info(d.kernel_id)
+            assert (d.vgprs, d.lds_bytes) == (vg, lds) and d.grid_blocks > 0
+    finally:
+        s.close()
+
+
+def test_scheduler_matches_oracle_on_random_dags():
+    """>= 10^4 seeded random DAGs with n <= 12 and caller-supplied demand records."""
+    rng = np.random.default_rng(20231210)
+    for trial in range(10000):
+        n = int(rng.integers(1, 13))
+        inputs = []
+        for v in range(n):
+            if v == 0 or rng.random() < 0.25:
+                inputs.append([-1])
+            else:
+                k = int(rng.integers(1, 4))
+                inputs.append([int(u) for u in rng.integers(0, v, size=k)])   # repeats allowed
+        descs = chain_descs(n, inputs)
+        for d in descs:
+            d.op_class = int(rng.integers(-1, 2))
+            d.grid_blocks = int(rng.integers(1, 5))
+            d.block_threads = int(rng.choice([64, 128, 256]))
+            d.lds_bytes = int(rng.choice([0, 1024, 65536]))
+            d.vgprs = int(rng.choice([16, 64, 128]))
+        dag = B.opara_build_dag(descs, [0x1000])
+        so, ns = B.opara_assign_streams(dag)
+        q = B.opara_order_launch(dag)
+        syncs = B.opara_sync_edges(dag)
+        dem = B.opara_get_demands(dag)
+        B.opara_dag_destroy(dag)
+        preds = sched.dedup_preds(inputs)
+        oso, ons = sched.assign_streams(preds)
+        cls = [d.op_class for d in dem]
+        for d, desc in zip(dem, descs):
+            assert d.op_class == (desc.op_class if desc.op_class >= 0 else B.MEM)   # ADD is memory-intensive
+        scal = [sched.demand_scalar((d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs), LIMITS) for d in descs]
+        assert [d.demand for d in dem] == scal
+        assert (so, ns) == (oso, ons), (trial, inputs)
+        assert q == sched.order_launch(preds, cls, scal), (trial, inputs)
+        assert syncs == sched.sync_edges(preds, oso)
+
+
+def test_random_small_workloads_schedule():
+    for seed in range(5):
+        wl = random_small_dag(seed, n_ops=60)
+        s = Session(wl, device=None)
+        so, ns, q, syncs = s.schedule()
+        dem = B.opara_get_demands(s.dag)
+        preds, oso, ons, oq, osync, _ = oracle_schedule(wl, dem)
+        assert (so, ns, q, syncs) == (oso, ons, oq, osync)
+        s.close()
+
+
+def test_kernel_table():
+    n = B.opara_kernel_count()
+    names = [B.opara_kernel_info(i)[0] for i in range(n)]
+    assert len(set(names)) == n and "igemm_f16_t64x64" in names
+    for i in range(n):
+        name, vg, lds = B.opara_kernel_info(i)
+        assert 0 < vg <= 512 and lds <= 65536
+        if name.startswith("igemm"):
+            assert lds > 0
+    with pytest.raises(B.OparaError):
+        B.opara_kernel_info(n)

@@ -4,7 +4,9 @@ Operators are emitted in trace order (branch by branch inside a block), which is
 topological order.  Tensors come from numpy Generator(PCG64(seed)); draw order is
 external inputs first (slot order), then per operator in id order: weight (bias is
 all zeros unless `random_bias`).  Values are drawn in fp32 and rounded once to the
-workload dtype.
+workload dtype.  `he_init` replaces the fixed weight deviation by sqrt(2/fan_in), which
+keeps activations of the deep CNNs at order one (a test aid: with the configs' fixed
+deviation of 0.02 the deep fp16 networks decay into the subnormal range).
 """
 import numpy as np
 from .dag import Op, Workload
@@ -14,7 +16,7 @@ CONFIG_NAMES = ("inception_block", "googlenet_like", "inception_v3_like",
                 "bert_base_like", "random_wide_dag")
 
 
-class _B:
+class Builder:
     """Tiny DAG builder: appends operators, tracks output shapes."""
 
     def __init__(self, name, dtype):
@@ -71,7 +73,7 @@ class _B:
     def rowwise(self, kind, xs, r, c, params=None, name=""):
         return self.add(kind, xs, [(r, c)] * len(xs), (r, c), params or {}, name)
 
-    def build(self, seed, random_bias=False, w_std=0.02):
+    def build(self, seed, random_bias=False, w_std=0.02, he_init=False):
         rng = np.random.Generator(np.random.PCG64(seed))
         npdt = np.float32 if self.dtype == "f32" else np.float16
         ext = [rng.standard_normal(s, dtype=np.float32).astype(npdt) for s in self.ext_shapes]
@@ -85,7 +87,8 @@ class _B:
             else:
                 continue
             w = rng.standard_normal(wshape, dtype=np.float32)
-            w *= np.float32(w_std)
+            fan_in = int(np.prod(wshape[1:])) if op.type == "conv2d" else wshape[0]
+            w *= np.float32(np.sqrt(2.0 / fan_in) if he_init else w_std)
             if random_bias:
                 b = rng.standard_normal(nb, dtype=np.float32) * np.float32(0.1)
             else:
@@ -107,7 +110,7 @@ def _inception(b, x, c1, c3r, c3, c5r, c5, pp, tag):
 
 
 def inception_block(seed=BASE_SEED + 0, dtype="f32", random_bias=False):
-    b = _B("inception_block", dtype)
+    b = Builder("inception_block", dtype)
     x = b.ext((64, 28, 28))
     _inception(b, x, 16, 24, 32, 8, 16, 16, "blk")
     return b.build(seed, random_bias)
@@ -122,8 +125,8 @@ GOOGLENET_WIDTHS = {  # (1x1, 3x3-reduce, 3x3, 5x5-reduce, 5x5, pool-proj)
 }
 
 
-def googlenet_like(seed=BASE_SEED + 1, dtype="f16"):
-    b = _B("googlenet_like", dtype)
+def googlenet_like(seed=BASE_SEED + 1, dtype="f16", he_init=False):
+    b = Builder("googlenet_like", dtype)
     x = b.ext((3, 224, 224))
     x = b.conv(x, 64, 7, stride=2, pad=3, name="stem.conv7x7")
     x = b.pool("maxpool", x, 3, 2, 1, name="stem.pool1")
@@ -140,11 +143,11 @@ def googlenet_like(seed=BASE_SEED + 1, dtype="f16"):
         x = _inception(b, x, *GOOGLENET_WIDTHS[tag], tag)
     x = b.gavgpool(x, name="gap")
     b.gemm(x, 1, 1024, 1000, name="fc")
-    return b.build(seed)
+    return b.build(seed, he_init=he_init)
 
 
-def inception_v3_like(seed=BASE_SEED + 2, dtype="f16"):
-    b = _B("inception_v3_like", dtype)
+def inception_v3_like(seed=BASE_SEED + 2, dtype="f16", he_init=False):
+    b = Builder("inception_v3_like", dtype)
     x = b.ext((3, 299, 299))
     x = b.conv(x, 32, 3, stride=2, name="stem.1")
     x = b.conv(x, 32, 3, name="stem.2")
@@ -209,12 +212,12 @@ def inception_v3_like(seed=BASE_SEED + 2, dtype="f16"):
         x = b.concat_c([b1, b2a, b2b, b3a, b3b, b4], name=f"{t}.cat")
     x = b.gavgpool(x, name="gap")
     b.gemm(x, 1, 2048, 1000, name="fc")
-    return b.build(seed)
+    return b.build(seed, he_init=he_init)
 
 
 def bert_base_like(seed=BASE_SEED + 3, dtype="f16", layers=12, seq=128, hidden=768,
                    heads=12, ffn=3072):
-    b = _B("bert_base_like", dtype)
+    b = Builder("bert_base_like", dtype)
     d = hidden // heads
     x = b.ext((seq, hidden))
     for l in range(layers):
@@ -255,7 +258,7 @@ def _random_dag(name, seed, dtype, n_ops, max_width, gemm_units, mem_elems, col_
     mem_elems=(lo,hi): element count range of memory-bound tensors; col_units: their
     column count = unit*U{lo..hi}."""
     rs = np.random.Generator(np.random.PCG64([seed, 7]))   # structure stream
-    b = _B(name, dtype)
+    b = Builder(name, dtype)
     levels = []
     while len(b.ops) < n_ops:
         width = min(int(rs.integers(1, max_width + 1)), n_ops - len(b.ops))
