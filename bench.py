@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark: batch-1 DAG latency of the operator-parallel graph replay on one MI355X.
+
+A step is one replay of the whole captured DAG (stream plan + launch order + single
+hipGraph) with inputs and weights resident in HBM.  The headline workload is the
+GoogLeNet-like fp16 DAG; the other configs are reported beside it.  One JSON line on
+stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def percentile(a, q):
+    return float(np.percentile(np.asarray(a), q))
+
+
+def time_replays(session, exe, steps, warmup):
+    """Per-replay latency (events on the launch stream, host sync after each) and
+    back-to-back time per replay (no host sync between replays)."""
+    import torch
+    from paper_2312_10351_amd import binding as B
+    st = session.make_streams(1)
+    h, ts = st.handles[0], st.torch_streams[0]
+    for _ in range(warmup):
+        B.opara_replay(exe, h)
+    ts.synchronize()
+    lat = []
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    for _ in range(steps):
+        e0.record(ts)
+        B.opara_replay(exe, h)
+        e1.record(ts)
+        ts.synchronize()
+        lat.append(e0.elapsed_time(e1) * 1e3)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(ts)
+    for _ in range(steps):
+        B.opara_replay(exe, h)
+    e1.record(ts)
+    ts.synchronize()
+    wall = time.perf_counter() - t0
+    return dict(median_us=percentile(lat, 50), mean_us=float(np.mean(lat)), p99_us=percentile(lat, 99),
+                min_us=float(np.min(lat)), back_to_back_us=e0.elapsed_time(e1) * 1e3 / steps,
+                wall_us_per_replay=wall * 1e6 / steps)
+
+
+def isolated_op_times(session, reps=20):
+    """Average duration of each operator's kernel launched alone `reps` times in a row
+    on one stream, bracketed by events on that stream (microseconds)."""
+    import torch
+    from paper_2312_10351_amd import binding as B
+    st = session.make_streams(1)
+    h, ts = st.handles[0], st.torch_streams[0]
+    out = []
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    for op in session.wl.ops:
+        for _ in range(3):
+            B.opara_launch_op(session.dag, op.id, h)
+        e0.record(ts)
+        for _ in range(reps):
+            B.opara_launch_op(session.dag, op.id, h)
+        e1.record(ts)
+        ts.synchronize()
+        out.append(e0.elapsed_time(e1) * 1e3 / reps)
+    return out
+
+
+def bench_config(index, steps, warmup, with_kernels):
+    from paper_2312_10351_amd import binding as B
+    from paper_2312_10351_amd.runtime import Session
+    from paper_2312_10351_amd.roofline import dag_roofline, MFMA_FLOPS, HBM_BYTES_PER_S
+    from workloads import build_config
+    wl = build_config(index)
+    s = Session(wl)
+    try:
+        t0 = time.perf_counter()
+        so, ns = B.opara_assign_streams(s.dag)
+        t1 = time.perf_counter()
+        order = B.opara_order_launch(s.dag)
+        t2 = time.perf_counter()
+        syncs = B.opara_sync_edges(s.dag)
+        t3 = time.perf_counter()
+        par = s.capture(B.PARALLEL)
+        t4 = time.perf_counter()
+        seq = s.capture(B.SEQUENTIAL)
+        r_par = time_replays(s, par, steps, warmup)
+        r_seq = time_replays(s, seq, steps, warmup)
+        roof = dag_roofline(wl)
+        res = dict(workload=wl.name, dtype=wl.dtype, n_ops=len(wl.ops), n_streams=ns, n_sync_edges=len(syncs),
+                   graph_nodes_edges=B.opara_exec_info(par),
+                   assign_streams_ms=(t1 - t0) * 1e3, order_launch_ms=(t2 - t1) * 1e3, capture_ms=(t4 - t3) * 1e3,
+                   parallel=r_par, sequential=r_seq,
+                   speedup_vs_sequential=r_seq["median_us"] / r_par["median_us"],
+                   dag_flops=roof["flops"], dag_bytes=roof["bytes"],
+                   roofline_us=dict(flops=roof["t_flops_us"], bytes=roof["t_bytes_us"], critical_path=roof["t_cp_us"],
+                                    bound=roof["t_roof_us"]),
+                   roofline_fraction=roof["t_roof_us"] / r_par["median_us"])
+        kern = None
+        if with_kernels:
+            t_iso = isolated_op_times(s)
+            dem = B.opara_get_demands(s.dag)
+            by = {}
+            for op, d, t in zip(wl.ops, dem, t_iso):
+                name = B.opara_kernel_info(d.kernel_id)[0]
+                f, b = roof["per_op"][op.id]
+                e = by.setdefault(name, dict(launches=0, time_us=0.0, flops=0, bytes=0))
+                e["launches"] += 1; e["time_us"] += t; e["flops"] += f; e["bytes"] += b
+            dom = max(by, key=lambda k: by[k]["time_us"])
+            e = by[dom]
+            if dom.startswith("igemm") or dom.startswith("gemv"):
+                peak = MFMA_FLOPS[wl.dtype] / 1e12
+                ach = e["flops"] / (e["time_us"] * 1e-6) / 1e12
+                kern = dict(kernel=dom, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                            traffic=None)
+            else:
+                peak = HBM_BYTES_PER_S / 1e9
+                ach = e["bytes"] / (e["time_us"] * 1e-6) / 1e9
+                kern = dict(kernel=dom, bound="hbm", achieved=ach, peak=peak, unit="GB/s", frac=ach / peak,
+                            traffic=None)
+            kern.update(launches_per_step=e["launches"], avg_launch_us=e["time_us"] / e["launches"],
+                        flops_per_launch=e["flops"] / e["launches"], bytes_per_launch=e["bytes"] / e["launches"])
+            res["sum_isolated_us"] = float(sum(t_iso))
+            finish = [0.0] * len(wl.ops)
+            for op in wl.ops:
+                finish[op.id] = max([finish[u] for u in op.inputs if u >= 0], default=0.0) + t_iso[op.id]
+            res["critical_path_isolated_us"] = float(max(finish))
+            res["kernels"] = {k: dict(launches=v["launches"], avg_us=v["time_us"] / v["launches"]) for k, v in by.items()}
+        return res, kern
+    finally:
+        s.close()
+
+
+def cpu_baseline(budget_s=12.0):
+    """The oracle executor, as it stands, on the host cores: full passes over the
+    headline DAG until about `budget_s` seconds are spent."""
+    from oracle import executor
+    from workloads import build_config
+    wl = build_config(1)
+    sink = wl.sinks()
+    executor.run_dag(wl, keep=sink)
+    times = []
+    t_end = time.perf_counter() + budget_s
+    while time.perf_counter() < t_end or len(times) < 3:
+        t0 = time.perf_counter()
+        executor.run_dag(wl, keep=sink)
+        times.append(time.perf_counter() - t0)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=percentile(times, 50) * 1e6, unit="us", cores=int(threads), kind="oracle",
+                sample=f"{len(times)} full passes of the googlenet_like DAG (numpy fp64, all 81 operators), median")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--configs", type=str, default="0,2,3,4", help="extra configs reported beside the headline one")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this path runs on ONE GPU (a batch-1 DAG is not sharded); use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    head, kern = bench_config(1, a.steps, a.warmup, with_kernels=True)
+    others = []
+    for idx in [int(x) for x in a.configs.split(",") if x != ""]:
+        r, _ = bench_config(idx, max(100, a.steps // 4), a.warmup, with_kernels=False)
+        others.append(r)
+    line = {
+        "metric": "batch1_dag_latency_us", "value": head["parallel"]["median_us"], "unit": "us",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head["parallel"]["mean_us"] / 1e3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "googlenet_like fp16 batch 1, 1x3x224x224, 81 operators (configs[1])",
+                   "mode": "multi-stream hipGraph replay (Alg. 1 streams, Alg. 2 launch order)"},
+        "throughput_inferences_per_s": 1e6 / head["parallel"]["back_to_back_us"],
+        "speedup_vs_sequential_hipgraph": head["speedup_vs_sequential"],
+        "dag_roofline_fraction": head["roofline_fraction"],
+        "roofline": kern,
+        "headline": head,
+        "other_configs": others,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -187,9 +187,9 @@ int32_t opara_num_ops(const opara_dag *g);
  * A DAG with several roots or several sinks, and any DAG under
  * OPARA_PARALLEL_EXPLICIT, is instead assembled node by node with exactly the
  * dependencies the capture would record (previous operator of the same stream in
- * launch-queue order + every cross-stream predecessor), under one root / one leaf node
- * without work where there are several roots / sinks; the streams are then only
- * checked, not used.
+ * launch-queue order + every cross-stream predecessor), plus one trailing node without
+ * work that joins the sinks when there are several; the streams are then only checked,
+ * not used.
  * OPARA_SEQUENTIAL captures the same kernels with the same launch shapes on
  * hip_streams[0] alone in default topological order (the baseline: paper Sec. 5.1,
  * default sequential graph).

@@ -77,12 +77,12 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
   // Stream capture serves DAGs with one root and one sink.  Any other DAG, or an
   // explicit request, is built node by node with the very same dependencies: the
   // previous operator of the same stream in launch-queue order plus every
-  // cross-stream predecessor, under one root and one leaf node without work.
+  // cross-stream predecessor, closed by one leaf node without work if there are several
+  // sinks.
   if (mode == OPARA_PARALLEL_EXPLICIT || (mode == OPARA_PARALLEL && (n_roots > 1 || n_sinks > 1))) {
     std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(ns, nullptr), deps;
-    hipGraphNode_t root = nullptr, leaf = nullptr;
+    hipGraphNode_t leaf = nullptr;
     HIP_TRY(hipGraphCreate(&e->graph, 0));
-    if (n_roots > 1) HIP_TRY(add_noop_node(e->graph, nullptr, 0, &root));
     for (int32_t i = 0; i < n; ++i) {
       const int32_t v = q[i], sv = g->stream_of[v];
       deps.clear();
@@ -91,7 +91,6 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
         const int32_t u = g->pred[j];
         if (g->stream_of[u] != sv) deps.push_back(node_of[u]);
       }
-      if (deps.empty() && root) deps.push_back(root);
       HIP_TRY(add_plan_node(e->graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
       last_on_stream[sv] = node_of[v];
     }

@@ -64,11 +64,15 @@ struct ConcatArgs {
 #define OPARA_KERNEL_LIST(X)            \
   X(igemm_f16_t128x128, IgemmArgs)      \
   X(igemm_f16_t64x64, IgemmArgs)        \
-  X(igemm_f16_t32x32, IgemmArgs)        \
+  X(igemm_f16_direct4, IgemmArgs)       \
+  X(igemm_f16_direct8, IgemmArgs)       \
+  X(igemm_f16_direct16, IgemmArgs)      \
   X(igemm_f16_t64x64_scalar, IgemmArgs) \
   X(igemm_f32_t128x128, IgemmArgs)      \
   X(igemm_f32_t64x64, IgemmArgs)        \
-  X(igemm_f32_t32x32, IgemmArgs)        \
+  X(igemm_f32_direct4, IgemmArgs)       \
+  X(igemm_f32_direct8, IgemmArgs)       \
+  X(igemm_f32_direct16, IgemmArgs)      \
   X(igemm_f32_t64x64_scalar, IgemmArgs) \
   X(gemv_f16, IgemmArgs)                \
   X(gemv_f32, IgemmArgs)                \
@@ -127,7 +131,7 @@ struct KernelPlan {
 struct IgemmTile { int bn, bm, threads; };
 constexpr IgemmTile kTile128{128, 128, 256};
 constexpr IgemmTile kTile64{64, 64, 256};
-constexpr IgemmTile kTile32{32, 32, 64};
+constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)
 constexpr int kRowGroupBlock = 256;   // block variant

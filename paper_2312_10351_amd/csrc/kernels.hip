@@ -249,6 +249,158 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Latency-oriented implicit GEMM for small problems (batch-1 convolutions, skinny
+// GEMMs): a workgroup owns a 32 x 32 output tile and its WAVES wavefronts split K
+// between them.  Every lane fetches its MFMA fragments straight from global memory
+// (32 contiguous bytes per row and lane group, so four lane groups consume a whole
+// 128-byte line), two 64-byte-deep K steps in flight at a time, no LDS and no
+// barrier inside the K loop.  Partial tiles meet in LDS once, at the end, where 256
+// threads apply the epilogue and write 8/16-byte pieces of output rows.
+// ---------------------------------------------------------------------------------
+struct KPos { int ci, s, r; };
+
+__device__ __forceinline__ void kpos_advance(KPos &p, int delta, int Cin, int kw) {
+  p.ci += delta;
+  while (p.ci >= Cin) {
+    p.ci -= Cin;
+    if (++p.s == kw) { p.s = 0; ++p.r; }
+  }
+}
+
+template <typename T, int WAVES>
+__device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
+  typedef typename Vec16<T>::type V;
+  typedef typename Vec16<T>::quad Q;
+  constexpr int VE = Vec16<T>::N;
+  constexpr int DS = 8 * VE;               // K elements per step: 4 lane groups x 2 chunks
+  constexpr int U = 2;                     // steps in flight
+  constexpr int PITCH = 36;                // floats per pixel row of a partial tile in LDS
+  __shared__ __attribute__((aligned(16))) float part[WAVES][32][PITCH];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int grp = lane >> 4, r16 = lane & 15;
+  const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+
+  const int nds = (a.K + DS - 1) / DS;
+  const int per_wave = (nds + WAVES - 1) / WAVES;
+  const int ds_begin = wave * per_wave;
+  const int ds_end = min(nds, ds_begin + per_wave);
+
+  const T *wrow[2];
+  bool wok[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int n = n0 + i * 16 + r16;
+    wok[i] = n < a.N;
+    wrow[i] = w + (int64_t)(wok[i] ? n : 0) * a.ldb;
+  }
+  const T *xrow[2];
+  bool xok[2];
+  int ih0[2], iw0[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int m = m0 + j * 16 + r16;
+    xok[j] = m < a.M;
+    const int mm = xok[j] ? m : 0;
+    xrow[j] = x + (int64_t)mm * a.lda;
+    const int oh = mm / a.Wo, ow = mm - oh * a.Wo;      // only meaningful when gathering
+    ih0[j] = oh * a.sh - a.ph;
+    iw0[j] = ow * a.sw - a.pw;
+  }
+  KPos pos = {0, 0, 0};
+  if (a.gather && ds_begin < ds_end) {
+    const int k = ds_begin * DS + grp * 2 * VE;
+    pos.ci = k % a.Cin;
+    const int rs = k / a.Cin;
+    pos.s = rs % a.kw;
+    pos.r = rs / a.kw;
+  }
+
+  floatx4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const V vzero = {};
+
+  for (int ds = ds_begin; ds < ds_end; ds += U) {
+    V wa[U][2][2], xb[U][2][2];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool live = ds + u < ds_end;
+      KPos pc = pos;                       // position of chunk 0 of this step
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int k = (ds + u) * DS + grp * 2 * VE + c * VE;
+        const bool kok = live && k < a.K;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wa[u][i][c] = (kok && wok[i]) ? *(const V *)(wrow[i] + k) : vzero;
+        if (!a.gather) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) xb[u][j][c] = (kok && xok[j]) ? *(const V *)(xrow[j] + k) : vzero;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int ih = ih0[j] + pc.r, iw = iw0[j] + pc.s;
+            const bool ok = kok && xok[j] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            xb[u][j][c] = ok ? *(const V *)(x + ((int64_t)ih * a.W + iw) * a.Cin + pc.ci) : vzero;
+          }
+          if (c == 0) kpos_advance(pc, VE, a.Cin, a.kw);
+        }
+      }
+      if (a.gather) kpos_advance(pos, DS, a.Cin, a.kw);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = mma16<T>(wa[u][i][c], xb[u][j][c], acc[i][j]);
+  }
+
+  // ---- meet in LDS: lane holds channels n = i*16 + grp*4 + e of pixel m = j*16 + r16
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) *(floatx4 *)&part[wave][j * 16 + r16][i * 16 + grp * 4] = acc[i][j];
+  __syncthreads();
+  if (t < 256) {
+    const int pm = t >> 3, pn = (t & 7) * 4;
+    floatx4 sum = *(const floatx4 *)&part[0][pm][pn];
+#pragma unroll
+    for (int q = 1; q < WAVES; ++q) sum += *(const floatx4 *)&part[q][pm][pn];
+    const int m = m0 + pm, n = n0 + pn;
+    if (m < a.M && n < a.N) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float r = sum[e] * a.alpha;
+        if (n + e < a.N) {
+          if (a.bias) r += a.bias[n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
+        }
+        if (a.relu) r = fmaxf(r, 0.f);
+        v[e] = r;
+      }
+      T *dst = y + (int64_t)m * a.ldy + n;
+      if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+        Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+        *(Q *)dst = q4;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < a.N) dst[e] = (T)v[e];
+      }
+    }
+  }
+}
+
 // Matrix-vector shaped GEMM (M <= kGemvMaxM rows): one wavefront per output column,
 // 16-byte loads along K, shuffle reduction.  Weight-bandwidth bound by construction.
 template <typename T>
@@ -299,23 +451,43 @@ __device__ __forceinline__ void pool_body(const PoolArgs &a) {
   const int cc = (int)(item % cch);
   const int pix = (int)(item / cch);
   const int ow = pix % a.Wo, oh = pix / a.Wo;
-  const T *__restrict__ x = (const T *)a.x;
+  const T *__restrict__ x = (const T *)a.x + cc * VE;
+  const float fill = a.is_avg ? 0.f : -INFINITY;
   float acc[VE];
 #pragma unroll
-  for (int e = 0; e < VE; ++e) acc[e] = a.is_avg ? 0.f : -INFINITY;
-  for (int i = 0; i < a.kh; ++i) {
-    const int ih = oh * a.sh - a.ph + i;
-    if ((unsigned)ih >= (unsigned)a.H) continue;
-    for (int j = 0; j < a.kw; ++j) {
-      const int iw = ow * a.sw - a.pw + j;
-      if ((unsigned)iw >= (unsigned)a.W) continue;
-      const T *src = x + ((int64_t)ih * a.W + iw) * a.C + cc * VE;
-      T v[VE];
-      if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
-      else v[0] = src[0];
+  for (int e = 0; e < VE; ++e) acc[e] = fill;
+  auto fetch = [&](int ih, int iw, T *v) {
+    const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+    const T *src = x + ((int64_t)(ok ? ih : 0) * a.W + (ok ? iw : 0)) * a.C;
+    if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
+    else v[0] = src[0];
+    return ok;
+  };
+  auto fold = [&](bool ok, const T *v) {
 #pragma unroll
-      for (int e = 0; e < VE; ++e) acc[e] = a.is_avg ? acc[e] + (float)v[e] : fmaxf(acc[e], (float)v[e]);
+    for (int e = 0; e < VE; ++e) {
+      const float f = ok ? (float)v[e] : fill;
+      acc[e] = a.is_avg ? acc[e] + f : fmaxf(acc[e], f);
     }
+  };
+  const int ih0 = oh * a.sh - a.ph, iw0 = ow * a.sw - a.pw;
+  if (a.kh == 3 && a.kw == 3) {
+    // all nine taps in flight before the first use
+    T v[9][VE];
+    bool ok[9];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int j = 0; j < 3; ++j) ok[i * 3 + j] = fetch(ih0 + i, iw0 + j, v[i * 3 + j]);
+#pragma unroll
+    for (int q = 0; q < 9; ++q) fold(ok[q], v[q]);
+  } else {
+    for (int i = 0; i < a.kh; ++i)
+      for (int j = 0; j < a.kw; ++j) {
+        T v[VE];
+        const bool ok = fetch(ih0 + i, iw0 + j, v);
+        fold(ok, v);
+      }
   }
   const float scale = a.is_avg ? 1.0f / (float)(a.kh * a.kw) : 1.0f;
   T o[VE];
@@ -326,14 +498,28 @@ __device__ __forceinline__ void pool_body(const PoolArgs &a) {
   else dst[0] = o[0];
 }
 
+// Global average pool over [HW][C]: 256 threads = 64 channels x 4 pixel slices; each
+// thread sums its slice with independent loads, slices meet in LDS.
 template <typename T>
 __device__ __forceinline__ void gap_body(const GapArgs &a) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= a.C) return;
+  __shared__ float part[4][64];
+  const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   const T *__restrict__ x = (const T *)a.x;
   float s = 0.f;
-  for (int p = 0; p < a.HW; ++p) s += (float)x[(int64_t)p * a.C + c];
-  ((T *)a.y)[c] = (T)(s / (float)a.HW);
+  if (c < a.C) {
+    int p = slice;
+    for (; p + 12 < a.HW; p += 16) {
+      const float v0 = (float)x[(int64_t)p * a.C + c], v1 = (float)x[(int64_t)(p + 4) * a.C + c];
+      const float v2 = (float)x[(int64_t)(p + 8) * a.C + c], v3 = (float)x[(int64_t)(p + 12) * a.C + c];
+      s += (v0 + v1) + (v2 + v3);
+    }
+    for (; p < a.HW; p += 4) s += (float)x[(int64_t)p * a.C + c];
+  }
+  part[slice][cl] = s;
+  __syncthreads();
+  if (slice == 0 && c < a.C)
+    ((T *)a.y)[c] = (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW);
 }
 
 // ---------------------------------------------------------------------------------
@@ -516,11 +702,15 @@ using namespace opara;
 
 KDEF(igemm_f16_t128x128, 256, IgemmArgs, (igemm_body<half_t, 128, 128, 2, 2, true>(a)))
 KDEF(igemm_f16_t64x64, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true>(a)))
-KDEF(igemm_f16_t32x32, 64, IgemmArgs, (igemm_body<half_t, 32, 32, 1, 1, true>(a)))
+KDEF(igemm_f16_direct4, 256, IgemmArgs, (igemm_direct_body<half_t, 4>(a)))
+KDEF(igemm_f16_direct8, 512, IgemmArgs, (igemm_direct_body<half_t, 8>(a)))
+KDEF(igemm_f16_direct16, 1024, IgemmArgs, (igemm_direct_body<half_t, 16>(a)))
 KDEF(igemm_f16_t64x64_scalar, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false>(a)))
 KDEF(igemm_f32_t128x128, 256, IgemmArgs, (igemm_body<float, 128, 128, 2, 2, true>(a)))
 KDEF(igemm_f32_t64x64, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true>(a)))
-KDEF(igemm_f32_t32x32, 64, IgemmArgs, (igemm_body<float, 32, 32, 1, 1, true>(a)))
+KDEF(igemm_f32_direct4, 256, IgemmArgs, (igemm_direct_body<float, 4>(a)))
+KDEF(igemm_f32_direct8, 512, IgemmArgs, (igemm_direct_body<float, 8>(a)))
+KDEF(igemm_f32_direct16, 1024, IgemmArgs, (igemm_direct_body<float, 16>(a)))
 KDEF(igemm_f32_t64x64_scalar, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false>(a)))
 KDEF(gemv_f16, 256, IgemmArgs, (gemv_body<half_t>(a)))
 KDEF(gemv_f32, 256, IgemmArgs, (gemv_body<float>(a)))
@@ -528,8 +718,8 @@ KDEF(pool_f16_vec, 256, PoolArgs, (pool_body<half_t, 8>(a)))
 KDEF(pool_f16_scalar, 256, PoolArgs, (pool_body<half_t, 1>(a)))
 KDEF(pool_f32_vec, 256, PoolArgs, (pool_body<float, 4>(a)))
 KDEF(pool_f32_scalar, 256, PoolArgs, (pool_body<float, 1>(a)))
-KDEF(gap_f16, 64, GapArgs, (gap_body<half_t>(a)))
-KDEF(gap_f32, 64, GapArgs, (gap_body<float>(a)))
+KDEF(gap_f16, 256, GapArgs, (gap_body<half_t>(a)))
+KDEF(gap_f32, 256, GapArgs, (gap_body<float>(a)))
 KDEF(layernorm_f16_wave, 256, RowArgs, (row_cached_body<half_t, true, 64, 2>(a)))
 KDEF(layernorm_f16_block, 256, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks>(a)))
 KDEF(layernorm_f16_generic, 256, RowArgs, (row_generic_body<half_t, true>(a)))

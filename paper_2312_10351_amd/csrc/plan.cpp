@@ -95,10 +95,27 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     kernel = f16 ? K_igemm_f16_t64x64_scalar : K_igemm_f32_t64x64_scalar;
   } else {
     const int64_t n128 = (int64_t)cdiv(a.M, 128) * cdiv(a.N, 128) * batch;
-    const int64_t n64 = (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * batch;
-    if (n128 >= 128) { t = kTile128; kernel = f16 ? K_igemm_f16_t128x128 : K_igemm_f32_t128x128; }
-    else if (n64 >= 48) { t = kTile64; kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64; }
-    else { t = kTile32; kernel = f16 ? K_igemm_f16_t32x32 : K_igemm_f32_t32x32; }
+    if (n128 >= 128) {
+      t = kTile128;
+      kernel = f16 ? K_igemm_f16_t128x128 : K_igemm_f32_t128x128;
+    } else if (a.b_kmajor) {           // [K][N] operand: staged (and transposed) through LDS
+      t = kTile64;
+      kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64;
+    } else {
+      // Latency-oriented kernel; more wavefronts share K the deeper it is, so that no
+      // wavefront walks more than two pairs of 64-byte steps.
+      const int nds = (int)cdiv(a.K, 8 * ve);
+      const int waves = nds <= 16 ? 4 : nds <= 32 ? 8 : 16;
+      static const int ids[2][3] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_direct16},
+                                    {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_direct16}};
+      out->kernel = ids[f16][waves == 4 ? 0 : waves == 8 ? 1 : 2];
+      out->gx = cdiv(a.M, kDirectTile);
+      out->gy = cdiv(a.N, kDirectTile);
+      out->gz = (uint32_t)batch;
+      out->block = waves * 64;
+      out->args.igemm = a;
+      return OPARA_OK;
+    }
   }
   out->kernel = kernel;
   out->gx = cdiv(a.M, t.bm);
@@ -141,7 +158,7 @@ int plan_gap(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
   std::memset(&a, 0, sizeof a);
   a.x = in[0]; a.y = op.out; a.HW = p.h_in * p.w_in; a.C = p.c_in;
   out->kernel = op.dtype == OPARA_F16 ? K_gap_f16 : K_gap_f32;
-  out->gx = cdiv(p.c_in, 64); out->gy = out->gz = 1; out->block = 64;
+  out->gx = cdiv(p.c_in, 64); out->gy = out->gz = 1; out->block = 256;
   out->args.gap = a;
   return OPARA_OK;
 }

@@ -50,7 +50,11 @@ class StreamSet:
 class Session:
     """One workload bound to device buffers and a built DAG handle."""
 
-    def __init__(self, wl, device="cuda:0", demand_override=None, class_override=None):
+    def __init__(self, wl, device="cuda:0", demand_override=None, class_override=None, pad_channels=True):
+        """pad_channels: an external image whose channel count is not a multiple of the
+        16-byte vector width and that feeds convolutions only is stored with zero
+        channels appended (and the weights with matching zero taps) - a storage layout,
+        the results are unchanged."""
         self.wl = wl
         self.device = device
         self.dag = None
@@ -59,7 +63,18 @@ class Session:
         self._fake = 0x10000
         self._keep = []
         self.dtype_id = B.F32 if wl.dtype == "f32" else B.F16
-        self.ext_dev = [self._upload(self._to_physical_input(a)) for a in wl.ext_inputs]
+        ve = 4 if wl.dtype == "f32" else 8
+        self.ext_pad = {}
+        if pad_channels:
+            users = {}
+            for op in wl.ops:
+                for u in op.inputs:
+                    if u < 0:
+                        users.setdefault(-u - 1, []).append(op)
+            for slot, a in enumerate(wl.ext_inputs):
+                if a.ndim == 3 and a.shape[0] % ve and all(o.type == "conv2d" for o in users.get(slot, [])):
+                    self.ext_pad[slot] = (a.shape[0] + ve - 1) // ve * ve
+        self.ext_dev = [self._upload(self._to_physical_input(a, self.ext_pad.get(i))) for i, a in enumerate(wl.ext_inputs)]
         self.out_dev = []
         self.w_dev, self.b_dev = {}, {}
         descs = []
@@ -74,10 +89,16 @@ class Session:
             if demand_override is not None:
                 d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs = demand_override[op.id]
             self._fill_params(op, d.params)
+            if op.type == "conv2d" and op.inputs[0] < 0 and (-op.inputs[0] - 1) in self.ext_pad:
+                d.params.c_in = self.ext_pad[-op.inputs[0] - 1]
             if op.id in wl.weights:
                 w, b = wl.weights[op.id]["w"], wl.weights[op.id]["b"]
                 if op.type == "conv2d":
-                    wp = np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))
+                    wp = np.transpose(w, (0, 2, 3, 1))
+                    cpad = self.ext_pad.get(-op.inputs[0] - 1) if op.inputs[0] < 0 else None
+                    if cpad:
+                        wp = np.concatenate([wp, np.zeros(wp.shape[:3] + (cpad - wp.shape[3],), dtype=w.dtype)], axis=3)
+                    wp = np.ascontiguousarray(wp)
                 else:
                     wp = np.ascontiguousarray(w.T)
                 self.w_dev[op.id] = self._upload(wp)
@@ -114,8 +135,13 @@ class Session:
         return t if isinstance(t, int) else t.data_ptr()
 
     @staticmethod
-    def _to_physical_input(a):
-        return np.ascontiguousarray(np.transpose(a, (1, 2, 0))) if a.ndim == 3 else a
+    def _to_physical_input(a, pad_to=None):
+        if a.ndim != 3:
+            return a
+        hwc = np.transpose(a, (1, 2, 0))
+        if pad_to:
+            hwc = np.concatenate([hwc, np.zeros(hwc.shape[:2] + (pad_to - hwc.shape[2],), dtype=a.dtype)], axis=2)
+        return np.ascontiguousarray(hwc)
 
     def _fill_params(self, op, p):
         q, t = op.params, op.type

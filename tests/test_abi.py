@@ -187,7 +187,7 @@ def test_kernel_table():
     assert len(set(names)) == n and "igemm_f16_t64x64" in names
     for i in range(n):
         name, vg, lds = B.opara_kernel_info(i)
-        assert 0 < vg <= 512 and lds <= 65536
+        assert 0 < vg <= 512 and lds <= 163840
         if name.startswith("igemm"):
             assert lds > 0
     with pytest.raises(B.OparaError):

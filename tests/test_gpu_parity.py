@@ -12,11 +12,11 @@ from util import compare_all, literal_fp16_bound_ok
 pytestmark = pytest.mark.gpu
 
 
-def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlier_frac=0.0):
+def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlier_frac=0.0, pad_channels=True):
     """Run the workload in the given modes; every operator output must match the oracle.
     Returns {mode: {sink id: bytes}} so callers can also compare modes bit for bit."""
     ref = executor.run_dag(wl) if ref is None else ref
-    s = Session(wl)
+    s = Session(wl, pad_channels=pad_channels)
     sinks = {}
     try:
         for mode in modes:
@@ -53,7 +53,10 @@ def test_conv(case, dtype):
     x = b.ext((cin, h, w))
     b.conv(x, cout, k, stride=s, pad=p, relu=True)
     b.conv(x, cout, k, stride=s, pad=p, relu=False)
-    run_modes(b.build(11, random_bias=True, w_std=0.2), modes=("eager",))
+    wl = b.build(11, random_bias=True, w_std=0.2)
+    run_modes(wl, modes=("eager",), pad_channels=False)      # odd channel counts: scalar gather
+    if cin % 8:
+        run_modes(wl, modes=("eager",), pad_channels=True)   # same case through the padded layout
 
 
 GEMM_CASES = [(1, 64, 40), (3, 200, 17), (5, 96, 64), (37, 72, 50), (64, 256, 64), (130, 136, 200),
