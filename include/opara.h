@@ -164,6 +164,22 @@ int opara_assign_streams(opara_dag *g, int32_t *stream_of, int32_t *n_streams);
 int opara_order_launch(opara_dag *g, int32_t *order);
 
 /*
+ * Launch-order policies for ablation (paper Sec. 2.3: the launch order alone moves the
+ * latency).  OPARA_ORDER_ALG2 is opara_order_launch.  Every policy yields a topological
+ * order and replaces the queue a later opara_capture uses.
+ *   ALG2_COMP_FIRST  Alg. 2 with the preference starting at the compute list
+ *   LEAST_DEMAND     one ready list, least demand first (no class alternation)
+ *   MOST_DEMAND      one ready list, largest demand first
+ *   TOPO             ready operator with the smallest id first (trace order)
+ *   LEVEL            by depth (longest distance from a root), then id: wave by wave
+ */
+enum opara_order_policy {
+  OPARA_ORDER_ALG2 = 0, OPARA_ORDER_ALG2_COMP_FIRST, OPARA_ORDER_LEAST_DEMAND,
+  OPARA_ORDER_MOST_DEMAND, OPARA_ORDER_TOPO, OPARA_ORDER_LEVEL, OPARA_N_ORDER_POLICIES
+};
+int opara_order_launch_policy(opara_dag *g, int32_t policy, int32_t *order);
+
+/*
  * Dependencies that need a synchronisation operator (paper Sec. 3.1, Eq. 3; Sec. 4):
  * every edge (u,v) whose endpoints are on different streams, sorted by (v, argument
  * position of u).  uv: host int32[2*cap] filled with pairs u,v up to cap pairs;

@@ -110,6 +110,55 @@ def order_launch(preds, op_class, demand):
     return q
 
 
+POLICIES = ("alg2", "alg2_comp_first", "least_demand", "most_demand", "topo", "level")
+
+
+def order_launch_policy(preds, op_class, demand, policy):
+    """Launch-order variants for the order ablation (paper Sec. 2.3 compares launch
+    orders).  "alg2" is Algorithm 2; "alg2_comp_first" starts its alternation at the
+    compute list; "least_demand"/"most_demand" keep one ready list ordered by demand;
+    "topo" is Kahn smallest id; "level" goes wave by wave (depth, then id)."""
+    n = len(preds)
+    topo = kahn_order(n, _edges(preds))
+    tindex = {v: i for i, v in enumerate(topo)}
+    if policy == "alg2":
+        return order_launch(preds, op_class, demand)
+    if policy == "topo":
+        return topo
+    if policy == "level":
+        depth = [0] * n
+        for v in topo:
+            for u in preds[v]:
+                depth[v] = max(depth[v], depth[u] + 1)
+        return sorted(range(n), key=lambda v: (depth[v], tindex[v]))
+    succ = [[] for _ in range(n)]
+    indeg = [len(p) for p in preds]
+    for v, ps in enumerate(preds):
+        for u in ps:
+            succ[u].append(v)
+    ready = [v for v in topo if indeg[v] == 0]
+    q, pref = [], COMP
+    while ready:
+        if policy == "alg2_comp_first":
+            pool = [v for v in ready if op_class[v] == pref] or ready
+            key = lambda u: (demand[u], tindex[u])
+        elif policy == "least_demand":
+            pool, key = ready, (lambda u: (demand[u], tindex[u]))
+        elif policy == "most_demand":
+            pool, key = ready, (lambda u: (-demand[u], tindex[u]))
+        else:
+            raise ValueError(policy)
+        v = min(pool, key=key)
+        ready.remove(v)
+        q.append(v)
+        pref = MEM if op_class[v] == COMP else COMP
+        for s in succ[v]:
+            indeg[s] -= 1
+            if indeg[s] == 0:
+                ready.append(s)
+    return q
+
+
 def sync_edges(preds, stream_of):
     """All dependencies whose endpoints sit on different streams, sorted by (v, arg position)."""
     return [(u, v) for v, ps in enumerate(preds) for u in ps if stream_of[u] != stream_of[v]]

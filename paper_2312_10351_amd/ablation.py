@@ -1,0 +1,108 @@
+"""Launch-order and interference ablations over the same kernels and graphs.
+
+  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300]
+
+Part 1 (paper Sec. 2.3, "GPU blocking"): the parallel graph is captured with each
+launch-order policy of opara_order_launch_policy and replayed; only the queue differs.
+Part 2 (paper Sec. 2.3, "Performance interference"): two independent operators are
+replayed alone, back to back on one stream, and side by side on two streams, for a
+compute-intensive + memory-intensive pair and for two pairs of one class.
+Prints one JSON object per line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def replay_latency(session, exe, replays, warmup=30):
+    from . import binding as B
+    st = session.make_streams(1)
+    h, ts = st.handles[0], st.torch_streams[0]
+    for _ in range(warmup):
+        B.opara_replay(exe, h)
+    ts.synchronize()
+    lat = []
+    for _ in range(replays):
+        t0 = time.perf_counter()
+        B.opara_replay(exe, h)
+        ts.synchronize()
+        lat.append((time.perf_counter() - t0) * 1e6)
+    return float(np.median(lat))
+
+
+def order_ablation(index, replays):
+    from . import binding as B
+    from .runtime import Session
+    from workloads import build_config
+    wl = build_config(index)
+    s = Session(wl)
+    try:
+        row = {"ablation": "launch_order", "workload": wl.name, "n_ops": len(wl.ops)}
+        row["sequential_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
+        for pid, name in enumerate(B.ORDER_POLICY_NAMES):
+            row[name + "_us"] = replay_latency(s, s.capture(B.PARALLEL, policy=pid), replays)
+        return row
+    finally:
+        s.close()
+
+
+def _pair(kind_a, kind_b):
+    """Two independent operators of the given classes reading the same external tensor."""
+    from workloads import Builder
+    b = Builder(f"{kind_a}_{kind_b}", "f16")
+    x = b.ext((512, 4096))
+    big = b.ext((8192, 8192))
+    for kind in (kind_a, kind_b):
+        if kind == "comp":
+            b.gemm(x, 512, 4096, 4096)                    # 17 GFLOP, 32 MB of weights
+        else:
+            b.rowwise("gelu", [big], 8192, 8192)          # 128 MB read + 128 MB written
+    return b
+
+
+def interference(kind_a, kind_b, replays):
+    from . import binding as B
+    from .runtime import Session
+    from workloads import Builder
+    row = {"ablation": "interference", "pair": f"{kind_a}||{kind_b}"}
+    wl = _pair(kind_a, kind_b).build(3)
+    s = Session(wl)
+    try:
+        row["sequential_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
+        row["parallel_us"] = replay_latency(s, s.capture(B.PARALLEL), replays)
+    finally:
+        s.close()
+    for tag, kind in (("a", kind_a), ("b", kind_b)):
+        b = Builder("single", "f16")
+        if kind == "comp":
+            b.gemm(b.ext((512, 4096)), 512, 4096, 4096)
+        else:
+            b.rowwise("gelu", [b.ext((8192, 8192))], 8192, 8192)
+        s = Session(b.build(3))
+        try:
+            row[f"alone_{tag}_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
+        finally:
+            s.close()
+    row["overlap_gain"] = row["sequential_us"] / row["parallel_us"]
+    return row
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="0,1,2,3,4")
+    ap.add_argument("--replays", type=int, default=300)
+    a = ap.parse_args()
+    for idx in [int(x) for x in a.configs.split(",") if x]:
+        print(json.dumps(order_ablation(idx, a.replays)), flush=True)
+    for pair in (("comp", "mem"), ("mem", "mem"), ("comp", "comp")):
+        print(json.dumps(interference(*pair, max(50, a.replays // 3))), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -16,6 +16,9 @@ CLASS_DEFAULT, MEM, COMP = -1, 0, 1
 F32, F16 = 0, 1
 PARALLEL, SEQUENTIAL, PARALLEL_EXPLICIT = 0, 1, 2
 FLAG_RELU, FLAG_B_KMAJOR = 1, 2
+(ORDER_ALG2, ORDER_ALG2_COMP_FIRST, ORDER_LEAST_DEMAND, ORDER_MOST_DEMAND, ORDER_TOPO,
+ ORDER_LEVEL) = range(6)
+ORDER_POLICY_NAMES = ("alg2", "alg2_comp_first", "least_demand", "most_demand", "topo", "level")
 
 
 class OparaError(RuntimeError):
@@ -57,7 +60,7 @@ class Demand(C.Structure):
                 ("op_class", C.c_int32), ("kernel_id", C.c_int32), ("demand", C.c_uint64)]
 
 
-EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_sync_edges",
+EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_order_launch_policy", "opara_sync_edges",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
            "opara_replay", "opara_exec_info", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
@@ -80,6 +83,7 @@ def load():
                                     C.POINTER(Limits), C.POINTER(vp)]
     lib.opara_assign_streams.argtypes = [vp, i32p, i32p]
     lib.opara_order_launch.argtypes = [vp, i32p]
+    lib.opara_order_launch_policy.argtypes = [vp, C.c_int32, i32p]
     lib.opara_sync_edges.argtypes = [vp, i32p, C.c_int32, i32p]
     lib.opara_get_demands.argtypes = [vp, C.POINTER(Demand)]
     lib.opara_topo_order.argtypes = [vp, i32p]
@@ -137,6 +141,13 @@ def opara_order_launch(dag):
     n = opara_num_ops(dag)
     q = (C.c_int32 * n)()
     _check(load().opara_order_launch(dag, q))
+    return list(q)
+
+
+def opara_order_launch_policy(dag, policy):
+    n = opara_num_ops(dag)
+    q = (C.c_int32 * n)()
+    _check(load().opara_order_launch_policy(dag, policy, q))
     return list(q)
 
 

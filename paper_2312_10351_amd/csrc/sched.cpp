@@ -185,32 +185,57 @@ extern "C" int opara_assign_streams(opara_dag *g, int32_t *stream_of, int32_t *n
   return OPARA_OK;
 }
 
-extern "C" int opara_order_launch(opara_dag *g, int32_t *order) {
+extern "C" int opara_order_launch_policy(opara_dag *g, int32_t policy, int32_t *order) {
   if (!g || !order) { set_error("opara_order_launch: null pointer"); return OPARA_EINVAL; }
+  if (policy < 0 || policy >= OPARA_N_ORDER_POLICIES) {
+    set_error("opara_order_launch_policy: unknown policy %d", policy);
+    return OPARA_EINVAL;
+  }
   const int32_t n = g->n;
-  // Ready lists as min-heaps on (demand, topological index): the pop is the argmin.
+  // Ready lists as min-heaps; the pop is the argmin of the policy's key.  The paper's
+  // Alg. 2 keeps two lists (memory- / compute-intensive) keyed by (demand, topological
+  // index) and alternates between them; the other policies use a single list.
   typedef std::pair<uint64_t, int32_t> Key;
   std::priority_queue<Key, std::vector<Key>, std::greater<Key>> ready[2];
-  std::vector<int32_t> indeg(n);
+  const bool two_lists = policy == OPARA_ORDER_ALG2 || policy == OPARA_ORDER_ALG2_COMP_FIRST;
+  std::vector<int32_t> indeg(n), level(n, 0);
   for (int32_t v = 0; v < n; ++v) indeg[v] = g->pred_off[v + 1] - g->pred_off[v];
-  for (int32_t v = 0; v < n; ++v)
-    if (indeg[v] == 0) ready[g->dem[v].op_class].push(Key(g->dem[v].demand, g->tindex[v]));
+  if (policy == OPARA_ORDER_LEVEL)
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = g->topo[i];
+      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) level[v] = std::max(level[v], level[g->pred[j]] + 1);
+    }
+  auto push = [&](int32_t v) {
+    switch (policy) {
+      case OPARA_ORDER_ALG2: case OPARA_ORDER_ALG2_COMP_FIRST:
+        ready[g->dem[v].op_class].push(Key(g->dem[v].demand, g->tindex[v])); break;
+      case OPARA_ORDER_LEAST_DEMAND: ready[0].push(Key(g->dem[v].demand, g->tindex[v])); break;
+      case OPARA_ORDER_MOST_DEMAND: ready[0].push(Key(~g->dem[v].demand, g->tindex[v])); break;
+      case OPARA_ORDER_LEVEL: ready[0].push(Key((uint64_t)level[v], g->tindex[v])); break;
+      default: ready[0].push(Key(0, g->tindex[v])); break;   // OPARA_ORDER_TOPO
+    }
+  };
+  for (int32_t v = 0; v < n; ++v) if (indeg[v] == 0) push(v);
   g->order.clear();
   g->order.reserve(n);
-  int pref = OPARA_MEM;
+  int pref = policy == OPARA_ORDER_ALG2_COMP_FIRST ? OPARA_COMP : OPARA_MEM;
   while (!ready[0].empty() || !ready[1].empty()) {
-    const int cls = !ready[pref].empty() ? pref : 1 - pref;
+    const int cls = two_lists ? (!ready[pref].empty() ? pref : 1 - pref) : 0;
     const int32_t v = g->topo[ready[cls].top().second];
     ready[cls].pop();
     g->order.push_back(v);
     pref = 1 - cls;
     for (int32_t j = g->succ_off[v]; j < g->succ_off[v + 1]; ++j) {
       const int32_t s = g->succ[j];
-      if (--indeg[s] == 0) ready[g->dem[s].op_class].push(Key(g->dem[s].demand, g->tindex[s]));
+      if (--indeg[s] == 0) push(s);
     }
   }
   std::memcpy(order, g->order.data(), sizeof(int32_t) * n);
   return OPARA_OK;
+}
+
+extern "C" int opara_order_launch(opara_dag *g, int32_t *order) {
+  return opara_order_launch_policy(g, OPARA_ORDER_ALG2, order);
 }
 
 extern "C" int opara_sync_edges(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges) {

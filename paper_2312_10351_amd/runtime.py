@@ -186,9 +186,9 @@ class Session:
             p.eps = q.get("eps", 0.0)
 
     # ---- the path
-    def schedule(self):
+    def schedule(self, policy=B.ORDER_ALG2):
         so, ns = B.opara_assign_streams(self.dag)
-        order = B.opara_order_launch(self.dag)
+        order = B.opara_order_launch_policy(self.dag, policy)
         return so, ns, order, B.opara_sync_edges(self.dag)
 
     def make_streams(self, n):
@@ -198,9 +198,9 @@ class Session:
             self.streams = StreamSet(n, self.device)
         return self.streams
 
-    def capture(self, mode):
+    def capture(self, mode, policy=B.ORDER_ALG2):
         if mode != B.SEQUENTIAL:
-            _, ns, _, _ = self.schedule()
+            _, ns, _, _ = self.schedule(policy)
         else:
             ns = 1
         st = self.make_streams(max(ns, 1))

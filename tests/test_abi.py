@@ -170,6 +170,33 @@ def test_scheduler_matches_oracle_on_random_dags():
         assert syncs == sched.sync_edges(preds, oso)
 
 
+def test_order_policies_match_oracle():
+    rng = np.random.default_rng(99)
+    for trial in range(300):
+        n = int(rng.integers(1, 25))
+        inputs = [[-1] if v == 0 or rng.random() < 0.3 else [int(u) for u in rng.integers(0, v, size=int(rng.integers(1, 4)))]
+                  for v in range(n)]
+        descs = chain_descs(n, inputs)
+        for d in descs:
+            d.op_class = int(rng.integers(0, 2))
+            d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs = int(rng.integers(1, 4)), 256, 0, 32
+        dag = B.opara_build_dag(descs, [0x1000])
+        preds = sched.dedup_preds(inputs)
+        cls = [d.op_class for d in descs]
+        dem = [sched.demand_scalar((d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs), LIMITS) for d in descs]
+        so, ns = sched.assign_streams(preds)
+        B.opara_assign_streams(dag)
+        for pid, name in enumerate(sched.POLICIES):
+            q = B.opara_order_launch_policy(dag, pid)
+            assert q == sched.order_launch_policy(preds, cls, dem, name), (trial, name, inputs)
+            assert sched.check_schedule(preds, so, q, sched.sync_edges(preds, so))
+        assert B.opara_order_launch_policy(dag, B.ORDER_ALG2) == B.opara_order_launch(dag)
+        with pytest.raises(B.OparaError):
+            B.opara_order_launch_policy(dag, 17)
+        B.opara_dag_destroy(dag)
+    assert B.ORDER_POLICY_NAMES == sched.POLICIES
+
+
 def test_random_small_workloads_schedule():
     for seed in range(5):
         wl = random_small_dag(seed, n_ops=60)

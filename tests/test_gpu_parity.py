@@ -42,7 +42,8 @@ CONV_CASES = [  # cin, h, w, cout, k, stride, pad
     (8, 9, 11, 20, 1, 1, 0), (16, 13, 9, 40, 3, 1, 1), (8, 12, 12, 24, 5, 1, 2), (3, 21, 19, 10, 7, 2, 3),
     (24, 15, 15, 33, 3, 2, 0), (8, 10, 9, 16, (1, 7), 1, (0, 3)), (8, 9, 10, 16, (7, 1), 1, (3, 0)),
     (16, 8, 8, 72, (1, 3), 1, (0, 1)), (16, 8, 8, 72, (3, 1), 1, (1, 0)), (5, 7, 6, 7, 3, 1, 1),
-    (64, 28, 28, 96, 3, 1, 1), (40, 20, 20, 130, 1, 1, 0), (8, 40, 40, 136, 3, 1, 1)]
+    (64, 28, 28, 96, 3, 1, 1), (40, 20, 20, 130, 1, 1, 0), (8, 40, 40, 136, 3, 1, 1),
+    (128, 56, 56, 256, 3, 1, 1), (96, 47, 45, 200, 5, 2, 2)]   # large enough for the tiled split-K kernel
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
@@ -60,7 +61,8 @@ def test_conv(case, dtype):
 
 
 GEMM_CASES = [(1, 64, 40), (3, 200, 17), (5, 96, 64), (37, 72, 50), (64, 256, 64), (130, 136, 200),
-              (128, 768, 768), (512, 320, 1024), (33, 7, 9), (1, 1024, 1000)]
+              (128, 768, 768), (512, 320, 1024), (33, 7, 9), (1, 1024, 1000),
+              (256, 2048, 1024), (512, 4096, 512), (200, 1544, 2048), (384, 512, 4096), (1100, 264, 2000)]
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
