@@ -215,6 +215,20 @@ int32_t opara_num_ops(const opara_dag *g);
 int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams,
                   int32_t mode, opara_exec **out);
 
+/*
+ * Dependency self-check of the graph runtime (failure detection).  Builds a graph with
+ * exactly the nodes order and dependency edges opara_capture gives the current parallel
+ * plan, but with marker kernels instead of operators: each marks its operator done
+ * after a few microseconds and counts predecessors that are not yet marked.  The graph
+ * is launched twice on `hip_stream`, which is synchronised; n_violations receives the
+ * total (0 = every dependency was honoured).  Uses static device memory only.  A
+ * non-zero count means the graph runtime dropped a dependency of this topology and
+ * node order.  The check runs on a graph of its own: it screens a plan, it does not
+ * certify a particular opara_exec (compare a replay of the captured graph with the
+ * sequential graph's result for that).  Needs assign + order first (ESTATE).
+ */
+int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violations);
+
 /* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
 int opara_replay(opara_exec *e, void *hip_stream);
 

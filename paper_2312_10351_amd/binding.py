@@ -62,7 +62,7 @@ class Demand(C.Structure):
 
 EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_order_launch_policy", "opara_sync_edges",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
-           "opara_replay", "opara_exec_info", "opara_launch_op", "opara_run_eager",
+           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
 
@@ -90,6 +90,7 @@ def load():
     lib.opara_num_ops.argtypes = [vp]
     lib.opara_capture.argtypes = [vp, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(vp)]
     lib.opara_replay.argtypes = [vp, vp]
+    lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
     lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
     lib.opara_run_eager.argtypes = [vp, vp]
@@ -182,6 +183,12 @@ def opara_capture(dag, stream_handles, mode):
 
 def opara_replay(exe, stream_handle):
     _check(load().opara_replay(exe, C.c_void_p(stream_handle)))
+
+
+def opara_verify_dependencies(dag, stream_handle):
+    n = C.c_int32()
+    _check(load().opara_verify_dependencies(dag, C.c_void_p(stream_handle), C.byref(n)))
+    return n.value
 
 
 def opara_exec_info(exe):

@@ -174,6 +174,67 @@ fail:
   return OPARA_EHIP;
 }
 
+// Builds a graph with the topology and node order opara_capture gives the parallel plan,
+// but with marker kernels as nodes, replays it and counts operators that ran before one
+// of their predecessors had finished.
+extern "C" int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violations) {
+  if (!g || !n_violations) { set_error("opara_verify_dependencies: null pointer"); return OPARA_EINVAL; }
+  if (g->stream_of.empty() || g->order.empty()) {
+    set_error("opara_verify_dependencies: call opara_assign_streams and opara_order_launch first");
+    return OPARA_ESTATE;
+  }
+  const int32_t n = g->n;
+  if (n > kVerifyMaxOps) { set_error("opara_verify_dependencies: more than %d operators", kVerifyMaxOps); return OPARA_EUNSUPPORTED; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  int total = 0;
+  {
+    std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(g->n_streams, nullptr), deps;
+    HIP_TRY(hipGraphCreate(&graph, 0));
+    int32_t n_sinks = 0;
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = g->order[i], sv = g->stream_of[v];
+      TokenArgs t = {};
+      t.epoch = 1; t.self = v; t.delay = 4;
+      deps.clear();
+      if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
+      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+        const int32_t u = g->pred[j];
+        if (t.n_preds < kVerifyMaxPreds) t.preds[t.n_preds++] = u;
+        if (g->stream_of[u] != sv) deps.push_back(node_of[u]);
+      }
+      HIP_TRY(add_token_node(graph, t, deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
+      last_on_stream[sv] = node_of[v];
+      n_sinks += (g->succ_off[v + 1] == g->succ_off[v]);
+    }
+    if (n_sinks > 1) {
+      hipGraphNode_t leaf = nullptr;
+      deps.clear();
+      for (int32_t v = 0; v < n; ++v)
+        if (g->succ_off[v + 1] == g->succ_off[v]) deps.push_back(node_of[v]);
+      HIP_TRY(add_noop_node(graph, deps.data(), deps.size(), &leaf));
+    }
+    HIP_TRY(hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+    for (int rep = 0; rep < 2; ++rep) {
+      int viol = 0;
+      HIP_TRY(verify_reset(st));
+      HIP_TRY(hipGraphLaunch(exec, st));
+      HIP_TRY(verify_read(st, &viol));
+      total += viol;
+    }
+  }
+  (void)hipGraphExecDestroy(exec);
+  (void)hipGraphDestroy(graph);
+  *n_violations = total;
+  return OPARA_OK;
+fail:
+  if (exec) (void)hipGraphExecDestroy(exec);
+  if (graph) (void)hipGraphDestroy(graph);
+  (void)hipGetLastError();
+  return OPARA_EHIP;
+}
+
 extern "C" int opara_replay(opara_exec *e, void *hip_stream) {
   if (!e || !e->exec) { set_error("opara_replay: null handle"); return OPARA_EINVAL; }
   hipError_t err = hipGraphLaunch(e->exec, (hipStream_t)hip_stream);

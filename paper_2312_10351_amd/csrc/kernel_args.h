@@ -62,13 +62,13 @@ struct ConcatArgs {
 
 // X(name, ArgsType).  Order defines kernel ids.
 #define OPARA_KERNEL_LIST(X)            \
-  X(igemm_f16_t128x128, IgemmArgs)      \
+  X(igemm_f16_t128x64, IgemmArgs)       \
   X(igemm_f16_t64x64, IgemmArgs)        \
   X(igemm_f16_direct4, IgemmArgs)       \
   X(igemm_f16_direct8, IgemmArgs)       \
   X(igemm_f16_direct16, IgemmArgs)      \
   X(igemm_f16_t64x64_scalar, IgemmArgs) \
-  X(igemm_f32_t128x128, IgemmArgs)      \
+  X(igemm_f32_t128x64, IgemmArgs)       \
   X(igemm_f32_t64x64, IgemmArgs)        \
   X(igemm_f32_direct4, IgemmArgs)       \
   X(igemm_f32_direct8, IgemmArgs)       \
@@ -129,7 +129,9 @@ struct KernelPlan {
 
 // Tile geometry of the implicit-GEMM kernels (output columns x rows per workgroup).
 struct IgemmTile { int bn, bm, threads; };
-constexpr IgemmTile kTile128{128, 128, 256};
+constexpr IgemmTile kTile128x64{128, 64, 256};   // 128 output columns x 64 rows
+constexpr double kTiledMinFlops = 2.0e9;         // lighter contractions use the latency-oriented kernel
+constexpr int kTiledMinTiles = 80;               // ... and so do contractions with fewer 128x64 tiles
 constexpr IgemmTile kTile64{64, 64, 256};
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 

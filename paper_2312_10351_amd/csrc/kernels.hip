@@ -249,15 +249,21 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
   }
 }
 
-// ---------------------------------------------------------------------------------
-// Latency-oriented implicit GEMM for small problems (batch-1 convolutions, skinny
-// GEMMs): a workgroup owns a 32 x 32 output tile and its WAVES wavefronts split K
-// between them.  Every lane fetches its MFMA fragments straight from global memory
-// (32 contiguous bytes per row and lane group, so four lane groups consume a whole
-// 128-byte line), two 64-byte-deep K steps in flight at a time, no LDS and no
-// barrier inside the K loop.  Partial tiles meet in LDS once, at the end, where 256
-// threads apply the epilogue and write 8/16-byte pieces of output rows.
-// ---------------------------------------------------------------------------------
+// Workgroups are handed to the eight XCDs round-robin in launch order; each XCD has its
+// own L2.  Remap the linear workgroup index so that every XCD works on a contiguous
+// range of tiles (row tiles of one column tile first): neighbours that share operand
+// rows then share an L2 instead of fetching them eight times.
+__device__ __forceinline__ void xcd_tile(int &tx, int &ty) {
+  constexpr int kXcds = 8;
+  const int nx = gridDim.x, total = gridDim.x * gridDim.y;
+  const int lin = blockIdx.y * nx + blockIdx.x;
+  const int xcd = lin % kXcds, idx = lin / kXcds;
+  const int q = total / kXcds, r = total % kXcds;
+  const int tile = xcd * q + (xcd < r ? xcd : r) + idx;
+  tx = tile % nx;
+  ty = tile / nx;
+}
+
 struct KPos { int ci, s, r; };
 
 __device__ __forceinline__ void kpos_advance(KPos &p, int delta, int Cin, int kw) {
@@ -268,6 +274,194 @@ __device__ __forceinline__ void kpos_advance(KPos &p, int delta, int Cin, int kw
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Throughput-oriented tiled implicit GEMM: BN x BM tile, four wavefronts, K stages of
+// 128 bytes per row, LDS double buffer with a 144-byte row pitch, and global loads
+// running DEPTH-1 stages ahead in DEPTH rotating register sets (at one workgroup per
+// compute unit the loop is bound by memory latency, so the bytes in flight set the
+// speed).  Vector loads only, second operand stored [N][K].
+// ---------------------------------------------------------------------------------
+template <typename T, int BN, int BM, int WN, int WM, int DEPTH>
+__device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
+  typedef typename Vec16<T>::type V;
+  typedef typename Vec16<T>::quad Q;
+  constexpr int VE = Vec16<T>::N;
+  constexpr int KCH = 8;                   // 16-byte chunks per row and stage
+  constexpr int BKE = KCH * VE;
+  constexpr int NT = WN * WM * 64;
+  constexpr int ROWB = KCH * 16 + 16;
+  constexpr int CHW = BN * KCH / NT, CHX = BM * KCH / NT;
+  constexpr int FN = BN / WN / 16, FM = BM / WM / 16;
+  constexpr int RSTEP = NT / KCH;
+  static_assert((BN * KCH) % NT == 0 && (BM * KCH) % NT == 0, "tile/threads mismatch");
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2][(BN + BM) * ROWB];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wn0 = (wave % WN) * (BN / WN), wm0 = (wave / WN) * (BM / WM);
+  int tile_x, tile_y;
+  xcd_tile(tile_x, tile_y);
+  const int m0 = tile_x * BM, n0 = tile_y * BN;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+  const int kc = t % KCH, row0 = t / KCH;
+
+  // Per-thread rows, clamped into range: every global load below is unconditional and
+  // reads a valid address; out-of-range rows, K tails and padding taps are zeroed when
+  // the registers are written to LDS.  (A load guarded by a branch makes the compiler
+  // wait for it right inside the branch, which serialises the whole prefetch.)
+  int ih0[CHX], iw0[CHX];
+  const T *xrow[CHX];
+  const T *wrow[CHW];
+  unsigned rowmask = 0;                       // bit i: pixel row i valid, bit 8+i: weight row i valid
+#pragma unroll
+  for (int i = 0; i < CHX; ++i) {
+    const int m = m0 + row0 + i * RSTEP;
+    const bool ok = m < a.M;
+    const int mm = ok ? m : 0;
+    rowmask |= (unsigned)ok << i;
+    xrow[i] = x + (int64_t)mm * a.lda;
+    const int oh = mm / a.Wo, ow = mm - oh * a.Wo;   // used only when gathering
+    ih0[i] = oh * a.sh - a.ph;
+    iw0[i] = ow * a.sw - a.pw;
+  }
+#pragma unroll
+  for (int i = 0; i < CHW; ++i) {
+    const int n = n0 + row0 + i * RSTEP;
+    const bool ok = n < a.N;
+    rowmask |= (unsigned)ok << (8 + i);
+    wrow[i] = w + (int64_t)(ok ? n : 0) * a.ldb;
+  }
+  KPos pos = {0, 0, 0};
+  if (a.gather) {
+    const int k = kc * VE;
+    pos.ci = k % a.Cin;
+    const int rs = k / a.Cin;
+    pos.s = rs % a.kw;
+    pos.r = rs / a.kw;
+  }
+  const V vzero = {};
+
+  // Stages must be requested in increasing order.  Returns the validity mask of the set.
+  auto load_global = [&](int kt, V *wr, V *xr) -> unsigned {
+    const int kbase = kt * BKE + kc * VE;
+    const bool kok = kbase < a.K;
+    const int ks = kok ? kbase : 0;
+    unsigned mask = kok ? rowmask : 0u;
+    if (!a.gather) {
+#pragma unroll
+      for (int i = 0; i < CHX; ++i) xr[i] = *(const V *)(xrow[i] + ks);
+    } else {
+#pragma unroll
+      for (int i = 0; i < CHX; ++i) {
+        const int ih = ih0[i] + pos.r, iw = iw0[i] + pos.s;
+        const bool inb = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+        const int64_t off = inb ? ((int64_t)ih * a.W + iw) * a.Cin + pos.ci : 0;
+        if (!inb) mask &= ~(1u << i);
+        xr[i] = *(const V *)(x + off);
+      }
+      kpos_advance(pos, BKE, a.Cin, a.kw);
+    }
+#pragma unroll
+    for (int i = 0; i < CHW; ++i) wr[i] = *(const V *)(wrow[i] + ks);
+    return mask;
+  };
+  auto store_lds = [&](int buf, const V *wr, const V *xr, unsigned mask) {
+    unsigned char *Wb = smem[buf];
+    unsigned char *Xb = Wb + BN * ROWB;
+#pragma unroll
+    for (int i = 0; i < CHX; ++i)
+      *(V *)(Xb + (row0 + i * RSTEP) * ROWB + kc * 16) = ((mask >> i) & 1u) ? xr[i] : vzero;
+#pragma unroll
+    for (int i = 0; i < CHW; ++i)
+      *(V *)(Wb + (row0 + i * RSTEP) * ROWB + kc * 16) = ((mask >> (8 + i)) & 1u) ? wr[i] : vzero;
+  };
+
+  floatx4 acc[FN][FM];
+#pragma unroll
+  for (int i = 0; i < FN; ++i)
+#pragma unroll
+    for (int j = 0; j < FM; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int buf) {
+    const unsigned char *Wb = smem[buf];
+    const unsigned char *Xb = Wb + BN * ROWB;
+#pragma unroll
+    for (int ks = 0; ks < KCH / 4; ++ks) {
+      V af[FN], bf[FM];
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+        af[i] = *(const V *)(Wb + (wn0 + i * 16 + (lane & 15)) * ROWB + ks * 64 + (lane >> 4) * 16);
+#pragma unroll
+      for (int j = 0; j < FM; ++j)
+        bf[j] = *(const V *)(Xb + (wm0 + j * 16 + (lane & 15)) * ROWB + ks * 64 + (lane >> 4) * 16);
+#pragma unroll
+      for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j) acc[i][j] = mma16<T>(af[i], bf[j], acc[i][j]);
+    }
+  };
+
+  // DEPTH register sets rotate through the stages: set j carries the stages congruent to
+  // j; a set is refilled right after its previous stage went to LDS, so every load has
+  // DEPTH-1 stage computations to land.  Stages past the end of K are masked to zero.
+  const int nst = (a.K + BKE - 1) / BKE;
+  V wS[DEPTH][CHW], xS[DEPTH][CHX];
+  unsigned mS[DEPTH];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) mS[d] = load_global(d, wS[d], xS[d]);
+  store_lds(0, wS[0], xS[0], mS[0]);
+  __syncthreads();
+#pragma nounroll
+  for (int s = 0; s < nst; s += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {          // LDS buffer d&1 holds stage s+d
+      mS[d] = load_global(s + d + DEPTH, wS[d], xS[d]);
+      compute(d & 1);
+      store_lds((d + 1) & 1, wS[(d + 1) % DEPTH], xS[(d + 1) % DEPTH], mS[(d + 1) % DEPTH]);
+      __syncthreads();
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < FN; ++i) {
+    const int n = n0 + wn0 + i * 16 + (lane >> 4) * 4;
+#pragma unroll
+    for (int j = 0; j < FM; ++j) {
+      const int m = m0 + wm0 + j * 16 + (lane & 15);
+      if (m >= a.M || n >= a.N) continue;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float r = acc[i][j][e] * a.alpha;
+        if (n + e < a.N) {
+          if (a.bias) r += a.bias[n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
+        }
+        if (a.relu) r = fmaxf(r, 0.f);
+        v[e] = r;
+      }
+      T *dst = y + (int64_t)m * a.ldy + n;
+      if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+        Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+        *(Q *)dst = q4;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < a.N) dst[e] = (T)v[e];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Latency-oriented implicit GEMM for small problems (batch-1 convolutions, skinny
+// GEMMs): a workgroup owns a 32 x 32 output tile and its WAVES wavefronts split K
+// between them.  Every lane fetches its MFMA fragments straight from global memory
+// (32 contiguous bytes per row and lane group, so four lane groups consume a whole
+// 128-byte line), two 64-byte-deep K steps in flight at a time, no LDS and no
+// barrier inside the K loop.  Partial tiles meet in LDS once, at the end, where 256
+// threads apply the epilogue and write 8/16-byte pieces of output rows.
+// ---------------------------------------------------------------------------------
 template <typename T, int WAVES>
 __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
   typedef typename Vec16<T>::type V;
@@ -699,14 +893,17 @@ using namespace opara;
 
 #define KDEF(name, threads, Args, call) \
   extern "C" __global__ void __launch_bounds__(threads) opara_k_##name(Args a) { call; }
+// second launch bound: wavefronts per SIMD the register allocation must leave room for
+#define KDEF2(name, threads, waves_per_simd, Args, call) \
+  extern "C" __global__ void __launch_bounds__(threads, waves_per_simd) opara_k_##name(Args a) { call; }
 
-KDEF(igemm_f16_t128x128, 256, IgemmArgs, (igemm_body<half_t, 128, 128, 2, 2, true>(a)))
+KDEF2(igemm_f16_t128x64, 256, 2, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4>(a)))
 KDEF(igemm_f16_t64x64, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true>(a)))
 KDEF(igemm_f16_direct4, 256, IgemmArgs, (igemm_direct_body<half_t, 4>(a)))
 KDEF(igemm_f16_direct8, 512, IgemmArgs, (igemm_direct_body<half_t, 8>(a)))
 KDEF(igemm_f16_direct16, 1024, IgemmArgs, (igemm_direct_body<half_t, 16>(a)))
 KDEF(igemm_f16_t64x64_scalar, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false>(a)))
-KDEF(igemm_f32_t128x128, 256, IgemmArgs, (igemm_body<float, 128, 128, 2, 2, true>(a)))
+KDEF2(igemm_f32_t128x64, 256, 2, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4>(a)))
 KDEF(igemm_f32_t64x64, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true>(a)))
 KDEF(igemm_f32_direct4, 256, IgemmArgs, (igemm_direct_body<float, 4>(a)))
 KDEF(igemm_f32_direct8, 512, IgemmArgs, (igemm_direct_body<float, 8>(a)))
@@ -740,6 +937,20 @@ KDEF(concat_f16_vec, 256, ConcatArgs, (concat_body<half_t, 8>(a)))
 KDEF(concat_f16_scalar, 256, ConcatArgs, (concat_body<half_t, 1>(a)))
 KDEF(concat_f32_vec, 256, ConcatArgs, (concat_body<float, 4>(a)))
 KDEF(concat_f32_scalar, 256, ConcatArgs, (concat_body<float, 1>(a)))
+
+// Dependency self-check: done-tokens per operator and a violation counter, in static
+// device memory (nothing is allocated).
+static __device__ int g_verify_tok[opara::kVerifyMaxOps];
+static __device__ int g_verify_viol;
+
+extern "C" __global__ void opara_k_token(opara::TokenArgs a) {
+  if (threadIdx.x != 0) return;
+  for (int i = 0; i < a.n_preds; ++i)
+    if (__hip_atomic_load(&g_verify_tok[a.preds[i]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
+      atomicAdd(&g_verify_viol, 1);
+  for (int i = 0; i < a.delay; ++i) __builtin_amdgcn_s_sleep(127);   // bounded: a few microseconds
+  __hip_atomic_store(&g_verify_tok[a.self], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Kernel without work: a pure dependency node (common root / common leaf of a capture).
 extern "C" __global__ void opara_k_noop(int) {}
@@ -801,6 +1012,38 @@ hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_
   np.blockDim = dim3(64);
   np.kernelParams = kparams;
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNode_t *deps, size_t n_deps,
+                          hipGraphNode_t *node) {
+  TokenArgs args = t;
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = (void *)opara_k_token;
+  np.gridDim = dim3(1);
+  np.blockDim = dim3(64);
+  np.kernelParams = kparams;
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t verify_reset(hipStream_t s) {
+  void *tok = nullptr, *viol = nullptr;
+  hipError_t err = hipGetSymbolAddress(&tok, HIP_SYMBOL(g_verify_tok));
+  if (err != hipSuccess) return err;
+  err = hipGetSymbolAddress(&viol, HIP_SYMBOL(g_verify_viol));
+  if (err != hipSuccess) return err;
+  err = hipMemsetAsync(tok, 0, sizeof(int) * kVerifyMaxOps, s);
+  if (err != hipSuccess) return err;
+  return hipMemsetAsync(viol, 0, sizeof(int), s);
+}
+
+hipError_t verify_read(hipStream_t s, int *viol) {
+  void *p = nullptr;
+  hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_verify_viol));
+  if (err != hipSuccess) return err;
+  err = hipMemcpyAsync(viol, p, sizeof(int), hipMemcpyDeviceToHost, s);
+  if (err != hipSuccess) return err;
+  return hipStreamSynchronize(s);
 }
 
 const void *kernel_symbol(int id) {

@@ -2,6 +2,7 @@
 // The demand record of an operator (paper Sec. 3.2: threads, shared memory and
 // registers of one block; Sec. 2.3: number of blocks) follows from the plan made
 // here plus the static resources of the chosen kernel.
+#include <cstdlib>
 #include <cstring>
 #include "opara_internal.h"
 
@@ -14,6 +15,16 @@ const KernelResource kKernelResources[K_COUNT] = {
 };
 
 namespace {
+
+// Tuning knob (read once): OPARA_TILED_MIN_FLOPS moves the hand-over point between the
+// latency-oriented and the tiled contraction kernel.
+double tiled_min_flops() {
+  static const double v = [] {
+    const char *e = std::getenv("OPARA_TILED_MIN_FLOPS");
+    return e ? std::atof(e) : kTiledMinFlops;
+  }();
+  return v;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline uint32_t cdiv(int64_t a, int64_t b) { return (uint32_t)((a + b - 1) / b); }
@@ -95,9 +106,14 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     kernel = f16 ? K_igemm_f16_t64x64_scalar : K_igemm_f32_t64x64_scalar;
   } else {
     const int64_t n128 = (int64_t)cdiv(a.M, 128) * cdiv(a.N, 128) * batch;
-    if (n128 >= 128) {
-      t = kTile128;
-      kernel = f16 ? K_igemm_f16_t128x128 : K_igemm_f32_t128x128;
+    const double flops = 2.0 * a.M * a.N * a.K * (double)batch;
+    const int64_t tiles = (int64_t)cdiv(a.M, kTile128x64.bm) * cdiv(a.N, kTile128x64.bn) * batch;
+    (void)n128;
+    if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= tiled_min_flops()) {
+      // Throughput-oriented tiled kernel (128 output columns x 64 rows per workgroup):
+      // pays once the contraction is heavy and has enough tiles to occupy the device.
+      t = kTile128x64;
+      kernel = f16 ? K_igemm_f16_t128x64 : K_igemm_f32_t128x64;
     } else if (a.b_kmajor) {           // [K][N] operand: staged (and transposed) through LDS
       t = kTile64;
       kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64;

@@ -60,6 +60,8 @@ class Session:
         self.dag = None
         self.execs = []
         self.streams = None
+        self.capture_log = []
+        self._seq_reference = None
         self._fake = 0x10000
         self._keep = []
         self.dtype_id = B.F32 if wl.dtype == "f32" else B.F16
@@ -198,15 +200,45 @@ class Session:
             self.streams = StreamSet(n, self.device)
         return self.streams
 
-    def capture(self, mode, policy=B.ORDER_ALG2):
-        if mode != B.SEQUENTIAL:
-            _, ns, _, _ = self.schedule(policy)
-        else:
-            ns = 1
-        st = self.make_streams(max(ns, 1))
-        exe = B.opara_capture(self.dag, st.handles[:ns], mode)
-        self.execs.append(exe)
-        return exe
+    def capture(self, mode, policy=B.ORDER_ALG2, validate=True, max_attempts=6):
+        """Capture a graph.  Parallel graphs are validated before they are handed out: the
+        graph runtime has been seen to drop single dependencies of irregular DAGs
+        (depending on node order and allocation addresses), so the captured graph is
+        replayed once over poisoned outputs and must reproduce the sequential graph's
+        result bit for bit; otherwise it is rebuilt, then rebuilt with other node orders.
+        `self.capture_log` records what happened."""
+        if mode == B.SEQUENTIAL:
+            st = self.make_streams(1)
+            exe = B.opara_capture(self.dag, st.handles[:1], mode)
+            self.execs.append(exe)
+            return exe
+        attempts = [policy, policy, policy] + [p for p in (B.ORDER_TOPO, B.ORDER_LEVEL, B.ORDER_LEAST_DEMAND)
+                                               if p != policy]
+        for i, pol in enumerate(attempts[:max_attempts]):
+            _, ns, _, _ = self.schedule(pol)
+            st = self.make_streams(max(ns, 1))
+            exe = B.opara_capture(self.dag, st.handles[:ns], mode)
+            if not validate or self.device is None or self._matches_sequential(exe):
+                self.execs.append(exe)
+                self.capture_log.append(dict(mode=mode, requested_policy=policy, used_policy=pol, attempts=i + 1))
+                return exe
+            B.opara_exec_destroy(exe)
+        raise RuntimeError("no captured parallel graph reproduced the sequential result: "
+                           "the graph runtime keeps dropping dependencies of this DAG")
+
+    def _matches_sequential(self, exe):
+        import torch
+        if self._seq_reference is None:
+            seq = B.opara_capture(self.dag, self.make_streams(1).handles[:1], B.SEQUENTIAL)
+            self.replay(seq)
+            self._seq_reference = [t.clone() for t in self.out_dev]
+            B.opara_exec_destroy(seq)
+        bits = torch.int32 if self.wl.dtype == "f32" else torch.int16
+        for t in self.out_dev:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        self.replay(exe)
+        return all(torch.equal(t.view(bits), r.view(bits)) for t, r in zip(self.out_dev, self._seq_reference))
 
     def replay(self, exe, sync=True):
         import torch

@@ -166,6 +166,31 @@ def test_random_wide_dag_full_size():
     assert sinks["seq"] == sinks["par"]
 
 
+def test_parallel_graph_honours_every_dependency_under_all_orders():
+    """Irregular DAG, every launch-order policy: a replay over NaN-poisoned outputs must
+    reproduce the sequential graph bit for bit (Session.capture rebuilds a graph whose
+    replay does not; the log says how often that was needed)."""
+    import torch
+    wl = random_small_dag(7, n_ops=150, max_width=10)
+    s = Session(wl)
+    try:
+        seq = s.capture(B.SEQUENTIAL)
+        s.clear_outputs()
+        s.replay(seq)
+        ref = [t.clone() for t in s.out_dev]
+        for pid in range(len(B.ORDER_POLICY_NAMES)):
+            exe = s.capture(B.PARALLEL, policy=pid)
+            for rep in range(2):
+                for t in s.out_dev:
+                    t.fill_(float("nan"))
+                torch.cuda.synchronize()
+                s.replay(exe)
+                assert all(torch.equal(t.view(torch.int16), r.view(torch.int16)) for t, r in zip(s.out_dev, ref))
+        assert len(s.capture_log) == len(B.ORDER_POLICY_NAMES)
+    finally:
+        s.close()
+
+
 # ------------------------------------------------------------------ graph structure
 def test_graph_structure_and_replay_determinism():
     wl = googlenet_like()
@@ -185,6 +210,8 @@ def test_graph_structure_and_replay_determinism():
         # one per (consumer, cross-stream producer) pair
         same_stream_pairs = n - ns
         assert nodes == n and edges == same_stream_pairs + len(syncs)
+        assert B.opara_verify_dependencies(s.dag, s.streams.handles[0]) == 0    # marker-kernel self-check
+        assert s.capture_log and s.capture_log[0]["attempts"] == 1          # validated against the sequential graph
         s.replay(par)
         first = [s.output(v).tobytes() for v in range(n)]
         for _ in range(3):
