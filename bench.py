@@ -141,6 +141,25 @@ def bench_config(index, steps, warmup, with_kernels):
         s.close()
 
 
+def calibration_copy(reps=10, mib=64):
+    """Plain streaming kernel of known size (ReLU over `mib` MiB of fp16: that many bytes
+    read and as many written per launch), used to scale the HBM traffic counters."""
+    from paper_2312_10351_amd import binding as B
+    from paper_2312_10351_amd.runtime import Session
+    from workloads import Builder
+    rows = mib * 1024 * 1024 // 2 // 4096
+    b = Builder("calibration_copy", "f16")
+    b.rowwise("relu", [b.ext((rows, 4096))], rows, 4096)
+    s = Session(b.build(1))
+    try:
+        st = s.make_streams(1)
+        for _ in range(reps):
+            B.opara_launch_op(s.dag, 0, st.handles[0])
+        st.torch_streams[0].synchronize()
+    finally:
+        s.close()
+
+
 def cpu_baseline(budget_s=12.0):
     """The oracle executor, as it stands, on the host cores: full passes over the
     headline DAG until about `budget_s` seconds are spent."""
@@ -171,6 +190,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--configs", type=str, default="0,2,3,4", help="extra configs reported beside the headline one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch a 64 MiB streaming kernel 10 times (scale for rocprofv3 --pmc traffic counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (a batch-1 DAG is not sharded); use --gpus 1")
@@ -178,6 +199,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if a.calibration_copy:
+        calibration_copy()
     head, kern = bench_config(1, a.steps, a.warmup, with_kernels=True)
     others = []
     for idx in [int(x) for x in a.configs.split(",") if x != ""]:

@@ -474,7 +474,9 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int grp = lane >> 4, r16 = lane & 15;
-  const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+  int tile_x, tile_y;
+  xcd_tile(tile_x, tile_y);
+  const int m0 = tile_x * 32, n0 = tile_y * 32;
   const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
   const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
   T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
@@ -484,24 +486,22 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
   const int ds_begin = wave * per_wave;
   const int ds_end = min(nds, ds_begin + per_wave);
 
-  const T *wrow[2];
-  bool wok[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int n = n0 + i * 16 + r16;
-    wok[i] = n < a.N;
-    wrow[i] = w + (int64_t)(wok[i] ? n : 0) * a.ldb;
-  }
-  const T *xrow[2];
-  bool xok[2];
+  // Rows are clamped into range and every load is unconditional (a load behind a branch
+  // is waited for inside the branch).  Results of clamped rows are never stored; K
+  // tails are cancelled by zeroing the weight fragment, padding taps by zeroing the
+  // pixel fragment.
+  const T *wrow[2], *xrow[2];
   int ih0[2], iw0[2];
 #pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int n = min(n0 + i * 16 + r16, a.N - 1);
+    wrow[i] = w + (int64_t)n * a.ldb;
+  }
+#pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int m = m0 + j * 16 + r16;
-    xok[j] = m < a.M;
-    const int mm = xok[j] ? m : 0;
-    xrow[j] = x + (int64_t)mm * a.lda;
-    const int oh = mm / a.Wo, ow = mm - oh * a.Wo;      // only meaningful when gathering
+    const int m = min(m0 + j * 16 + r16, a.M - 1);
+    xrow[j] = x + (int64_t)m * a.lda;
+    const int oh = m / a.Wo, ow = m - oh * a.Wo;        // only meaningful when gathering
     ih0[j] = oh * a.sh - a.ph;
     iw0[j] = ow * a.sw - a.pw;
   }
@@ -523,25 +523,27 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
 
   for (int ds = ds_begin; ds < ds_end; ds += U) {
     V wa[U][2][2], xb[U][2][2];
+    bool kok[U][2], inb[U][2][2];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const bool live = ds + u < ds_end;
       KPos pc = pos;                       // position of chunk 0 of this step
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int k = (ds + u) * DS + grp * 2 * VE + c * VE;
-        const bool kok = live && k < a.K;
+        kok[u][c] = ds + u < ds_end && k < a.K;
+        const int ks = kok[u][c] ? k : 0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) wa[u][i][c] = (kok && wok[i]) ? *(const V *)(wrow[i] + k) : vzero;
+        for (int i = 0; i < 2; ++i) wa[u][i][c] = *(const V *)(wrow[i] + ks);
         if (!a.gather) {
 #pragma unroll
-          for (int j = 0; j < 2; ++j) xb[u][j][c] = (kok && xok[j]) ? *(const V *)(xrow[j] + k) : vzero;
+          for (int j = 0; j < 2; ++j) xb[u][j][c] = *(const V *)(xrow[j] + ks);
         } else {
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
             const int ih = ih0[j] + pc.r, iw = iw0[j] + pc.s;
-            const bool ok = kok && xok[j] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            xb[u][j][c] = ok ? *(const V *)(x + ((int64_t)ih * a.W + iw) * a.Cin + pc.ci) : vzero;
+            inb[u][j][c] = kok[u][c] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const int64_t off = inb[u][j][c] ? ((int64_t)ih * a.W + iw) * a.Cin + pc.ci : 0;
+            xb[u][j][c] = *(const V *)(x + off);
           }
           if (c == 0) kpos_advance(pc, VE, a.Cin, a.kw);
         }
@@ -551,11 +553,18 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
+      for (int c = 0; c < 2; ++c) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wa[u][i][c] = kok[u][c] ? wa[u][i][c] : vzero;
+        if (a.gather) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) xb[u][j][c] = inb[u][j][c] ? xb[u][j][c] : vzero;
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j] = mma16<T>(wa[u][i][c], xb[u][j][c], acc[i][j]);
+      }
   }
 
   // ---- meet in LDS: lane holds channels n = i*16 + grp*4 + e of pixel m = j*16 + r16
@@ -566,24 +575,39 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
   __syncthreads();
   if (t < 256) {
     const int pm = t >> 3, pn = (t & 7) * 4;
+    const int m = m0 + pm, n = n0 + pn;
+    const bool full = n + 3 < a.N;         // whole group of four channels inside the tensor
+    const bool live = m < a.M && n < a.N;
+    // epilogue operands first (independent loads), then the partial sums
+    floatx4 badd = {0.f, 0.f, 0.f, 0.f};
+    if (live && a.bias) {
+      if (full && ((uintptr_t)(a.bias + n) & 15) == 0) badd = *(const floatx4 *)(a.bias + n);
+      else
+        for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] = a.bias[n + e];
+    }
+    if (live)
+      for (int q = 0; q < a.n_extra; ++q) {
+        const T *ex = (const T *)a.extra[q] + (int64_t)m * a.N + n;
+        if (full && ((uintptr_t)ex & (4 * sizeof(T) - 1)) == 0) {
+          const Q v = *(const Q *)ex;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) badd[e] += (float)v[e];
+        } else {
+          for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] += (float)ex[e];
+        }
+      }
     floatx4 sum = *(const floatx4 *)&part[0][pm][pn];
 #pragma unroll
     for (int q = 1; q < WAVES; ++q) sum += *(const floatx4 *)&part[q][pm][pn];
-    const int m = m0 + pm, n = n0 + pn;
-    if (m < a.M && n < a.N) {
+    if (live) {
       float v[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float r = sum[e] * a.alpha;
-        if (n + e < a.N) {
-          if (a.bias) r += a.bias[n + e];
-          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
-        }
-        if (a.relu) r = fmaxf(r, 0.f);
-        v[e] = r;
+        const float r = sum[e] * a.alpha + badd[e];
+        v[e] = a.relu ? fmaxf(r, 0.f) : r;
       }
       T *dst = y + (int64_t)m * a.ldy + n;
-      if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+      if (full && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
         *(Q *)dst = q4;
       } else {
