@@ -62,7 +62,7 @@ enum opara_op_type {
 /* Operator table of paper Sec. 3.3 (memory- vs compute-intensive operators). */
 enum opara_class { OPARA_CLASS_DEFAULT = -1, OPARA_MEM = 0, OPARA_COMP = 1 };
 enum opara_dtype { OPARA_F32 = 0, OPARA_F16 = 1 };
-enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_EXPLICIT = 2 };
+enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_CAPTURE = 2 };
 
 enum opara_flags {
   OPARA_FLAG_RELU     = 1u,  /* CONV2D / GEMM: clamp the result at zero                    */
@@ -193,24 +193,29 @@ int opara_topo_order(const opara_dag *g, int32_t *order);
 int32_t opara_num_ops(const opara_dag *g);
 
 /*
- * Graph capture (paper Sec. 3.4).  OPARA_PARALLEL puts hip_streams[0..n_streams)
- * (hipStream_t handles supplied by the caller, at least as many as
- * opara_assign_streams reported, all distinct) into one stream capture, launches
- * every operator on its stream in launch-queue order, records one event after each
- * producer that has a cross-stream consumer, makes each consumer's stream wait once
- * per such producer, joins all streams back into hip_streams[0] and instantiates ONE
- * executable graph.  Nothing executes.
- * A DAG with several roots or several sinks, and any DAG under
- * OPARA_PARALLEL_EXPLICIT, is instead assembled node by node with exactly the
- * dependencies the capture would record (previous operator of the same stream in
- * launch-queue order + every cross-stream predecessor), plus one trailing node without
- * work that joins the sinks when there are several; the streams are then only checked,
- * not used.
- * OPARA_SEQUENTIAL captures the same kernels with the same launch shapes on
- * hip_streams[0] alone in default topological order (the baseline: paper Sec. 5.1,
- * default sequential graph).
- * Errors: ESTATE if assign/order were not called (parallel modes), EINVAL, EHIP (a
- * running capture is ended and the partial graph destroyed before returning).
+ * Graph capture (paper Sec. 3.4): one executable graph that holds every operator,
+ * with exactly these dependencies: the previous operator of the same stream in
+ * launch-queue order, plus every cross-stream predecessor (what recording one event
+ * after each producer with a cross-stream consumer and waiting once per such producer
+ * on the consumer's stream yields).  Nothing executes.
+ *   OPARA_PARALLEL          assembles that graph node by node.  hip_streams[0..n_streams)
+ *                           (hipStream_t handles supplied by the caller, at least as many
+ *                           as opara_assign_streams reported, all distinct) are checked
+ *                           but carry no work.  A DAG with several sinks gets one
+ *                           trailing node without work that joins them.
+ *   OPARA_PARALLEL_CAPTURE  obtains the same graph the paper's way: the streams are put
+ *                           into one stream capture, every operator is launched on its
+ *                           stream in launch-queue order with event record / wait on
+ *                           the cross-stream edges, all streams join hip_streams[0].
+ *                           Only for DAGs with one root and one sink (EUNSUPPORTED
+ *                           otherwise); with the ROCm 7.0 runtime, capturing DAGs whose
+ *                           streams wait on each other in both directions crashed the
+ *                           host process, which is why this is not the default.
+ *   OPARA_SEQUENTIAL        captures the same kernels with the same launch shapes on
+ *                           hip_streams[0] alone in default topological order (the
+ *                           baseline: paper Sec. 5.1, default sequential graph).
+ * Errors: ESTATE if assign/order were not called (parallel modes), EINVAL,
+ * EUNSUPPORTED, EHIP (a running capture is ended and the partial graph destroyed).
  */
 int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams,
                   int32_t mode, opara_exec **out);

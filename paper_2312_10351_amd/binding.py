@@ -14,7 +14,7 @@ OP_TYPE_IDS = dict(conv2d=CONV2D, gemm=GEMM, bgemm=BGEMM, maxpool=MAXPOOL, avgpo
                    gelu=GELU, relu=RELU, add=ADD)
 CLASS_DEFAULT, MEM, COMP = -1, 0, 1
 F32, F16 = 0, 1
-PARALLEL, SEQUENTIAL, PARALLEL_EXPLICIT = 0, 1, 2
+PARALLEL, SEQUENTIAL, PARALLEL_CAPTURE = 0, 1, 2
 FLAG_RELU, FLAG_B_KMAJOR = 1, 2
 (ORDER_ALG2, ORDER_ALG2_COMP_FIRST, ORDER_LEAST_DEMAND, ORDER_MOST_DEMAND, ORDER_TOPO,
  ORDER_LEVEL) = range(6)

@@ -40,7 +40,7 @@ void destroy_exec(opara_exec *e) {
 
 extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams, int32_t mode,
                              opara_exec **out) {
-  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_EXPLICIT)) {
+  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_CAPTURE)) {
     set_error("opara_capture: bad argument");
     return OPARA_EINVAL;
   }
@@ -74,12 +74,16 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
     n_roots += (g->pred_off[v + 1] == g->pred_off[v]);
     n_sinks += (g->succ_off[v + 1] == g->succ_off[v]);
   }
-  // Stream capture serves DAGs with one root and one sink.  Any other DAG, or an
-  // explicit request, is built node by node with the very same dependencies: the
-  // previous operator of the same stream in launch-queue order plus every
-  // cross-stream predecessor, closed by one leaf node without work if there are several
-  // sinks.
-  if (mode == OPARA_PARALLEL_EXPLICIT || (mode == OPARA_PARALLEL && (n_roots > 1 || n_sinks > 1))) {
+  if (mode == OPARA_PARALLEL_CAPTURE && (n_roots > 1 || n_sinks > 1)) {
+    set_error("opara_capture: stream capture serves DAGs with one root and one sink (this one has %d / %d)",
+              n_roots, n_sinks);
+    delete e;
+    return OPARA_EUNSUPPORTED;
+  }
+  // Default: the graph is assembled node by node.  Each node depends on the previous
+  // operator of its stream in launch-queue order and on every cross-stream predecessor;
+  // one leaf node without work closes a DAG with several sinks.
+  if (mode == OPARA_PARALLEL) {
     std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(ns, nullptr), deps;
     hipGraphNode_t leaf = nullptr;
     HIP_TRY(hipGraphCreate(&e->graph, 0));
