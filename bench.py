@@ -18,6 +18,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
+# a streaming kernel of known size (profiles/igemm_f16_direct4_hbm_traffic.md).
+MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): 1493 * 1024}
+
+
 def percentile(a, q):
     return float(np.percentile(np.asarray(a), q))
 
@@ -122,7 +127,7 @@ def bench_config(index, steps, warmup, with_kernels):
                 peak = MFMA_FLOPS[wl.dtype] / 1e12
                 ach = e["flops"] / (e["time_us"] * 1e-6) / 1e12
                 kern = dict(kernel=dom, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
-                            traffic=None)
+                            traffic=MEASURED_TRAFFIC_BYTES.get((wl.name, dom)))
             else:
                 peak = HBM_BYTES_PER_S / 1e9
                 ach = e["bytes"] / (e["time_us"] * 1e-6) / 1e9
