@@ -80,15 +80,16 @@ typedef struct {
 
 /*
  * Shape parameters.  Which fields an operator reads:
- *   CONV2D            h_in,w_in,c_in, h_out,w_out,c_out, kh,kw,sh,sw,ph,pw, flags(RELU).
+ *   CONV2D            h_in,w_in,c_in, h_out,w_out,c_out, kh,kw,sh,sw,ph,pw, flags(RELU), batch
+ *                     (images, 0 = 1; activations are then [batch][H][W][C]).
  *                     y[oh][ow][co] = bias[co] + sum x[oh*sh+i-ph][ow*sw+j-pw][ci]*w[co][i][j][ci],
  *                     zero padding, cross-correlation, floor output size.
  *   GEMM              m,n,k, flags(RELU).  Y[m][n] = X[m][k].W + bias + sum of inputs[1..] viewed [m][n].
  *   BGEMM             batch,m,n,k, alpha, the six strides (in elements), flags(B_KMAJOR).
  *                     C_b[m][n] = alpha * A_b[m][k] . B_b ; A = inputs[0], B = inputs[1].
- *   MAXPOOL/AVGPOOL   h_in,w_in,c_in,h_out,w_out, kh,kw,sh,sw,ph,pw.  Max pads with -inf;
+ *   MAXPOOL/AVGPOOL   h_in,w_in,c_in,h_out,w_out, kh,kw,sh,sw,ph,pw, batch.  Max pads with -inf;
  *                     average pads with zero and always divides by kh*kw.
- *   GAVGPOOL          h_in,w_in,c_in -> [c_in].
+ *   GAVGPOOL          h_in,w_in,c_in, batch -> [batch][c_in].
  *   CONCAT            m rows; in_cols[i] columns from input i; n = sum of in_cols.
  *   LAYERNORM/SOFTMAX m rows, n cols, eps (LayerNorm: biased variance, gamma 1, beta 0),
  *                     applied to the SUM of all inputs, each viewed [m][n].

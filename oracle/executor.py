@@ -43,6 +43,13 @@ def _view(buf, shape):
     return flat[:n].reshape(shape)
 
 
+_IMAGE_OPS = ("conv2d", "maxpool", "avgpool", "gavgpool")
+
+
+def is_image_op(op):
+    return op.type in _IMAGE_OPS or (op.type == "concat" and op.params.get("axis") == 0)
+
+
 def run_op(op, ins, wts):
     """ins: fp64 arrays already viewed in op.in_shapes; returns fp64 result."""
     p, t = op.params, op.type
@@ -92,12 +99,17 @@ def run_dag(wl, order=None, keep=None):
     out = {}
     for v in order:
         op = wl.ops[v]
+        batched = wl.batch > 1 and is_image_op(op)     # image operators act on each image alone
         ins = []
         for u, shp in zip(op.inputs, op.in_shapes):
             src = wl.ext_inputs[-u - 1] if u < 0 else out[u]
-            ins.append(_view(src, shp).astype(np.float64))
-        y = run_op(op, ins, wl.weights.get(v))
-        assert y.shape == tuple(op.out_shape), (op.name, y.shape, op.out_shape)
+            ins.append(_view(src, ((wl.batch,) + tuple(shp)) if batched else shp).astype(np.float64))
+        if batched:
+            y = np.stack([run_op(op, [a[b] for a in ins], wl.weights.get(v)) for b in range(wl.batch)])
+            assert y.shape[1:] == tuple(op.out_shape), (op.name, y.shape, op.out_shape)
+        else:
+            y = run_op(op, ins, wl.weights.get(v))
+            assert y.shape == tuple(op.out_shape), (op.name, y.shape, op.out_shape)
         out[v] = y.astype(st)
         for u in op.inputs:
             if u >= 0:

@@ -1,12 +1,13 @@
 """Launch-order and interference ablations over the same kernels and graphs.
 
-  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300]
+  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32]
 
 Part 1 (paper Sec. 2.3, "GPU blocking"): the parallel graph is captured with each
 launch-order policy of opara_order_launch_policy and replayed; only the queue differs.
 Part 2 (paper Sec. 2.3, "Performance interference"): two independent operators are
 replayed alone, back to back on one stream, and side by side on two streams, for a
 compute-intensive + memory-intensive pair and for two pairs of one class.
+Part 3 (paper Sec. 5.2): batch sweep of the Inception-v3-like DAG.
 Prints one JSON object per line.
 """
 import argparse
@@ -48,6 +49,24 @@ def order_ablation(index, replays):
         for pid, name in enumerate(B.ORDER_POLICY_NAMES):
             row[name + "_us"] = replay_latency(s, s.capture(B.PARALLEL, policy=pid), replays)
         return row
+    finally:
+        s.close()
+
+
+def batch_sweep(batch, replays):
+    """Inception-v3-like DAG at a given batch size: latency and images/s of the parallel and
+    the sequential graph (paper Sec. 5.2, throughput under different batch sizes)."""
+    from . import binding as B
+    from .runtime import Session
+    from workloads import inception_v3_like
+    wl = inception_v3_like(batch=batch)
+    s = Session(wl)
+    try:
+        seq = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
+        par = replay_latency(s, s.capture(B.PARALLEL), replays)
+        return {"ablation": "batch_sweep", "workload": wl.name, "batch": batch, "sequential_us": seq,
+                "parallel_us": par, "speedup": seq / par, "parallel_images_per_s": batch * 1e6 / par,
+                "sequential_images_per_s": batch * 1e6 / seq}
     finally:
         s.close()
 
@@ -97,7 +116,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="0,1,2,3,4")
     ap.add_argument("--replays", type=int, default=300)
+    ap.add_argument("--batches", default="1,2,4,8,16,32")
     a = ap.parse_args()
+    for bsz in [int(x) for x in a.batches.split(",") if x]:
+        print(json.dumps(batch_sweep(bsz, max(50, a.replays // 3))), flush=True)
     for idx in [int(x) for x in a.configs.split(",") if x]:
         print(json.dumps(order_ablation(idx, a.replays)), flush=True)
     for pair in (("comp", "mem"), ("mem", "mem"), ("comp", "comp")):

@@ -19,6 +19,8 @@ struct IgemmArgs {
   int32_t M, N, K;
   int32_t gather;
   int32_t H, W, Cin, Wo, kh, kw, sh, sw, ph, pw;
+  int32_t HoWo;                 // output pixels per image; row m belongs to image m / HoWo
+  int64_t img_stride;           // elements between consecutive input images (H*W*Cin)
   int64_t lda, ldb, ldy;        // row strides in elements
   int64_t a_bs, b_bs, y_bs;     // batch strides in elements (blockIdx.z)
   int32_t b_kmajor;             // second operand stored [K][N]
@@ -31,12 +33,13 @@ struct PoolArgs {
   void *y;
   int32_t H, W, C, Ho, Wo, kh, kw, sh, sw, ph, pw;
   int32_t is_avg;
+  int32_t B;                    // images
 };
 
 struct GapArgs {
   const void *x;
   void *y;
-  int32_t HW, C;
+  int32_t HW, C;              // per image; blockIdx.y is the image
 };
 
 struct RowArgs {               // LayerNorm / softmax over rows of the summed inputs

@@ -69,13 +69,16 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
   constexpr int RSTEP = NT / 4;
 
   int ih0[CHX], iw0[CHX];
+  const T *ximg[CHX];
   if (a.gather) {
 #pragma unroll
     for (int i = 0; i < CHX; ++i) {
       const int m = m0 + row0 + i * RSTEP;
-      const int oh = m / a.Wo, ow = m - oh * a.Wo;
+      const int img = m / a.HoWo, pix = m - img * a.HoWo;
+      const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
       ih0[i] = oh * a.sh - a.ph;
       iw0[i] = ow * a.sw - a.pw;
+      ximg[i] = x + (int64_t)img * a.img_stride;
     }
   }
   // running decomposition of this thread's K position (vector path, gather only)
@@ -105,7 +108,7 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
           } else {
             const int ih = ih0[i] + g_r, iw = iw0[i] + g_s;
             if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-              v = *(const V *)(x + ((int64_t)ih * a.W + iw) * a.Cin + g_ci);
+              v = *(const V *)(ximg[i] + ((int64_t)ih * a.W + iw) * a.Cin + g_ci);
           }
         }
       } else {
@@ -120,7 +123,7 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
                 const int ci = k % a.Cin, rs = k / a.Cin;
                 const int ih = ih0[i] + rs / a.kw, iw = iw0[i] + rs % a.kw;
                 if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-                  v[e] = x[((int64_t)ih * a.W + iw) * a.Cin + ci];
+                  v[e] = ximg[i][((int64_t)ih * a.W + iw) * a.Cin + ci];
               }
             }
           }
@@ -311,7 +314,7 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
   // the registers are written to LDS.  (A load guarded by a branch makes the compiler
   // wait for it right inside the branch, which serialises the whole prefetch.)
   int ih0[CHX], iw0[CHX];
-  const T *xrow[CHX];
+  const T *xrow[CHX], *ximg[CHX];
   const T *wrow[CHW];
   unsigned rowmask = 0;                       // bit i: pixel row i valid, bit 8+i: weight row i valid
 #pragma unroll
@@ -321,9 +324,11 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
     const int mm = ok ? m : 0;
     rowmask |= (unsigned)ok << i;
     xrow[i] = x + (int64_t)mm * a.lda;
-    const int oh = mm / a.Wo, ow = mm - oh * a.Wo;   // used only when gathering
+    const int img = mm / a.HoWo, pix = mm - img * a.HoWo;   // used only when gathering
+    const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
     ih0[i] = oh * a.sh - a.ph;
     iw0[i] = ow * a.sw - a.pw;
+    ximg[i] = x + (int64_t)img * a.img_stride;
   }
 #pragma unroll
   for (int i = 0; i < CHW; ++i) {
@@ -358,7 +363,7 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
         const bool inb = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
         const int64_t off = inb ? ((int64_t)ih * a.W + iw) * a.Cin + pos.ci : 0;
         if (!inb) mask &= ~(1u << i);
-        xr[i] = *(const V *)(x + off);
+        xr[i] = *(const V *)(ximg[i] + off);
       }
       kpos_advance(pos, BKE, a.Cin, a.kw);
     }
@@ -490,7 +495,7 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
   // is waited for inside the branch).  Results of clamped rows are never stored; K
   // tails are cancelled by zeroing the weight fragment, padding taps by zeroing the
   // pixel fragment.
-  const T *wrow[2], *xrow[2];
+  const T *wrow[2], *xrow[2], *ximg[2];
   int ih0[2], iw0[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -501,9 +506,11 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
   for (int j = 0; j < 2; ++j) {
     const int m = min(m0 + j * 16 + r16, a.M - 1);
     xrow[j] = x + (int64_t)m * a.lda;
-    const int oh = m / a.Wo, ow = m - oh * a.Wo;        // only meaningful when gathering
+    const int img = m / a.HoWo, pix = m - img * a.HoWo;   // only meaningful when gathering
+    const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
     ih0[j] = oh * a.sh - a.ph;
     iw0[j] = ow * a.sw - a.pw;
+    ximg[j] = x + (int64_t)img * a.img_stride;
   }
   KPos pos = {0, 0, 0};
   if (a.gather && ds_begin < ds_end) {
@@ -543,7 +550,7 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
             const int ih = ih0[j] + pc.r, iw = iw0[j] + pc.s;
             inb[u][j][c] = kok[u][c] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
             const int64_t off = inb[u][j][c] ? ((int64_t)ih * a.W + iw) * a.Cin + pc.ci : 0;
-            xb[u][j][c] = *(const V *)(x + off);
+            xb[u][j][c] = *(const V *)(ximg[j] + off);
           }
           if (c == 0) kpos_advance(pc, VE, a.Cin, a.kw);
         }
@@ -665,11 +672,12 @@ template <typename T, int VE>
 __device__ __forceinline__ void pool_body(const PoolArgs &a) {
   const int cch = a.C / VE;
   const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (item >= (int64_t)a.Ho * a.Wo * cch) return;
+  if (item >= (int64_t)a.B * a.Ho * a.Wo * cch) return;
   const int cc = (int)(item % cch);
-  const int pix = (int)(item / cch);
-  const int ow = pix % a.Wo, oh = pix / a.Wo;
-  const T *__restrict__ x = (const T *)a.x + cc * VE;
+  const int pix = (int)(item / cch);                   // output pixel over all images
+  const int img = pix / (a.Ho * a.Wo), ipix = pix - img * (a.Ho * a.Wo);
+  const int ow = ipix % a.Wo, oh = ipix / a.Wo;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)img * a.H * a.W * a.C + cc * VE;
   const float fill = a.is_avg ? 0.f : -INFINITY;
   float acc[VE];
 #pragma unroll
@@ -723,7 +731,7 @@ __device__ __forceinline__ void gap_body(const GapArgs &a) {
   __shared__ float part[4][64];
   const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
-  const T *__restrict__ x = (const T *)a.x;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.y * a.HW * a.C;
   float s = 0.f;
   if (c < a.C) {
     int p = slice;
@@ -737,7 +745,7 @@ __device__ __forceinline__ void gap_body(const GapArgs &a) {
   part[slice][cl] = s;
   __syncthreads();
   if (slice == 0 && c < a.C)
-    ((T *)a.y)[c] = (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW);
+    ((T *)a.y)[(int64_t)blockIdx.y * a.C + c] = (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW);
 }
 
 // ---------------------------------------------------------------------------------

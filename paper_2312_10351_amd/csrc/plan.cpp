@@ -55,8 +55,12 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     if (p.h_out != (p.h_in + 2 * p.ph - p.kh) / p.sh + 1 || p.w_out != (p.w_in + 2 * p.pw - p.kw) / p.sw + 1 ||
         p.h_out <= 0 || p.w_out <= 0)
       return fail("convolution output size does not match floor((in + 2*pad - k)/stride) + 1", op);
+    if (p.batch < 0 || p.batch > 4096) return fail("bad image batch", op);
+    const int images = p.batch > 0 ? p.batch : 1;
     a.w = op.weight;
-    a.M = p.h_out * p.w_out;
+    a.HoWo = p.h_out * p.w_out;
+    a.img_stride = (int64_t)p.h_in * p.w_in * p.c_in;
+    a.M = images * a.HoWo;
     a.N = p.c_out;
     a.K = p.kh * p.kw * p.c_in;
     a.gather = !(p.kh == 1 && p.kw == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0);
@@ -70,6 +74,7 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     a.w = op.weight;
     a.M = p.m; a.N = p.n; a.K = p.k;
     a.lda = p.k; a.ldb = p.k; a.ldy = p.n;
+    a.HoWo = p.m; a.Wo = 1;
     a.n_extra = op.n_inputs - 1;
     for (int i = 0; i < a.n_extra; ++i) a.extra[i] = in[i + 1];
     vec = (p.k % ve == 0);
@@ -82,6 +87,7 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     a.w = in[1];
     a.M = p.m; a.N = p.n; a.K = p.k;
     a.lda = p.a_row_stride; a.ldb = p.b_row_stride; a.ldy = p.c_row_stride;
+    a.HoWo = p.m; a.Wo = 1;
     a.a_bs = p.a_batch_stride; a.b_bs = p.b_batch_stride; a.y_bs = p.c_batch_stride;
     a.b_kmajor = (p.flags & OPARA_FLAG_B_KMAJOR) ? 1 : 0;
     if (a.b_kmajor ? p.b_row_stride < p.n : p.b_row_stride < p.k) return fail("bad batched GEMM strides", op);
@@ -159,9 +165,11 @@ int plan_pool(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
   a.H = p.h_in; a.W = p.w_in; a.C = p.c_in; a.Ho = p.h_out; a.Wo = p.w_out;
   a.kh = p.kh; a.kw = p.kw; a.sh = p.sh; a.sw = p.sw; a.ph = p.ph; a.pw = p.pw;
   a.is_avg = op.op_type == OPARA_AVGPOOL;
+  if (p.batch < 0 || p.batch > 4096) return fail("bad image batch", op);
+  a.B = p.batch > 0 ? p.batch : 1;
   const bool vec = (p.c_in % ve == 0) && aligned16(a.x) && aligned16(a.y);
   out->kernel = f16 ? (vec ? K_pool_f16_vec : K_pool_f16_scalar) : (vec ? K_pool_f32_vec : K_pool_f32_scalar);
-  const int64_t items = (int64_t)p.h_out * p.w_out * (vec ? p.c_in / ve : p.c_in);
+  const int64_t items = (int64_t)a.B * p.h_out * p.w_out * (vec ? p.c_in / ve : p.c_in);
   out->gx = cdiv(items, 256); out->gy = out->gz = 1; out->block = 256;
   out->args.pool = a;
   return OPARA_OK;
@@ -174,7 +182,8 @@ int plan_gap(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
   std::memset(&a, 0, sizeof a);
   a.x = in[0]; a.y = op.out; a.HW = p.h_in * p.w_in; a.C = p.c_in;
   out->kernel = op.dtype == OPARA_F16 ? K_gap_f16 : K_gap_f32;
-  out->gx = cdiv(p.c_in, 64); out->gy = out->gz = 1; out->block = 256;
+  if (p.batch < 0 || p.batch > 4096) return fail("bad image batch", op);
+  out->gx = cdiv(p.c_in, 64); out->gy = p.batch > 0 ? p.batch : 1; out->gz = 1; out->block = 256;
   out->args.gap = a;
   return OPARA_OK;
 }

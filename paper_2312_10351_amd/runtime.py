@@ -74,8 +74,9 @@ class Session:
                     if u < 0:
                         users.setdefault(-u - 1, []).append(op)
             for slot, a in enumerate(wl.ext_inputs):
-                if a.ndim == 3 and a.shape[0] % ve and all(o.type == "conv2d" for o in users.get(slot, [])):
-                    self.ext_pad[slot] = (a.shape[0] + ve - 1) // ve * ve
+                chans = a.shape[-3] if a.ndim >= 3 else 0
+                if a.ndim >= 3 and chans % ve and all(o.type == "conv2d" for o in users.get(slot, [])):
+                    self.ext_pad[slot] = (chans + ve - 1) // ve * ve
         self.ext_dev = [self._upload(self._to_physical_input(a, self.ext_pad.get(i))) for i, a in enumerate(wl.ext_inputs)]
         self.out_dev = []
         self.w_dev, self.b_dev = {}, {}
@@ -107,7 +108,7 @@ class Session:
                 self.b_dev[op.id] = self._upload(b.astype(np.float32))
                 d.weight = self._ptr(self.w_dev[op.id])
                 d.bias = self._ptr(self.b_dev[op.id])
-            out = self._alloc(int(np.prod(op.out_shape)))
+            out = self._alloc(int(np.prod(op.out_shape)) * (wl.batch if _is_image(op) else 1))
             self.out_dev.append(out)
             d.out = self._ptr(out)
             descs.append(d)
@@ -138,11 +139,11 @@ class Session:
 
     @staticmethod
     def _to_physical_input(a, pad_to=None):
-        if a.ndim != 3:
+        if a.ndim < 3:
             return a
-        hwc = np.transpose(a, (1, 2, 0))
+        hwc = np.moveaxis(a, -3, -1)                  # [..., C, H, W] -> [..., H, W, C]
         if pad_to:
-            hwc = np.concatenate([hwc, np.zeros(hwc.shape[:2] + (pad_to - hwc.shape[2],), dtype=a.dtype)], axis=2)
+            hwc = np.concatenate([hwc, np.zeros(hwc.shape[:-1] + (pad_to - hwc.shape[-1],), dtype=a.dtype)], axis=-1)
         return np.ascontiguousarray(hwc)
 
     def _fill_params(self, op, p):
@@ -150,6 +151,7 @@ class Session:
         if t in ("conv2d", "maxpool", "avgpool", "gavgpool"):
             p.c_in, p.h_in, p.w_in = op.in_shapes[0]
             p.c_out, p.h_out, p.w_out = op.out_shape
+            p.batch = self.wl.batch
             for k in ("kh", "kw", "sh", "sw", "ph", "pw"):
                 if k in q:
                     setattr(p, k, q[k])
@@ -175,7 +177,7 @@ class Session:
                 p.flags |= B.FLAG_B_KMAJOR
         elif t == "concat":
             if q["axis"] == 0:
-                p.m = op.out_shape[1] * op.out_shape[2]
+                p.m = op.out_shape[1] * op.out_shape[2] * self.wl.batch
                 cols = [s[0] for s in op.in_shapes]
             else:
                 p.m = op.out_shape[0]
@@ -264,6 +266,8 @@ class Session:
         a = self.out_dev[op_id].cpu().numpy()
         if _is_image(op):
             c, h, w = op.out_shape
+            if self.wl.batch > 1:
+                return np.ascontiguousarray(np.transpose(a.reshape(self.wl.batch, h, w, c), (0, 3, 1, 2)))
             return np.ascontiguousarray(np.transpose(a.reshape(h, w, c), (2, 0, 1)))
         return a.reshape(op.out_shape)
 

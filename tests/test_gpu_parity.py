@@ -159,6 +159,16 @@ def test_random_small_dags(seed, dtype):
     run_modes(wl, modes=("par",), outlier_frac=1e-3)
 
 
+@pytest.mark.parametrize("builder,kw", [
+    (inception_block, dict(batch=3, random_bias=True)), (inception_block, dict(batch=5, dtype="f16")),
+    (googlenet_like, dict(batch=2, he_init=True)), (inception_v3_like, dict(batch=4, he_init=True))])
+def test_image_batches(builder, kw):
+    """Batch > 1 (batch sweep of the paper's Sec. 5.2): [B][H][W][C] activations, M = B*H*W rows."""
+    wl = builder(**kw)
+    sinks = run_modes(wl, modes=("seq", "par"))
+    assert sinks["seq"] == sinks["par"]
+
+
 def test_random_wide_dag_full_size():
     wl = random_wide_dag()
     ref = executor.run_dag(wl)

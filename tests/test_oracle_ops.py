@@ -228,3 +228,18 @@ def test_executor_fp16_storage_and_prefix_views():
             assert np.abs(s - 1).max() <= op.out_shape[1] * 2.0 ** -11
     with pytest.raises(ValueError):
         executor.kahn_order(2, [(0, 1), (1, 0)])
+
+
+def test_executor_batch_is_per_image():
+    """With a batch, image operators act on every image alone and the FC sees one row per image."""
+    from workloads import googlenet_like
+    from workloads.dag import Workload
+    wl = inception_block(batch=3, random_bias=True)
+    out = executor.run_dag(wl)
+    for b in range(3):
+        one = Workload(wl.name, wl.dtype, wl.ops, [wl.ext_inputs[0][b]], wl.weights, wl.seed, 1)
+        ref = executor.run_dag(one)
+        assert all(out[v][b].tobytes() == ref[v].tobytes() for v in ref)
+    g = googlenet_like(batch=2, he_init=True)
+    og = executor.run_dag(g, keep=g.sinks())
+    assert og[80].shape == (2, 1000) and not np.array_equal(og[80][0], og[80][1])

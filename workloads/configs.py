@@ -19,8 +19,8 @@ CONFIG_NAMES = ("inception_block", "googlenet_like", "inception_v3_like",
 class Builder:
     """Tiny DAG builder: appends operators, tracks output shapes."""
 
-    def __init__(self, name, dtype):
-        self.name, self.dtype = name, dtype
+    def __init__(self, name, dtype, batch=1):
+        self.name, self.dtype, self.batch = name, dtype, batch
         self.ops = []
         self.ext_shapes = []
 
@@ -76,7 +76,8 @@ class Builder:
     def build(self, seed, random_bias=False, w_std=0.02, he_init=False):
         rng = np.random.Generator(np.random.PCG64(seed))
         npdt = np.float32 if self.dtype == "f32" else np.float16
-        ext = [rng.standard_normal(s, dtype=np.float32).astype(npdt) for s in self.ext_shapes]
+        lead = lambda s: ((self.batch,) + s) if (self.batch > 1 and len(s) == 3) else s
+        ext = [rng.standard_normal(lead(s), dtype=np.float32).astype(npdt) for s in self.ext_shapes]
         weights = {}
         for op in self.ops:
             p = op.params
@@ -94,7 +95,7 @@ class Builder:
             else:
                 b = np.zeros(nb, dtype=np.float32)
             weights[op.id] = {"w": w.astype(npdt), "b": b.astype(npdt)}
-        return Workload(self.name, self.dtype, self.ops, ext, weights, seed)
+        return Workload(self.name, self.dtype, self.ops, ext, weights, seed, self.batch)
 
 
 def _inception(b, x, c1, c3r, c3, c5r, c5, pp, tag):
@@ -109,8 +110,8 @@ def _inception(b, x, c1, c3r, c3, c5r, c5, pp, tag):
     return b.concat_c([b1, b2, b3, b4], name=f"{tag}.cat")
 
 
-def inception_block(seed=BASE_SEED + 0, dtype="f32", random_bias=False):
-    b = Builder("inception_block", dtype)
+def inception_block(seed=BASE_SEED + 0, dtype="f32", random_bias=False, batch=1):
+    b = Builder("inception_block", dtype, batch)
     x = b.ext((64, 28, 28))
     _inception(b, x, 16, 24, 32, 8, 16, 16, "blk")
     return b.build(seed, random_bias)
@@ -125,8 +126,8 @@ GOOGLENET_WIDTHS = {  # (1x1, 3x3-reduce, 3x3, 5x5-reduce, 5x5, pool-proj)
 }
 
 
-def googlenet_like(seed=BASE_SEED + 1, dtype="f16", he_init=False):
-    b = Builder("googlenet_like", dtype)
+def googlenet_like(seed=BASE_SEED + 1, dtype="f16", he_init=False, batch=1):
+    b = Builder("googlenet_like", dtype, batch)
     x = b.ext((3, 224, 224))
     x = b.conv(x, 64, 7, stride=2, pad=3, name="stem.conv7x7")
     x = b.pool("maxpool", x, 3, 2, 1, name="stem.pool1")
@@ -142,12 +143,12 @@ def googlenet_like(seed=BASE_SEED + 1, dtype="f16", he_init=False):
     for tag in ("5a", "5b"):
         x = _inception(b, x, *GOOGLENET_WIDTHS[tag], tag)
     x = b.gavgpool(x, name="gap")
-    b.gemm(x, 1, 1024, 1000, name="fc")
+    b.gemm(x, batch, 1024, 1000, name="fc")
     return b.build(seed, he_init=he_init)
 
 
-def inception_v3_like(seed=BASE_SEED + 2, dtype="f16", he_init=False):
-    b = Builder("inception_v3_like", dtype)
+def inception_v3_like(seed=BASE_SEED + 2, dtype="f16", he_init=False, batch=1):
+    b = Builder("inception_v3_like", dtype, batch)
     x = b.ext((3, 299, 299))
     x = b.conv(x, 32, 3, stride=2, name="stem.1")
     x = b.conv(x, 32, 3, name="stem.2")
@@ -211,7 +212,7 @@ def inception_v3_like(seed=BASE_SEED + 2, dtype="f16", he_init=False):
         b4 = b.conv(b4, 192, 1, name=f"{t}.b4.1x1")
         x = b.concat_c([b1, b2a, b2b, b3a, b3b, b4], name=f"{t}.cat")
     x = b.gavgpool(x, name="gap")
-    b.gemm(x, 1, 2048, 1000, name="fc")
+    b.gemm(x, batch, 2048, 1000, name="fc")
     return b.build(seed, he_init=he_init)
 
 

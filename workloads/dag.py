@@ -2,7 +2,9 @@
 
 Logical tensor conventions (both executors agree on these; physical layouts are
 each executor's own business):
-  * CNN activations: [C, H, W] (batch 1).
+  * CNN activations: [C, H, W] per image; with Workload.batch = B > 1 every image
+    tensor carries a leading batch axis [B, C, H, W] while operator records keep the
+    per-image shapes.
   * matrices: [R, C] row-major.
   * an operator views each input as the leading prefix of its producer's flat
     row-major buffer, reshaped to the input shape the operator states.
@@ -36,6 +38,7 @@ class Workload:
     ext_inputs: List[np.ndarray]      # already rounded to dtype
     weights: Dict[int, Dict[str, np.ndarray]]  # op id -> {"w": ..., "b": ...}, rounded to dtype
     seed: int = 0
+    batch: int = 1                    # images per pass; image tensors are then [batch, C, H, W]
 
     @property
     def np_dtype(self):
