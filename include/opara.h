@@ -235,6 +235,57 @@ int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams,
  */
 int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violations);
 
+/*
+ * Persistent executor: the paper's goal (Sec. 2.2, 3.1: keep the GPU's units busy by
+ * running independent operators side by side, with as little synchronisation cost
+ * `t_overhead` as possible, Eq. 3) reached without streams.  The captured graph holds ONE
+ * kernel.  The (operator, tile) work items of the launch queue (the queue of the last
+ * opara_order_launch / _policy call, so Alg. 2 still decides which operators meet on the
+ * chip) are dealt round-robin to its workgroups; an item starts as soon as every
+ * predecessor of its operator has finished all its tiles.  The workgroup that finishes
+ * an operator's last tile raises the operator's completion flags in device memory;
+ * activations are written and read with device-coherent accesses, so a dependency costs
+ * one flag hand-off (about half a microsecond) instead of a graph-node boundary, and
+ * independent operators overlap at tile granularity.  Stream assignment plays no part.
+ *
+ * workspace: device memory, caller-owned, 256-byte aligned, at least
+ * opara_persistent_workspace_bytes() bytes, exclusively this executor's until it is
+ * destroyed; capture writes the operator records into it with a blocking copy.
+ * n_workgroups: 0 = as many as the device holds at once (two per compute unit for DAGs up
+ * to a few hundred operators); a smaller positive count is honoured, a larger one is cut
+ * to that maximum, because every workgroup must be resident.  Items follow a topological
+ * order, so the holder of the lowest unfinished item can always run.
+ * Operators planned on 8- or 16-wavefront contraction kernels run the 4-wavefront form
+ * (same tiles, longer K walk per wavefront): results may differ from the other modes in
+ * the last bits, and are identical from replay to replay.
+ * Every wait inside the kernel is bounded (spin_limit polls, default 2^22); a wait that
+ * runs out makes all workgroups leave and sets a sticky error word (1 + queue position
+ * of the waiting operator), which opara_persistent_status reads after synchronising
+ * `hip_stream`.  opara_persistent_reset synchronises the stream, clears counters, flags
+ * and error word and sets the spin limit (0 = default).  Replays of one executor must not
+ * overlap (same stream, or ordered by the caller).
+ * Errors: ESTATE without a launch queue, EINVAL (workspace), EUNSUPPORTED (more than 8
+ * predecessors or 65535 tiles per operator, more than about 2,600 operators, mixed
+ * element types), EHIP.
+ * Replay with opara_replay, destroy with opara_exec_destroy.
+ */
+int opara_persistent_workspace_bytes(const opara_dag *g, uint64_t *bytes);
+int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t workspace_bytes,
+                             int32_t n_workgroups, opara_exec **out);
+int opara_persistent_status(opara_exec *e, void *hip_stream, uint32_t *error_word);
+/* Work items and workgroups of a persistent executor (host int32 each). */
+int opara_persistent_info(const opara_exec *e, int32_t *n_items, int32_t *n_workgroups);
+/*
+ * Timeline of the following replays (tracing; the one kernel hides the operators from
+ * a profiler).  trace: device memory, caller-owned, 8-byte aligned, 32 bytes per work
+ * item, or NULL to switch tracing off.  Work item i (launch-queue order, tiles of an
+ * operator consecutive) gets four uint64: the 100 MHz device clock when its workgroup
+ * began looking it up, when its predecessors were complete, when its body had finished,
+ * and (queue position << 32 | workgroup).  Synchronises `hip_stream`.
+ */
+int opara_persistent_set_trace(opara_exec *e, void *hip_stream, void *trace, uint64_t trace_bytes);
+int opara_persistent_reset(opara_exec *e, void *hip_stream, uint32_t spin_limit);
+
 /* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
 int opara_replay(opara_exec *e, void *hip_stream);
 

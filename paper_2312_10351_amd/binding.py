@@ -62,6 +62,8 @@ class Demand(C.Structure):
 
 EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_order_launch_policy", "opara_sync_edges",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
+           "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
+           "opara_persistent_reset", "opara_persistent_info", "opara_persistent_set_trace",
            "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
@@ -90,6 +92,12 @@ def load():
     lib.opara_num_ops.argtypes = [vp]
     lib.opara_capture.argtypes = [vp, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(vp)]
     lib.opara_replay.argtypes = [vp, vp]
+    lib.opara_persistent_workspace_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
+    lib.opara_capture_persistent.argtypes = [vp, vp, C.c_uint64, C.c_int32, C.POINTER(vp)]
+    lib.opara_persistent_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
+    lib.opara_persistent_reset.argtypes = [vp, vp, C.c_uint32]
+    lib.opara_persistent_info.argtypes = [vp, i32p, i32p]
+    lib.opara_persistent_set_trace.argtypes = [vp, vp, vp, C.c_uint64]
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
     lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
@@ -179,6 +187,39 @@ def opara_capture(dag, stream_handles, mode):
     out = C.c_void_p()
     _check(load().opara_capture(dag, arr, len(stream_handles), mode, C.byref(out)))
     return out
+
+
+def opara_persistent_workspace_bytes(dag):
+    n = C.c_uint64()
+    _check(load().opara_persistent_workspace_bytes(dag, C.byref(n)))
+    return n.value
+
+
+def opara_capture_persistent(dag, workspace_ptr, workspace_bytes, n_workgroups=0):
+    out = C.c_void_p()
+    _check(load().opara_capture_persistent(dag, C.c_void_p(workspace_ptr), workspace_bytes, n_workgroups,
+                                           C.byref(out)))
+    return out
+
+
+def opara_persistent_status(exe, stream_handle):
+    w = C.c_uint32()
+    _check(load().opara_persistent_status(exe, C.c_void_p(stream_handle), C.byref(w)))
+    return w.value
+
+
+def opara_persistent_info(exe):
+    a, b = C.c_int32(), C.c_int32()
+    _check(load().opara_persistent_info(exe, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def opara_persistent_set_trace(exe, stream_handle, trace_ptr, trace_bytes):
+    _check(load().opara_persistent_set_trace(exe, C.c_void_p(stream_handle), C.c_void_p(trace_ptr), trace_bytes))
+
+
+def opara_persistent_reset(exe, stream_handle, spin_limit=0):
+    _check(load().opara_persistent_reset(exe, C.c_void_p(stream_handle), spin_limit))
 
 
 def opara_replay(exe, stream_handle):

@@ -3,6 +3,7 @@
 // queue order, cross-stream dependencies become event record / wait pairs, and the
 // result is instantiated as a single executable graph.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <new>
 #include <vector>
 #include "launch.h"
@@ -13,6 +14,9 @@ struct opara_exec {
   hipGraphExec_t exec = nullptr;
   std::vector<hipEvent_t> events;
   int32_t n_nodes = 0, n_edges = 0;
+  // persistent executor only: caller-owned workspace and the size of its counter block
+  void *workspace = nullptr;
+  int32_t persist_ops = 0, persist_items = 0, persist_workgroups = 0;
 };
 
 using namespace opara;
@@ -235,6 +239,186 @@ extern "C" int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t
 fail:
   if (exec) (void)hipGraphExecDestroy(exec);
   if (graph) (void)hipGraphDestroy(graph);
+  (void)hipGetLastError();
+  return OPARA_EHIP;
+}
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct PersistLayout { size_t done, flags, begin, preds, rec, bytes; };
+
+PersistLayout persist_layout(int32_t n) {
+  PersistLayout l;
+  l.done = align_up(sizeof(PersistHeader), 256);
+  l.flags = align_up(l.done + sizeof(uint32_t) * (size_t)n * kPersistCounterStride, 256);
+  l.begin = align_up(l.flags + sizeof(uint32_t) * (size_t)n * kPersistReplicas * kPersistFlagStride, 256);
+  l.preds = align_up(l.begin + sizeof(int32_t) * ((size_t)n + 1), 256);
+  l.rec = align_up(l.preds + sizeof(PersistPredsLds) * (size_t)n, 256);
+  l.bytes = align_up(l.rec + sizeof(PersistOp) * (size_t)n, 256);
+  return l;
+}
+
+}  // namespace
+
+extern "C" int opara_persistent_workspace_bytes(const opara_dag *g, uint64_t *bytes) {
+  if (!g || !bytes) { set_error("opara_persistent_workspace_bytes: null pointer"); return OPARA_EINVAL; }
+  *bytes = persist_layout(g->n).bytes;
+  return OPARA_OK;
+}
+
+extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t workspace_bytes,
+                                        int32_t n_workgroups, opara_exec **out) {
+  if (!g || !workspace || !out || n_workgroups < 0) { set_error("opara_capture_persistent: bad argument"); return OPARA_EINVAL; }
+  *out = nullptr;
+  if (g->order.empty()) { set_error("opara_capture_persistent: call opara_order_launch first"); return OPARA_ESTATE; }
+  const int32_t n = g->n;
+  const PersistLayout lay = persist_layout(n);
+  if (workspace_bytes < lay.bytes || ((uintptr_t)workspace & 255u)) {
+    set_error("opara_capture_persistent: workspace of %llu bytes (need %llu, 256-byte aligned)",
+              (unsigned long long)workspace_bytes, (unsigned long long)lay.bytes);
+    return OPARA_EINVAL;
+  }
+  const uint32_t lds_bytes = persist_lds_bytes((uint32_t)n);
+  if (lds_bytes > kPersistMaxLds || n > 65535) {
+    set_error("opara_capture_persistent: %d operators exceed the ticket table held in workgroup memory", n);
+    return OPARA_EUNSUPPORTED;
+  }
+  // Records in launch-queue order.
+  std::vector<unsigned char> host(lay.bytes, 0);
+  PersistHeader *hdr = (PersistHeader *)host.data();
+  hdr->spin_limit = kPersistDefaultSpinLimit;
+  hdr->epoch = 1;
+  int32_t *begin = (int32_t *)(host.data() + lay.begin);
+  PersistPredsLds *preds = (PersistPredsLds *)(host.data() + lay.preds);
+  PersistOp *rec = (PersistOp *)(host.data() + lay.rec);
+  std::vector<int32_t> pos_of(n, -1);
+  std::vector<uint32_t> tiles(n, 0);
+  int64_t total = 0;
+  bool f16 = false;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t v = g->order[i];
+    const KernelPlan &p = g->plan[v];
+    const int kid = persist_kernel_id(p.kernel);
+    if (kid < 0) { set_error("opara_capture_persistent: operator %d has no persistent kernel", v); return OPARA_EUNSUPPORTED; }
+    const bool is16 = kernel_is_f16(kid);
+    if (i > 0 && is16 != f16) { set_error("opara_capture_persistent: mixed element types"); return OPARA_EUNSUPPORTED; }
+    f16 = is16;
+    pos_of[v] = i;
+    const int64_t t = (int64_t)p.gx * p.gy * p.gz;
+    if (t < 1 || t > 65535 || total + t > INT32_MAX) { set_error("opara_capture_persistent: work-item count out of range"); return OPARA_EUNSUPPORTED; }
+    tiles[i] = (uint32_t)t;
+    begin[i] = (int32_t)total;
+    total += t;
+    rec[i].kernel = kid + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
+    rec[i].gx = (int32_t)p.gx; rec[i].gy = (int32_t)p.gy; rec[i].gz = (int32_t)p.gz;
+    rec[i].args = p.args;
+    const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
+    if (np > kPersistMaxPreds) { set_error("opara_capture_persistent: operator %d has %d predecessors (limit %d)", v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
+    preds[i].n = (uint16_t)np;
+    preds[i].tiles = (uint16_t)t;
+    for (int32_t j = 0; j < np; ++j) {
+      const int32_t u = pos_of[g->pred[g->pred_off[v] + j]];
+      if (u < 0) { set_error("opara_capture_persistent: launch queue is not topological"); return OPARA_ESTATE; }
+      preds[i].pos[j] = (uint16_t)u;
+    }
+  }
+  begin[n] = (int32_t)total;
+  opara_exec *e = new (std::nothrow) opara_exec();
+  if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
+  {
+    uint32_t wgs = 0;
+    HIP_TRY(persist_max_workgroups(f16, lds_bytes, &wgs));       // all workgroups must be resident
+    if (wgs == 0) { set_error("opara_capture_persistent: the kernel does not fit a compute unit"); goto fail; }
+    if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
+    if ((int64_t)wgs > total) wgs = (uint32_t)total;
+    HIP_TRY(hipMemcpy(workspace, host.data(), lay.bytes, hipMemcpyHostToDevice));
+    PersistArgs pa;
+    unsigned char *ws = (unsigned char *)workspace;
+    pa.hdr = (PersistHeader *)ws;
+    pa.done = (uint32_t *)(ws + lay.done);
+    pa.flags = (uint32_t *)(ws + lay.flags);
+    pa.item_begin = (const int32_t *)(ws + lay.begin);
+    pa.preds = (const PersistPredsLds *)(ws + lay.preds);
+    pa.rec = (const PersistOp *)(ws + lay.rec);
+    pa.n = n;
+    pa.total = (int32_t)total;
+    hipGraphNode_t node = nullptr;
+    HIP_TRY(hipGraphCreate(&e->graph, 0));
+    HIP_TRY(add_persist_node(e->graph, f16, pa, wgs, lds_bytes, &node));
+    HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+    e->n_nodes = 1;
+    e->n_edges = 0;
+    e->workspace = workspace;
+    e->persist_ops = n;
+    e->persist_items = (int32_t)total;
+    e->persist_workgroups = (int32_t)wgs;
+  }
+  *out = e;
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  destroy_exec(e);
+  return OPARA_EHIP;
+}
+
+extern "C" int opara_persistent_status(opara_exec *e, void *hip_stream, uint32_t *error_word) {
+  if (!e || !e->workspace || !error_word) { set_error("opara_persistent_status: not a persistent executor"); return OPARA_EINVAL; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  PersistHeader h;
+  HIP_TRY(hipMemcpyAsync(&h, e->workspace, sizeof(h), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  *error_word = h.error;
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  return OPARA_EHIP;
+}
+
+extern "C" int opara_persistent_info(const opara_exec *e, int32_t *n_items, int32_t *n_workgroups) {
+  if (!e || !e->workspace) { set_error("opara_persistent_info: not a persistent executor"); return OPARA_EINVAL; }
+  if (n_items) *n_items = e->persist_items;
+  if (n_workgroups) *n_workgroups = e->persist_workgroups;
+  return OPARA_OK;
+}
+
+extern "C" int opara_persistent_set_trace(opara_exec *e, void *hip_stream, void *trace, uint64_t trace_bytes) {
+  if (!e || !e->workspace) { set_error("opara_persistent_set_trace: not a persistent executor"); return OPARA_EINVAL; }
+  if (trace && (trace_bytes < 32ull * (uint64_t)e->persist_items || ((uintptr_t)trace & 7u))) {
+    set_error("opara_persistent_set_trace: buffer of %llu bytes, need %llu (8-byte aligned)",
+              (unsigned long long)trace_bytes, 32ull * (unsigned long long)e->persist_items);
+    return OPARA_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const uint64_t addr = (uint64_t)(uintptr_t)trace;
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipMemcpyAsync((unsigned char *)e->workspace + offsetof(PersistHeader, trace), &addr, sizeof(addr),
+                         hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  return OPARA_EHIP;
+}
+
+extern "C" int opara_persistent_reset(opara_exec *e, void *hip_stream, uint32_t spin_limit) {
+  if (!e || !e->workspace) { set_error("opara_persistent_reset: not a persistent executor"); return OPARA_EINVAL; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const PersistLayout lay = persist_layout(e->persist_ops);
+  PersistHeader h = {};
+  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipMemcpyAsync(&h, e->workspace, sizeof(h), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  h.exited = 0;
+  h.error = 0;
+  h.epoch = 1;
+  h.spin_limit = spin_limit ? spin_limit : kPersistDefaultSpinLimit;
+  HIP_TRY(hipMemcpyAsync(e->workspace, &h, sizeof(h), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemsetAsync((unsigned char *)e->workspace + lay.done, 0, lay.begin - lay.done, st));   // counters and flags
+  HIP_TRY(hipStreamSynchronize(st));
+  return OPARA_OK;
+fail:
   (void)hipGetLastError();
   return OPARA_EHIP;
 }

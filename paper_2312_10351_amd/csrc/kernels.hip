@@ -16,9 +16,80 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Position of a workgroup in its operator's launch grid.  An ordinary launch fills it
+// from blockIdx/gridDim; the persistent executor hands out grid positions itself.
+struct Blk {
+  int x, y, z, gx, gy;
+  bool remap;                              // apply the XCD-aware tile remap (hardware launch order only)
+};
+__device__ __forceinline__ Blk launch_blk() {
+  return Blk{(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.x, (int)gridDim.y, true};
+}
+
 template <typename T> struct Vec16;
 template <> struct Vec16<half_t> { typedef half8 type; typedef half4 quad; static constexpr int N = 8; };
 template <> struct Vec16<float> { typedef floatx4 type; typedef floatx4 quad; static constexpr int N = 4; };
+
+// Access policy of a body.  Ordinary launches use plain loads and stores: kernel
+// boundaries make results visible.  Inside the persistent executor an operator's inputs
+// were written by other workgroups of the same launch, possibly on another XCD with its
+// own L2; there every access to an activation is an agent-scope (device-coherent) access,
+// which the hardware completes at the point all XCDs share, so that a completion counter
+// published after a wait for the stores is all the synchronisation a consumer needs: no
+// cache write-back or invalidate.  Weights are never written and stay plain (L2-cached).
+constexpr int kCohAct = 1;     // first operand, residual inputs, row/element inputs, outputs
+constexpr int kCohW = 2;       // second operand too (batched GEMM of two activations)
+
+template <bool COH, typename V, typename P>
+__device__ __forceinline__ V ldg(const P *p) {
+  if constexpr (!COH) {
+    return *(const V *)p;
+  } else {
+    V v;
+    if constexpr (sizeof(V) == 16) {
+      uint64_t q[2];
+      q[0] = __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      q[1] = __hip_atomic_load((const uint64_t *)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_memcpy(&v, q, 16);
+    } else if constexpr (sizeof(V) == 8) {
+      const uint64_t q = __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_memcpy(&v, &q, 8);
+    } else if constexpr (sizeof(V) == 4) {
+      const uint32_t q = __hip_atomic_load((const uint32_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_memcpy(&v, &q, 4);
+    } else {
+      static_assert(sizeof(V) == 2, "access width");
+      const uint16_t q = __hip_atomic_load((const uint16_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_memcpy(&v, &q, 2);
+    }
+    return v;
+  }
+}
+
+template <bool COH, typename V, typename P>
+__device__ __forceinline__ void stg(P *p, const V &v) {
+  if constexpr (!COH) {
+    *(V *)p = v;
+  } else if constexpr (sizeof(V) == 16) {
+    uint64_t q[2];
+    __builtin_memcpy(q, &v, 16);
+    __hip_atomic_store((uint64_t *)p, q[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store((uint64_t *)p + 1, q[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else if constexpr (sizeof(V) == 8) {
+    uint64_t q;
+    __builtin_memcpy(&q, &v, 8);
+    __hip_atomic_store((uint64_t *)p, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else if constexpr (sizeof(V) == 4) {
+    uint32_t q;
+    __builtin_memcpy(&q, &v, 4);
+    __hip_atomic_store((uint32_t *)p, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    static_assert(sizeof(V) == 2, "access width");
+    uint16_t q;
+    __builtin_memcpy(&q, &v, 2);
+    __hip_atomic_store((uint16_t *)p, q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
 // ---------------------------------------------------------------------------------
 // Implicit GEMM on the matrix cores.
@@ -44,8 +115,8 @@ template <> __device__ __forceinline__ floatx4 mma16<float>(floatx4 a, floatx4 b
   return c;
 }
 
-template <typename T, int BN, int BM, int WN, int WM, bool VEC>
-__device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
+template <typename T, int BN, int BM, int WN, int WM, bool VEC, int COH, typename AR>
+__device__ __forceinline__ void igemm_body(const AR &a, const Blk &b, unsigned char *lds) {
   typedef typename Vec16<T>::type V;
   typedef typename Vec16<T>::quad Q;
   constexpr int VE = Vec16<T>::N;
@@ -56,14 +127,15 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
   constexpr int CHX = BM * 4 / NT;
   constexpr int FN = BN / WN / 16, FM = BM / WM / 16;
   static_assert((BN * 4) % NT == 0 && (BM * 4) % NT == 0, "tile/threads mismatch");
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][(BN + BM) * ROWB];
+  unsigned char (*smem)[(BN + BM) * ROWB] = (unsigned char (*)[(BN + BM) * ROWB])lds;   // [2][...]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wn0 = (wave % WN) * (BN / WN), wm0 = (wave / WN) * (BM / WM);
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
-  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
-  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+  const int m0 = b.x * BM, n0 = b.y * BN;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
   const int kc = t & 3;                    // which 16-byte chunk of a 64-byte K slice
   const int row0 = t >> 2;                 // first tile row this thread moves
   constexpr int RSTEP = NT / 4;
@@ -104,11 +176,11 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
       if (VEC) {
         if (m < a.M && kbase < a.K) {
           if (!a.gather) {
-            v = *(const V *)(x + (int64_t)m * a.lda + kbase);
+            v = ldg<CA, V>(x + (int64_t)m * a.lda + kbase);
           } else {
             const int ih = ih0[i] + g_r, iw = iw0[i] + g_s;
             if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-              v = *(const V *)(ximg[i] + ((int64_t)ih * a.W + iw) * a.Cin + g_ci);
+              v = ldg<CA, V>(ximg[i] + ((int64_t)ih * a.W + iw) * a.Cin + g_ci);
           }
         }
       } else {
@@ -118,12 +190,12 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
             const int k = kbase + e;
             if (k < a.K) {
               if (!a.gather) {
-                v[e] = x[(int64_t)m * a.lda + k];
+                v[e] = ldg<CA, T>(x + (int64_t)m * a.lda + k);
               } else {
                 const int ci = k % a.Cin, rs = k / a.Cin;
                 const int ih = ih0[i] + rs / a.kw, iw = iw0[i] + rs % a.kw;
                 if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-                  v[e] = ximg[i][((int64_t)ih * a.W + iw) * a.Cin + ci];
+                  v[e] = ldg<CA, T>(ximg[i] + ((int64_t)ih * a.W + iw) * a.Cin + ci);
               }
             }
           }
@@ -138,11 +210,11 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
       if (!a.b_kmajor) {
         const int n = n0 + row0 + i * RSTEP;
         if (VEC) {
-          if (n < a.N && kbase < a.K) v = *(const V *)(w + (int64_t)n * a.ldb + kbase);
+          if (n < a.N && kbase < a.K) v = ldg<CW, V>(w + (int64_t)n * a.ldb + kbase);
         } else if (n < a.N) {
 #pragma unroll
           for (int e = 0; e < VE; ++e)
-            if (kbase + e < a.K) v[e] = w[(int64_t)n * a.ldb + kbase + e];
+            if (kbase + e < a.K) v[e] = ldg<CW, T>(w + (int64_t)n * a.ldb + kbase + e);
         }
       } else {
         // operand stored [K][N]: a chunk runs along N at one K position
@@ -151,11 +223,11 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
         const int k = kt * BKE + krow, n = n0 + nch * VE;
         if (k < a.K) {
           if (VEC) {
-            if (n < a.N) v = *(const V *)(w + (int64_t)k * a.ldb + n);
+            if (n < a.N) v = ldg<CW, V>(w + (int64_t)k * a.ldb + n);
           } else {
 #pragma unroll
             for (int e = 0; e < VE; ++e)
-              if (n + e < a.N) v[e] = w[(int64_t)k * a.ldb + n + e];
+              if (n + e < a.N) v[e] = ldg<CW, T>(w + (int64_t)k * a.ldb + n + e);
           }
         }
       }
@@ -234,7 +306,7 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
         float r = acc[i][j][e] * a.alpha;
         if (n + e < a.N) {
           if (a.bias) r += a.bias[n + e];
-          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)ldg<CA, T>((const T *)a.extra[q] + (int64_t)m * a.N + n + e);
         }
         if (a.relu) r = fmaxf(r, 0.f);
         v[e] = r;
@@ -242,11 +314,11 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
       T *dst = y + (int64_t)m * a.ldy + n;
       if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        *(Q *)dst = q4;
+        stg<CA, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) dst[e] = (T)v[e];
+          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -256,10 +328,11 @@ __device__ __forceinline__ void igemm_body(const IgemmArgs &a) {
 // own L2.  Remap the linear workgroup index so that every XCD works on a contiguous
 // range of tiles (row tiles of one column tile first): neighbours that share operand
 // rows then share an L2 instead of fetching them eight times.
-__device__ __forceinline__ void xcd_tile(int &tx, int &ty) {
+__device__ __forceinline__ void xcd_tile(const Blk &b, int &tx, int &ty) {
   constexpr int kXcds = 8;
-  const int nx = gridDim.x, total = gridDim.x * gridDim.y;
-  const int lin = blockIdx.y * nx + blockIdx.x;
+  if (!b.remap) { tx = b.x; ty = b.y; return; }
+  const int nx = b.gx, total = b.gx * b.gy;
+  const int lin = b.y * nx + b.x;
   const int xcd = lin % kXcds, idx = lin / kXcds;
   const int q = total / kXcds, r = total % kXcds;
   const int tile = xcd * q + (xcd < r ? xcd : r) + idx;
@@ -284,8 +357,8 @@ __device__ __forceinline__ void kpos_advance(KPos &p, int delta, int Cin, int kw
 // compute unit the loop is bound by memory latency, so the bytes in flight set the
 // speed).  Vector loads only, second operand stored [N][K].
 // ---------------------------------------------------------------------------------
-template <typename T, int BN, int BM, int WN, int WM, int DEPTH>
-__device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
+template <typename T, int BN, int BM, int WN, int WM, int DEPTH, int COH, typename AR>
+__device__ __forceinline__ void igemm_pipe_body(const AR &a, const Blk &b, unsigned char *lds) {
   typedef typename Vec16<T>::type V;
   typedef typename Vec16<T>::quad Q;
   constexpr int VE = Vec16<T>::N;
@@ -297,16 +370,17 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
   constexpr int FN = BN / WN / 16, FM = BM / WM / 16;
   constexpr int RSTEP = NT / KCH;
   static_assert((BN * KCH) % NT == 0 && (BM * KCH) % NT == 0, "tile/threads mismatch");
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][(BN + BM) * ROWB];
+  unsigned char (*smem)[(BN + BM) * ROWB] = (unsigned char (*)[(BN + BM) * ROWB])lds;   // [2][...]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wn0 = (wave % WN) * (BN / WN), wm0 = (wave / WN) * (BM / WM);
   int tile_x, tile_y;
-  xcd_tile(tile_x, tile_y);
+  xcd_tile(b, tile_x, tile_y);
   const int m0 = tile_x * BM, n0 = tile_y * BN;
-  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
-  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
-  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
   const int kc = t % KCH, row0 = t / KCH;
 
   // Per-thread rows, clamped into range: every global load below is unconditional and
@@ -355,7 +429,7 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
     unsigned mask = kok ? rowmask : 0u;
     if (!a.gather) {
 #pragma unroll
-      for (int i = 0; i < CHX; ++i) xr[i] = *(const V *)(xrow[i] + ks);
+      for (int i = 0; i < CHX; ++i) xr[i] = ldg<CA, V>(xrow[i] + ks);
     } else {
 #pragma unroll
       for (int i = 0; i < CHX; ++i) {
@@ -363,12 +437,12 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
         const bool inb = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
         const int64_t off = inb ? ((int64_t)ih * a.W + iw) * a.Cin + pos.ci : 0;
         if (!inb) mask &= ~(1u << i);
-        xr[i] = *(const V *)(ximg[i] + off);
+        xr[i] = ldg<CA, V>(ximg[i] + off);
       }
       kpos_advance(pos, BKE, a.Cin, a.kw);
     }
 #pragma unroll
-    for (int i = 0; i < CHW; ++i) wr[i] = *(const V *)(wrow[i] + ks);
+    for (int i = 0; i < CHW; ++i) wr[i] = ldg<CW, V>(wrow[i] + ks);
     return mask;
   };
   auto store_lds = [&](int buf, const V *wr, const V *xr, unsigned mask) {
@@ -440,7 +514,7 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
         float r = acc[i][j][e] * a.alpha;
         if (n + e < a.N) {
           if (a.bias) r += a.bias[n + e];
-          for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)ldg<CA, T>((const T *)a.extra[q] + (int64_t)m * a.N + n + e);
         }
         if (a.relu) r = fmaxf(r, 0.f);
         v[e] = r;
@@ -448,11 +522,11 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
       T *dst = y + (int64_t)m * a.ldy + n;
       if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        *(Q *)dst = q4;
+        stg<CA, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) dst[e] = (T)v[e];
+          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -467,24 +541,24 @@ __device__ __forceinline__ void igemm_pipe_body(const IgemmArgs &a) {
 // barrier inside the K loop.  Partial tiles meet in LDS once, at the end, where 256
 // threads apply the epilogue and write 8/16-byte pieces of output rows.
 // ---------------------------------------------------------------------------------
-template <typename T, int WAVES>
-__device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
+template <typename T, int WAVES, int U, int COH, typename AR>
+__device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, unsigned char *lds) {
   typedef typename Vec16<T>::type V;
   typedef typename Vec16<T>::quad Q;
   constexpr int VE = Vec16<T>::N;
   constexpr int DS = 8 * VE;               // K elements per step: 4 lane groups x 2 chunks
-  constexpr int U = 2;                     // steps in flight
   constexpr int PITCH = 36;                // floats per pixel row of a partial tile in LDS
-  __shared__ __attribute__((aligned(16))) float part[WAVES][32][PITCH];
+  float (*part)[32][PITCH] = (float (*)[32][PITCH])lds;                                // [WAVES][32][PITCH]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int grp = lane >> 4, r16 = lane & 15;
   int tile_x, tile_y;
-  xcd_tile(tile_x, tile_y);
+  xcd_tile(b, tile_x, tile_y);
   const int m0 = tile_x * 32, n0 = tile_y * 32;
-  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.z * a.a_bs;
-  const T *__restrict__ w = (const T *)a.w + (int64_t)blockIdx.z * a.b_bs;
-  T *__restrict__ y = (T *)a.y + (int64_t)blockIdx.z * a.y_bs;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
 
   const int nds = (a.K + DS - 1) / DS;
   const int per_wave = (nds + WAVES - 1) / WAVES;
@@ -528,6 +602,30 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
     for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   const V vzero = {};
 
+  // Epilogue operands of this thread's output piece (bias, residual inputs) are requested
+  // before the K walk, so that their latency is hidden behind it.
+  const int pm = t >> 3, pn = (t & 7) * 4;
+  const int m = m0 + pm, n = n0 + pn;
+  const bool full = n + 3 < a.N;           // whole group of four channels inside the tensor
+  const bool live = t < 256 && m < a.M && n < a.N;
+  floatx4 badd = {0.f, 0.f, 0.f, 0.f};
+  if (live && a.bias) {
+    if (full && ((uintptr_t)(a.bias + n) & 15) == 0) badd = *(const floatx4 *)(a.bias + n);
+    else
+      for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] = a.bias[n + e];
+  }
+  if (live)
+    for (int q = 0; q < a.n_extra; ++q) {
+      const T *ex = (const T *)a.extra[q] + (int64_t)m * a.N + n;
+      if (full && ((uintptr_t)ex & (4 * sizeof(T) - 1)) == 0) {
+        const Q v = ldg<CA, Q>(ex);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) badd[e] += (float)v[e];
+      } else {
+        for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] += (float)ldg<CA, T>(ex + e);
+      }
+    }
+
   for (int ds = ds_begin; ds < ds_end; ds += U) {
     V wa[U][2][2], xb[U][2][2];
     bool kok[U][2], inb[U][2][2];
@@ -540,17 +638,17 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
         kok[u][c] = ds + u < ds_end && k < a.K;
         const int ks = kok[u][c] ? k : 0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) wa[u][i][c] = *(const V *)(wrow[i] + ks);
+        for (int i = 0; i < 2; ++i) wa[u][i][c] = ldg<CW, V>(wrow[i] + ks);
         if (!a.gather) {
 #pragma unroll
-          for (int j = 0; j < 2; ++j) xb[u][j][c] = *(const V *)(xrow[j] + ks);
+          for (int j = 0; j < 2; ++j) xb[u][j][c] = ldg<CA, V>(xrow[j] + ks);
         } else {
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
             const int ih = ih0[j] + pc.r, iw = iw0[j] + pc.s;
             inb[u][j][c] = kok[u][c] && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
             const int64_t off = inb[u][j][c] ? ((int64_t)ih * a.W + iw) * a.Cin + pc.ci : 0;
-            xb[u][j][c] = *(const V *)(ximg[j] + off);
+            xb[u][j][c] = ldg<CA, V>(ximg[j] + off);
           }
           if (c == 0) kpos_advance(pc, VE, a.Cin, a.kw);
         }
@@ -581,28 +679,6 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
     for (int j = 0; j < 2; ++j) *(floatx4 *)&part[wave][j * 16 + r16][i * 16 + grp * 4] = acc[i][j];
   __syncthreads();
   if (t < 256) {
-    const int pm = t >> 3, pn = (t & 7) * 4;
-    const int m = m0 + pm, n = n0 + pn;
-    const bool full = n + 3 < a.N;         // whole group of four channels inside the tensor
-    const bool live = m < a.M && n < a.N;
-    // epilogue operands first (independent loads), then the partial sums
-    floatx4 badd = {0.f, 0.f, 0.f, 0.f};
-    if (live && a.bias) {
-      if (full && ((uintptr_t)(a.bias + n) & 15) == 0) badd = *(const floatx4 *)(a.bias + n);
-      else
-        for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] = a.bias[n + e];
-    }
-    if (live)
-      for (int q = 0; q < a.n_extra; ++q) {
-        const T *ex = (const T *)a.extra[q] + (int64_t)m * a.N + n;
-        if (full && ((uintptr_t)ex & (4 * sizeof(T) - 1)) == 0) {
-          const Q v = *(const Q *)ex;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) badd[e] += (float)v[e];
-        } else {
-          for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] += (float)ex[e];
-        }
-      }
     floatx4 sum = *(const floatx4 *)&part[0][pm][pn];
 #pragma unroll
     for (int q = 1; q < WAVES; ++q) sum += *(const floatx4 *)&part[q][pm][pn];
@@ -616,11 +692,11 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
       T *dst = y + (int64_t)m * a.ldy + n;
       if (full && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        *(Q *)dst = q4;
+        stg<CA, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) dst[e] = (T)v[e];
+          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -628,22 +704,23 @@ __device__ __forceinline__ void igemm_direct_body(const IgemmArgs &a) {
 
 // Matrix-vector shaped GEMM (M <= kGemvMaxM rows): one wavefront per output column,
 // 16-byte loads along K, shuffle reduction.  Weight-bandwidth bound by construction.
-template <typename T>
-__device__ __forceinline__ void gemv_body(const IgemmArgs &a) {
+template <typename T, int COH, typename AR>
+__device__ __forceinline__ void gemv_body(const AR &a, const Blk &b, unsigned char *lds) {
   typedef typename Vec16<T>::type V;
   constexpr int VE = Vec16<T>::N;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n = blockIdx.x * 4 + wave;
+  const int n = b.x * 4 + wave;
   if (n >= a.N) return;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
   const T *__restrict__ x = (const T *)a.x;
   const T *__restrict__ wr = (const T *)a.w + (int64_t)n * a.ldb;
   float acc[kGemvMaxM] = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = lane * VE; k0 < a.K; k0 += 64 * VE) {
-    const V wv = *(const V *)(wr + k0);
+    const V wv = ldg<CW, V>(wr + k0);
 #pragma unroll
     for (int m = 0; m < kGemvMaxM; ++m) {
       if (m < a.M) {
-        const V xv = *(const V *)(x + (int64_t)m * a.lda + k0);
+        const V xv = ldg<CA, V>(x + (int64_t)m * a.lda + k0);
 #pragma unroll
         for (int e = 0; e < VE; ++e) acc[m] += (float)wv[e] * (float)xv[e];
       }
@@ -658,9 +735,9 @@ __device__ __forceinline__ void gemv_body(const IgemmArgs &a) {
     for (int m = 0; m < a.M; ++m) {
       float r = acc[m] * a.alpha;
       if (a.bias) r += a.bias[n];
-      for (int q = 0; q < a.n_extra; ++q) r += (float)((const T *)a.extra[q])[(int64_t)m * a.N + n];
+      for (int q = 0; q < a.n_extra; ++q) r += (float)ldg<CA, T>((const T *)a.extra[q] + (int64_t)m * a.N + n);
       if (a.relu) r = fmaxf(r, 0.f);
-      y[(int64_t)m * a.ldy + n] = (T)r;
+      stg<CA, T>(y + (int64_t)m * a.ldy + n, (T)r);
     }
   }
 }
@@ -668,10 +745,11 @@ __device__ __forceinline__ void gemv_body(const IgemmArgs &a) {
 // ---------------------------------------------------------------------------------
 // Pooling over [H][W][C]: one thread per output pixel and channel chunk.
 // ---------------------------------------------------------------------------------
-template <typename T, int VE>
-__device__ __forceinline__ void pool_body(const PoolArgs &a) {
+template <typename T, int VE, int COH, typename AR>
+__device__ __forceinline__ void pool_body(const AR &a, const Blk &b, unsigned char *lds) {
+  constexpr bool CA = (COH & kCohAct) != 0;
   const int cch = a.C / VE;
-  const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t item = (int64_t)b.x * 256 + threadIdx.x;
   if (item >= (int64_t)a.B * a.Ho * a.Wo * cch) return;
   const int cc = (int)(item % cch);
   const int pix = (int)(item / cch);                   // output pixel over all images
@@ -685,8 +763,8 @@ __device__ __forceinline__ void pool_body(const PoolArgs &a) {
   auto fetch = [&](int ih, int iw, T *v) {
     const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
     const T *src = x + ((int64_t)(ok ? ih : 0) * a.W + (ok ? iw : 0)) * a.C;
-    if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
-    else v[0] = src[0];
+    if constexpr (VE > 1) *(typename Vec16<T>::type *)v = ldg<CA, typename Vec16<T>::type>(src);
+    else v[0] = ldg<CA, T>(src);
     return ok;
   };
   auto fold = [&](bool ok, const T *v) {
@@ -720,32 +798,33 @@ __device__ __forceinline__ void pool_body(const PoolArgs &a) {
 #pragma unroll
   for (int e = 0; e < VE; ++e) o[e] = (T)(a.is_avg ? acc[e] * scale : acc[e]);
   T *dst = (T *)a.y + (int64_t)pix * a.C + cc * VE;
-  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)o;
-  else dst[0] = o[0];
+  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
+  else stg<CA, T>(dst, o[0]);
 }
 
 // Global average pool over [HW][C]: 256 threads = 64 channels x 4 pixel slices; each
 // thread sums its slice with independent loads, slices meet in LDS.
-template <typename T>
-__device__ __forceinline__ void gap_body(const GapArgs &a) {
-  __shared__ float part[4][64];
+template <typename T, int COH, typename AR>
+__device__ __forceinline__ void gap_body(const AR &a, const Blk &b, unsigned char *lds) {
+  float (*part)[64] = (float (*)[64])lds;                                              // [4][64]
   const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl;
-  const T *__restrict__ x = (const T *)a.x + (int64_t)blockIdx.y * a.HW * a.C;
+  const int c = b.x * 64 + cl;
+  constexpr bool CA = (COH & kCohAct) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.y * a.HW * a.C;
   float s = 0.f;
   if (c < a.C) {
     int p = slice;
     for (; p + 12 < a.HW; p += 16) {
-      const float v0 = (float)x[(int64_t)p * a.C + c], v1 = (float)x[(int64_t)(p + 4) * a.C + c];
-      const float v2 = (float)x[(int64_t)(p + 8) * a.C + c], v3 = (float)x[(int64_t)(p + 12) * a.C + c];
+      const float v0 = (float)ldg<CA, T>(x + (int64_t)p * a.C + c), v1 = (float)ldg<CA, T>(x + (int64_t)(p + 4) * a.C + c);
+      const float v2 = (float)ldg<CA, T>(x + (int64_t)(p + 8) * a.C + c), v3 = (float)ldg<CA, T>(x + (int64_t)(p + 12) * a.C + c);
       s += (v0 + v1) + (v2 + v3);
     }
-    for (; p < a.HW; p += 4) s += (float)x[(int64_t)p * a.C + c];
+    for (; p < a.HW; p += 4) s += (float)ldg<CA, T>(x + (int64_t)p * a.C + c);
   }
   part[slice][cl] = s;
   __syncthreads();
   if (slice == 0 && c < a.C)
-    ((T *)a.y)[(int64_t)blockIdx.y * a.C + c] = (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW);
+    stg<CA, T>((T *)a.y + (int64_t)b.y * a.C + c, (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW));
 }
 
 // ---------------------------------------------------------------------------------
@@ -772,13 +851,14 @@ __device__ __forceinline__ float group_reduce(float v, float *scratch) {
   return v;
 }
 
-template <typename T, bool IS_LN, int G, int MAXCH>
-__device__ __forceinline__ void row_cached_body(const RowArgs &a) {
+template <typename T, bool IS_LN, int G, int MAXCH, int COH, typename AR>
+__device__ __forceinline__ void row_cached_body(const AR &a, const Blk &b, unsigned char *lds) {
   typedef typename Vec16<T>::type V;
   constexpr int VE = Vec16<T>::N;
-  __shared__ float scratch[4];
+  float *scratch = (float *)lds;                                                       // [4]
+  constexpr bool CA = (COH & kCohAct) != 0;
   const int gl = threadIdx.x % G;
-  const int row = blockIdx.x * (256 / G) + threadIdx.x / G;
+  const int row = b.x * (256 / G) + threadIdx.x / G;
   if (G == 64 && row >= a.rows) return;          // whole wavefront leaves together
   float v[MAXCH][VE];
   const int64_t base = (int64_t)row * a.cols;
@@ -789,7 +869,7 @@ __device__ __forceinline__ void row_cached_body(const RowArgs &a) {
     for (int e = 0; e < VE; ++e) v[c][e] = 0.f;
     if (col < a.cols) {
       for (int q = 0; q < a.n_in; ++q) {
-        const V t = *(const V *)((const T *)a.in[q] + base + col);
+        const V t = ldg<CA, V>((const T *)a.in[q] + base + col);
 #pragma unroll
         for (int e = 0; e < VE; ++e) v[c][e] += (float)t[e];
       }
@@ -842,19 +922,20 @@ __device__ __forceinline__ void row_cached_body(const RowArgs &a) {
       V o;
 #pragma unroll
       for (int e = 0; e < VE; ++e) o[e] = (T)v[c][e];
-      *(V *)((T *)a.y + base + col) = o;
+      stg<CA, V>((T *)a.y + base + col, o);
     }
   }
 }
 
 // Any width / alignment: one workgroup per row, scalar accesses, inputs re-read per pass.
-template <typename T, bool IS_LN>
-__device__ __forceinline__ void row_generic_body(const RowArgs &a) {
-  __shared__ float scratch[4];
-  const int64_t base = (int64_t)blockIdx.x * a.cols;
+template <typename T, bool IS_LN, int COH, typename AR>
+__device__ __forceinline__ void row_generic_body(const AR &a, const Blk &b, unsigned char *lds) {
+  float *scratch = (float *)lds;                                                       // [4]
+  constexpr bool CA = (COH & kCohAct) != 0;
+  const int64_t base = (int64_t)b.x * a.cols;
   auto value = [&](int col) {
     float s = 0.f;
-    for (int q = 0; q < a.n_in; ++q) s += (float)((const T *)a.in[q])[base + col];
+    for (int q = 0; q < a.n_in; ++q) s += (float)ldg<CA, T>((const T *)a.in[q] + base + col);
     return s;
   };
   float p1 = IS_LN ? 0.f : -INFINITY;
@@ -869,7 +950,7 @@ __device__ __forceinline__ void row_generic_body(const RowArgs &a) {
   const float k = IS_LN ? 1.0f / sqrtf(r2 / (float)a.cols + a.eps) : 1.0f / r2;
   for (int col = threadIdx.x; col < a.cols; col += 256) {
     const float d = value(col) - r1;
-    ((T *)a.y)[base + col] = (T)(IS_LN ? d * k : expf(d) * k);
+    stg<CA, T>((T *)a.y + base + col, (T)(IS_LN ? d * k : expf(d) * k));
   }
 }
 
@@ -882,9 +963,10 @@ __device__ __forceinline__ float elt_apply(int op, float x) {
   return x;
 }
 
-template <typename T, int VE>
-__device__ __forceinline__ void elt_body(const EltArgs &a) {
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VE;
+template <typename T, int VE, int COH, typename AR>
+__device__ __forceinline__ void elt_body(const AR &a, const Blk &b, unsigned char *lds) {
+  constexpr bool CA = (COH & kCohAct) != 0;
+  const int64_t i = ((int64_t)b.x * 256 + threadIdx.x) * VE;
   if (i >= a.n) return;
   float s[VE];
 #pragma unroll
@@ -892,8 +974,8 @@ __device__ __forceinline__ void elt_body(const EltArgs &a) {
   for (int q = 0; q < a.n_in; ++q) {
     T v[VE];
     const T *src = (const T *)a.in[q] + i;
-    if (VE > 1) *(typename Vec16<T>::type *)v = *(const typename Vec16<T>::type *)src;
-    else v[0] = src[0];
+    if constexpr (VE > 1) *(typename Vec16<T>::type *)v = ldg<CA, typename Vec16<T>::type>(src);
+    else v[0] = ldg<CA, T>(src);
 #pragma unroll
     for (int e = 0; e < VE; ++e) s[e] += (float)v[e];
   }
@@ -901,74 +983,347 @@ __device__ __forceinline__ void elt_body(const EltArgs &a) {
 #pragma unroll
   for (int e = 0; e < VE; ++e) o[e] = (T)elt_apply(a.op, s[e]);
   T *dst = (T *)a.y + i;
-  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)o;
-  else dst[0] = o[0];
+  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
+  else stg<CA, T>(dst, o[0]);
 }
 
-template <typename T, int VE>
-__device__ __forceinline__ void concat_body(const ConcatArgs &a) {
-  const int q = blockIdx.y;
+template <typename T, int VE, int COH, typename AR>
+__device__ __forceinline__ void concat_body(const AR &a, const Blk &b, unsigned char *lds) {
+  constexpr bool CA = (COH & kCohAct) != 0;
+  const int q = b.y;
   const int cch = a.cols[q] / VE;
-  const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t item = (int64_t)b.x * 256 + threadIdx.x;
   if (item >= (int64_t)a.rows * cch) return;
   const int64_t r = item / cch;
   const int c = (int)(item % cch) * VE;
   const T *src = (const T *)a.in[q] + r * a.cols[q] + c;
   T *dst = (T *)a.y + r * a.out_cols + a.col_off[q] + c;
-  if (VE > 1) *(typename Vec16<T>::type *)dst = *(const typename Vec16<T>::type *)src;
-  else dst[0] = src[0];
+  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, ldg<CA, typename Vec16<T>::type>(src));
+  else stg<CA, T>(dst, ldg<CA, T>(src));
 }
 
 }  // namespace opara
 
 using namespace opara;
 
-#define KDEF(name, threads, Args, call) \
-  extern "C" __global__ void __launch_bounds__(threads) opara_k_##name(Args a) { call; }
-// second launch bound: wavefronts per SIMD the register allocation must leave room for
-#define KDEF2(name, threads, waves_per_simd, Args, call) \
-  extern "C" __global__ void __launch_bounds__(threads, waves_per_simd) opara_k_##name(Args a) { call; }
+// Workgroup-shared memory each body needs (bytes).
+constexpr int lds_igemm(int bn, int bm) { return 2 * (bn + bm) * 80; }
+constexpr int lds_pipe(int bn, int bm) { return 2 * (bn + bm) * 144; }
+constexpr int lds_direct(int waves) { return waves * 32 * 36 * 4; }
+constexpr int kLdsGap = 4 * 64 * 4, kLdsRow = 16, kLdsNone = 0;
 
-KDEF2(igemm_f16_t128x64, 256, 2, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4>(a)))
-KDEF(igemm_f16_t64x64, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true>(a)))
-KDEF(igemm_f16_direct4, 256, IgemmArgs, (igemm_direct_body<half_t, 4>(a)))
-KDEF(igemm_f16_direct8, 512, IgemmArgs, (igemm_direct_body<half_t, 8>(a)))
-KDEF(igemm_f16_direct16, 1024, IgemmArgs, (igemm_direct_body<half_t, 16>(a)))
-KDEF(igemm_f16_t64x64_scalar, 256, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false>(a)))
-KDEF2(igemm_f32_t128x64, 256, 2, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4>(a)))
-KDEF(igemm_f32_t64x64, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true>(a)))
-KDEF(igemm_f32_direct4, 256, IgemmArgs, (igemm_direct_body<float, 4>(a)))
-KDEF(igemm_f32_direct8, 512, IgemmArgs, (igemm_direct_body<float, 8>(a)))
-KDEF(igemm_f32_direct16, 1024, IgemmArgs, (igemm_direct_body<float, 16>(a)))
-KDEF(igemm_f32_t64x64_scalar, 256, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false>(a)))
-KDEF(gemv_f16, 256, IgemmArgs, (gemv_body<half_t>(a)))
-KDEF(gemv_f32, 256, IgemmArgs, (gemv_body<float>(a)))
-KDEF(pool_f16_vec, 256, PoolArgs, (pool_body<half_t, 8>(a)))
-KDEF(pool_f16_scalar, 256, PoolArgs, (pool_body<half_t, 1>(a)))
-KDEF(pool_f32_vec, 256, PoolArgs, (pool_body<float, 4>(a)))
-KDEF(pool_f32_scalar, 256, PoolArgs, (pool_body<float, 1>(a)))
-KDEF(gap_f16, 256, GapArgs, (gap_body<half_t>(a)))
-KDEF(gap_f32, 256, GapArgs, (gap_body<float>(a)))
-KDEF(layernorm_f16_wave, 256, RowArgs, (row_cached_body<half_t, true, 64, 2>(a)))
-KDEF(layernorm_f16_block, 256, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks>(a)))
-KDEF(layernorm_f16_generic, 256, RowArgs, (row_generic_body<half_t, true>(a)))
-KDEF(layernorm_f32_wave, 256, RowArgs, (row_cached_body<float, true, 64, 2>(a)))
-KDEF(layernorm_f32_block, 256, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks>(a)))
-KDEF(layernorm_f32_generic, 256, RowArgs, (row_generic_body<float, true>(a)))
-KDEF(softmax_f16_wave, 256, RowArgs, (row_cached_body<half_t, false, 64, 2>(a)))
-KDEF(softmax_f16_block, 256, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks>(a)))
-KDEF(softmax_f16_generic, 256, RowArgs, (row_generic_body<half_t, false>(a)))
-KDEF(softmax_f32_wave, 256, RowArgs, (row_cached_body<float, false, 64, 2>(a)))
-KDEF(softmax_f32_block, 256, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks>(a)))
-KDEF(softmax_f32_generic, 256, RowArgs, (row_generic_body<float, false>(a)))
-KDEF(elt_f16_vec, 256, EltArgs, (elt_body<half_t, 8>(a)))
-KDEF(elt_f16_scalar, 256, EltArgs, (elt_body<half_t, 1>(a)))
-KDEF(elt_f32_vec, 256, EltArgs, (elt_body<float, 4>(a)))
-KDEF(elt_f32_scalar, 256, EltArgs, (elt_body<float, 1>(a)))
-KDEF(concat_f16_vec, 256, ConcatArgs, (concat_body<half_t, 8>(a)))
-KDEF(concat_f16_scalar, 256, ConcatArgs, (concat_body<half_t, 1>(a)))
-KDEF(concat_f32_vec, 256, ConcatArgs, (concat_body<float, 4>(a)))
-KDEF(concat_f32_scalar, 256, ConcatArgs, (concat_body<float, 1>(a)))
+#define KDEF(name, threads, ldsb, Args, call)                                            \
+  extern "C" __global__ void __launch_bounds__(threads) opara_k_##name(Args a) {         \
+    __shared__ __attribute__((aligned(16))) unsigned char lds[(ldsb) > 0 ? (ldsb) : 16]; \
+    const Blk b = launch_blk();                                                          \
+    call;                                                                                \
+  }
+// second launch bound: wavefronts per SIMD the register allocation must leave room for
+#define KDEF2(name, threads, waves_per_simd, ldsb, Args, call)                                   \
+  extern "C" __global__ void __launch_bounds__(threads, waves_per_simd) opara_k_##name(Args a) { \
+    __shared__ __attribute__((aligned(16))) unsigned char lds[(ldsb) > 0 ? (ldsb) : 16];         \
+    const Blk b = launch_blk();                                                                  \
+    call;                                                                                        \
+  }
+
+KDEF2(igemm_f16_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+KDEF(igemm_f16_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
+KDEF(igemm_f16_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0>(a, b, lds)))
+KDEF(igemm_f16_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<half_t, 8, 2, 0>(a, b, lds)))
+KDEF(igemm_f16_direct16, 1024, lds_direct(16), IgemmArgs, (igemm_direct_body<half_t, 16, 2, 0>(a, b, lds)))
+KDEF(igemm_f16_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
+KDEF2(igemm_f32_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+KDEF(igemm_f32_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
+KDEF(igemm_f32_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<float, 4, 2, 0>(a, b, lds)))
+KDEF(igemm_f32_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<float, 8, 2, 0>(a, b, lds)))
+KDEF(igemm_f32_direct16, 1024, lds_direct(16), IgemmArgs, (igemm_direct_body<float, 16, 2, 0>(a, b, lds)))
+KDEF(igemm_f32_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
+KDEF(gemv_f16, 256, kLdsNone, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
+KDEF(gemv_f32, 256, kLdsNone, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
+KDEF(pool_f16_vec, 256, kLdsNone, PoolArgs, (pool_body<half_t, 8, 0>(a, b, lds)))
+KDEF(pool_f16_scalar, 256, kLdsNone, PoolArgs, (pool_body<half_t, 1, 0>(a, b, lds)))
+KDEF(pool_f32_vec, 256, kLdsNone, PoolArgs, (pool_body<float, 4, 0>(a, b, lds)))
+KDEF(pool_f32_scalar, 256, kLdsNone, PoolArgs, (pool_body<float, 1, 0>(a, b, lds)))
+KDEF(gap_f16, 256, kLdsGap, GapArgs, (gap_body<half_t, 0>(a, b, lds)))
+KDEF(gap_f32, 256, kLdsGap, GapArgs, (gap_body<float, 0>(a, b, lds)))
+KDEF(layernorm_f16_wave, 256, kLdsRow, RowArgs, (row_cached_body<half_t, true, 64, 2, 0>(a, b, lds)))
+KDEF(layernorm_f16_block, 256, kLdsRow, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, 0>(a, b, lds)))
+KDEF(layernorm_f16_generic, 256, kLdsRow, RowArgs, (row_generic_body<half_t, true, 0>(a, b, lds)))
+KDEF(layernorm_f32_wave, 256, kLdsRow, RowArgs, (row_cached_body<float, true, 64, 2, 0>(a, b, lds)))
+KDEF(layernorm_f32_block, 256, kLdsRow, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, 0>(a, b, lds)))
+KDEF(layernorm_f32_generic, 256, kLdsRow, RowArgs, (row_generic_body<float, true, 0>(a, b, lds)))
+KDEF(softmax_f16_wave, 256, kLdsRow, RowArgs, (row_cached_body<half_t, false, 64, 2, 0>(a, b, lds)))
+KDEF(softmax_f16_block, 256, kLdsRow, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, 0>(a, b, lds)))
+KDEF(softmax_f16_generic, 256, kLdsRow, RowArgs, (row_generic_body<half_t, false, 0>(a, b, lds)))
+KDEF(softmax_f32_wave, 256, kLdsRow, RowArgs, (row_cached_body<float, false, 64, 2, 0>(a, b, lds)))
+KDEF(softmax_f32_block, 256, kLdsRow, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, 0>(a, b, lds)))
+KDEF(softmax_f32_generic, 256, kLdsRow, RowArgs, (row_generic_body<float, false, 0>(a, b, lds)))
+KDEF(elt_f16_vec, 256, kLdsNone, EltArgs, (elt_body<half_t, 8, 0>(a, b, lds)))
+KDEF(elt_f16_scalar, 256, kLdsNone, EltArgs, (elt_body<half_t, 1, 0>(a, b, lds)))
+KDEF(elt_f32_vec, 256, kLdsNone, EltArgs, (elt_body<float, 4, 0>(a, b, lds)))
+KDEF(elt_f32_scalar, 256, kLdsNone, EltArgs, (elt_body<float, 1, 0>(a, b, lds)))
+KDEF(concat_f16_vec, 256, kLdsNone, ConcatArgs, (concat_body<half_t, 8, 0>(a, b, lds)))
+KDEF(concat_f16_scalar, 256, kLdsNone, ConcatArgs, (concat_body<half_t, 1, 0>(a, b, lds)))
+KDEF(concat_f32_vec, 256, kLdsNone, ConcatArgs, (concat_body<float, 4, 0>(a, b, lds)))
+KDEF(concat_f32_scalar, 256, kLdsNone, ConcatArgs, (concat_body<float, 1, 0>(a, b, lds)))
+
+// ---------------------------------------------------------------------------------
+// Persistent executor.  One launch runs the whole DAG: each workgroup repeatedly takes
+// the next ticket, finds the operator and tile it denotes, waits until that operator's
+// predecessors have completed all their tiles, runs the tile with the operator's own
+// body, and publishes the completion.  Tickets follow the launch queue, which is a
+// topological order, so the owner of the lowest unfinished ticket never waits for a
+// ticket nobody holds: the launch drains whatever number of workgroups is resident.
+// Every wait is bounded; a wait that runs out sets the sticky error word and all
+// workgroups leave.  The last workgroup to leave clears the counters for the next launch.
+// ---------------------------------------------------------------------------------
+template <typename A> __device__ __forceinline__ A load_uniform(const void *p) {
+  // Records are written once before the first launch and never by a kernel: read them
+  // through the constant address space so they arrive in scalar registers like
+  // ordinary kernel arguments.
+  typedef const uint32_t __attribute__((address_space(4))) *CP;
+  CP w = (CP)(uintptr_t)p;
+  union { A a; uint32_t w[sizeof(A) / 4]; } u;
+  static_assert(sizeof(A) % 4 == 0, "record size");
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(A) / 4; ++i) u.w[i] = w[i];
+  return u.a;
+}
+
+template <bool F16>
+__device__ __forceinline__ void persist_run(int kernel, const PersistOp *r, const Blk &b, unsigned char *lds) {
+#define PCASE_(label, Args, call)                             \
+  case label: {                                               \
+    typedef const Args __attribute__((address_space(4))) CA;  \
+    CA &a = *(CA *)(uintptr_t)&r->args;                       \
+    call;                                                     \
+  } break;
+#define PCASE(name, Args, call) PCASE_(K_##name, Args, call)
+#define PCASEW(name, Args, call) PCASE_(K_##name + kPersistActivationB, Args, call)
+  if (F16) {
+    switch (kernel) {
+      PCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kCohAct>(a, b, lds)))
+      PCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kCohAct>(a, b, lds)))
+      PCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 4, kCohAct>(a, b, lds)))
+      PCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kCohAct>(a, b, lds)))
+      PCASEW(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 4, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kCohAct | kCohW>(a, b, lds)))
+      PCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, kCohAct>(a, b, lds)))
+      PCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, kCohAct>(a, b, lds)))
+      PCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, kCohAct>(a, b, lds)))
+      PCASE(gap_f16, GapArgs, (gap_body<half_t, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f16_wave, RowArgs, (row_cached_body<half_t, true, 64, 2, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f16_block, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f16_generic, RowArgs, (row_generic_body<half_t, true, kCohAct>(a, b, lds)))
+      PCASE(softmax_f16_wave, RowArgs, (row_cached_body<half_t, false, 64, 2, kCohAct>(a, b, lds)))
+      PCASE(softmax_f16_block, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
+      PCASE(softmax_f16_generic, RowArgs, (row_generic_body<half_t, false, kCohAct>(a, b, lds)))
+      PCASE(elt_f16_vec, EltArgs, (elt_body<half_t, 8, kCohAct>(a, b, lds)))
+      PCASE(elt_f16_scalar, EltArgs, (elt_body<half_t, 1, kCohAct>(a, b, lds)))
+      PCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, kCohAct>(a, b, lds)))
+      PCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, kCohAct>(a, b, lds)))
+      default: break;
+    }
+  } else {
+    switch (kernel) {
+      PCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kCohAct>(a, b, lds)))
+      PCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kCohAct>(a, b, lds)))
+      PCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 4, kCohAct>(a, b, lds)))
+      PCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kCohAct>(a, b, lds)))
+      PCASEW(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 4, kCohAct | kCohW>(a, b, lds)))
+      PCASEW(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kCohAct | kCohW>(a, b, lds)))
+      PCASE(gemv_f32, IgemmArgs, (gemv_body<float, kCohAct>(a, b, lds)))
+      PCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, kCohAct>(a, b, lds)))
+      PCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, kCohAct>(a, b, lds)))
+      PCASE(gap_f32, GapArgs, (gap_body<float, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f32_wave, RowArgs, (row_cached_body<float, true, 64, 2, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f32_block, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
+      PCASE(layernorm_f32_generic, RowArgs, (row_generic_body<float, true, kCohAct>(a, b, lds)))
+      PCASE(softmax_f32_wave, RowArgs, (row_cached_body<float, false, 64, 2, kCohAct>(a, b, lds)))
+      PCASE(softmax_f32_block, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
+      PCASE(softmax_f32_generic, RowArgs, (row_generic_body<float, false, kCohAct>(a, b, lds)))
+      PCASE(elt_f32_vec, EltArgs, (elt_body<float, 4, kCohAct>(a, b, lds)))
+      PCASE(elt_f32_scalar, EltArgs, (elt_body<float, 1, kCohAct>(a, b, lds)))
+      PCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, kCohAct>(a, b, lds)))
+      PCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, kCohAct>(a, b, lds)))
+      default: break;
+    }
+  }
+#undef PCASE
+#undef PCASEW
+#undef PCASE_
+}
+
+// Thread 0 only: wait until every predecessor of the operator at queue position `pos`
+// has raised its flag for this launch.  Each workgroup polls its own copy of a flag
+// (hundreds of workgroups polling one address queue up behind each other, and the
+// counter updates behind them).  False: the wait ran out, or another workgroup's did.
+__device__ __forceinline__ bool persist_wait(const PersistArgs &pa, const PersistPredsLds *pl, int pos, uint32_t epoch,
+                                             uint32_t limit) {
+  const int np = pl->n;
+  const uint32_t copy = (blockIdx.x % kPersistReplicas) * kPersistFlagStride;
+  uint32_t spins = 0;
+  for (int j = 0; j < np; ++j) {
+    const uint32_t *f = pa.flags + (size_t)pl->pos[j] * (kPersistReplicas * kPersistFlagStride) + copy;
+    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+      ++spins;
+      if (spins > limit) {
+        __hip_atomic_store(&pa.hdr->error, (uint32_t)pos + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+      }
+      if ((spins & 31u) == 0 && __hip_atomic_load(&pa.hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+        return false;
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
+  return true;
+}
+
+// Thread 0 only, after the workgroup's stores are complete: count one finished tile of
+// the operator at `pos`; whoever counts the last tile clears the counter for the next
+// launch and raises every copy of the operator's flag.
+__device__ __forceinline__ void persist_publish(const PersistArgs &pa, const PersistPredsLds *preds, int pos, uint32_t epoch) {
+  uint32_t *d = pa.done + (size_t)pos * kPersistCounterStride;
+  const uint32_t before = __hip_atomic_fetch_add(d, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (before + 1u == (uint32_t)preds[pos].tiles) {
+    __hip_atomic_store(d, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t *f = pa.flags + (size_t)pos * (kPersistReplicas * kPersistFlagStride);
+#pragma unroll
+    for (int r = 0; r < kPersistReplicas; ++r)
+      __hip_atomic_store(f + r * kPersistFlagStride, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// Queue position of work item `item` (uniform; table in workgroup memory, begin[n] = total).
+__device__ __forceinline__ int persist_find(const int32_t *begin, int n, uint32_t item) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((uint32_t)begin[mid] <= item) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Work items are dealt round-robin: workgroup g runs items g, g + G, g + 2G, ... of the
+// launch queue, each after its operator's predecessors are complete.  The queue is a
+// topological order and every workgroup of the launch is resident (the host sizes G to
+// the occupancy), so the owner of the lowest unfinished item is always able to run it.
+//
+// Every activation access inside the bodies is device-coherent (see ldg/stg), so an item
+// is published by waiting for the workgroup's stores and then bumping the operator's
+// counter with relaxed atomics; a consumer that has read the full count may read the data.
+//
+// Each iteration has exactly ONE thread-0-only region (publish the previous item, await
+// the predecessors of this one), placed before the first of its two barriers.  With a
+// second such region after the last barrier the compiler threads thread 0 from the end of
+// one iteration straight into the next; the other lanes of its wavefront then reach the
+// barrier on their own, the wavefront arrives twice and the barrier count of the
+// workgroup no longer matches.
+template <bool F16>
+__device__ __forceinline__ void persist_body(const PersistArgs &pa) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+  unsigned char *lds = dyn_lds;                                  // kPersistBodyLds bytes for the bodies
+  int32_t *ctl = (int32_t *)(dyn_lds + kPersistBodyLds);         // [4] abort flag, -, last-out flag
+  int32_t *begin = ctl + 4;                                      // [n + 1]
+  const PersistPredsLds *preds = (const PersistPredsLds *)(begin + pa.n + 1);   // [n]
+  const int tid = threadIdx.x;
+  for (int i = tid; i <= pa.n; i += 256) begin[i] = pa.item_begin[i];
+  {
+    const uint32_t *src = (const uint32_t *)pa.preds;
+    uint32_t *dst = (uint32_t *)(begin + pa.n + 1);
+    const int words = pa.n * (int)(sizeof(PersistPredsLds) / 4);
+    for (int i = tid; i < words; i += 256) dst[i] = src[i];
+  }
+  if (tid == 0) ctl[0] = 0;
+  // Optional timeline: four 64-bit words per work item (constant 100 MHz clock): lookup
+  // started, predecessors complete, body finished, (queue position << 32 | workgroup).
+  uint64_t *trace = nullptr;
+  uint32_t limit = 0, epoch = 0;
+  uint64_t t_begin = 0, t_ready = 0;
+  if (tid == 0) {
+    trace = (uint64_t *)__hip_atomic_load(&pa.hdr->trace, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    limit = __hip_atomic_load(&pa.hdr->spin_limit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    epoch = __hip_atomic_load(&pa.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  int prev = -1;
+  uint32_t sink = 0;
+  for (uint32_t item = blockIdx.x; item < (uint32_t)pa.total; item += gridDim.x) {
+    const int pos = __builtin_amdgcn_readfirstlane(persist_find(begin, pa.n, item));
+    const int tile = (int)(item - (uint32_t)begin[pos]);
+    if (tid == 0) {
+      if (prev >= 0) {
+        persist_publish(pa, preds, prev, epoch);
+        if (trace) {
+          uint64_t *rec = trace + 4 * (uint64_t)(item - gridDim.x);
+          const uint64_t t_end = wall_clock64();
+          rec[0] = t_begin; rec[1] = t_ready; rec[2] = t_end;
+          rec[3] = ((uint64_t)(uint32_t)prev << 32) | blockIdx.x;
+        }
+      }
+      if (trace) t_begin = wall_clock64();
+      if (!persist_wait(pa, preds + pos, pos, epoch, limit)) ctl[0] = 1;
+      if (trace) t_ready = wall_clock64();
+    }
+    __syncthreads();                                             // predecessors complete (or abort)
+    if (ctl[0]) { prev = -1; break; }
+    const PersistOp *r = pa.rec + pos;
+    const int4 hd = load_uniform<int4>(r);                       // kernel, gx, gy, gz
+    // Touch the next item's record now so that its argument loads find it in the scalar
+    // cache; the values are only summed into a sink that is tested after the loop.
+    const uint32_t nitem = item + gridDim.x;
+    const int npos = nitem < (uint32_t)pa.total ? persist_find(begin, pa.n, nitem) : pos;
+    const unsigned char *nr = (const unsigned char *)(pa.rec + __builtin_amdgcn_readfirstlane(npos));
+    const uint32_t p0 = load_uniform<uint32_t>(nr), p1 = load_uniform<uint32_t>(nr + 64);
+    const uint32_t p2 = load_uniform<uint32_t>(nr + 128), p3 = load_uniform<uint32_t>(nr + 192);
+    Blk b;
+    b.gx = hd.y; b.gy = hd.z; b.remap = false;
+    b.x = tile % hd.y;
+    const int rest = tile / hd.y;
+    b.y = rest % hd.z;
+    b.z = rest / hd.z;
+    persist_run<F16>(hd.x, r, b, lds);
+    sink += (p0 ^ p1) + (p2 ^ p3);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): this wavefront's stores are complete
+    __syncthreads();                                             // ... for every wavefront, and ctl has been read
+    prev = pos;
+  }
+  // Leave: publish the last item; the last workgroup out clears the counters (nobody is
+  // left to read them) and advances the launch number.
+  if (tid == 0) {
+    if (prev >= 0) {
+      persist_publish(pa, preds, prev, epoch);
+      if (trace) {
+        // the loop has advanced `item` past the end: the last item of this workgroup is the
+        // largest g + k*G below total
+        const uint32_t last = blockIdx.x + ((uint32_t)pa.total - 1u - blockIdx.x) / gridDim.x * gridDim.x;
+        uint64_t *rec = trace + 4 * (uint64_t)last;
+        rec[0] = t_begin; rec[1] = t_ready; rec[2] = wall_clock64();
+        rec[3] = ((uint64_t)(uint32_t)prev << 32) | blockIdx.x;
+      }
+    }
+    if (sink == 0x9e3779b9u) pa.hdr->reserved0 = sink;           // keeps the record touches alive
+    const uint32_t e = __hip_atomic_fetch_add(&pa.hdr->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ctl[2] = (e == gridDim.x - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (ctl[2]) {
+    // Counters of operators that did not complete (abandoned launch) would poison the
+    // next one; after a clean launch they are all zero already.
+    for (int i = tid; i < pa.n; i += 256) pa.done[(size_t)i * kPersistCounterStride] = 0u;
+    if (tid == 0) {
+      pa.hdr->exited = 0u;
+      pa.hdr->epoch = epoch + 1u;
+    }
+  }
+}
+
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f16(PersistArgs pa) { persist_body<true>(pa); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f32(PersistArgs pa) { persist_body<false>(pa); }
 
 // Dependency self-check: done-tokens per operator and a violation counter, in static
 // device memory (nothing is allocated).
@@ -1056,6 +1411,52 @@ hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNo
   np.blockDim = dim3(64);
   np.kernelParams = kparams;
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+int persist_kernel_id(int id) {
+  switch (id) {
+    case K_igemm_f16_direct8: case K_igemm_f16_direct16: return K_igemm_f16_direct4;
+    case K_igemm_f32_direct8: case K_igemm_f32_direct16: return K_igemm_f32_direct4;
+    default: return (id >= 0 && id < K_COUNT) ? id : -1;
+  }
+}
+
+bool kernel_is_f16(int id) {
+  switch (id) {
+#define X(name, A) case K_##name: return sizeof(#name) > 1 && __builtin_strstr(#name, "_f16") != nullptr;
+    OPARA_KERNEL_LIST(X)
+#undef X
+    default: return false;
+  }
+}
+
+hipError_t persist_max_workgroups(bool f16, uint32_t lds_bytes, uint32_t *n_workgroups) {
+  int dev = 0, cus = 0, per_cu = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  err = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (err != hipSuccess) return err;
+  const void *func = f16 ? (const void *)opara_k_persist_f16 : (const void *)opara_k_persist_f32;
+  err = hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (err != hipSuccess) return err;
+  err = f16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, opara_k_persist_f16, 256, lds_bytes)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, opara_k_persist_f32, 256, lds_bytes);
+  if (err != hipSuccess) return err;
+  *n_workgroups = (uint32_t)(per_cu > 0 ? per_cu : 0) * (uint32_t)cus;
+  return hipSuccess;
+}
+
+hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, uint32_t n_workgroups,
+                            uint32_t lds_bytes, hipGraphNode_t *node) {
+  PersistArgs args = a;
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = f16 ? (void *)opara_k_persist_f16 : (void *)opara_k_persist_f32;
+  np.gridDim = dim3(n_workgroups);
+  np.blockDim = dim3(256);
+  np.sharedMemBytes = lds_bytes;
+  np.kernelParams = kparams;
+  return hipGraphAddKernelNode(node, graph, nullptr, 0, &np);
 }
 
 hipError_t verify_reset(hipStream_t s) {

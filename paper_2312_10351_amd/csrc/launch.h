@@ -20,6 +20,59 @@ constexpr int kVerifyMaxPreds = 8;
 struct TokenArgs { int32_t epoch, self, n_preds, delay; int32_t preds[kVerifyMaxPreds]; };
 hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNode_t *deps, size_t n_deps,
                           hipGraphNode_t *node);
+
+// ---- Persistent executor: the whole DAG as one kernel -------------------------------
+// Workgroups of one launch draw (operator, tile) work items from a ticket counter in
+// launch-queue order; an item starts once the completion counters of its operator's
+// predecessors have reached their tile counts.  Records live in a caller-owned
+// workspace.  Positions ("pos") index operators in launch-queue order.
+constexpr int kPersistMaxPreds = 8;
+constexpr int kPersistCounterStride = 64;        // uint32 words between completion counters: one per 256 bytes
+constexpr int kPersistReplicas = 32;             // copies of each operator's "complete" flag, 128 bytes apart:
+constexpr int kPersistFlagStride = 32;           // a workgroup polls copy (blockIdx % replicas), so that a
+                                                 // flag has at most 1/32 of the waiting workgroups polling it
+constexpr uint32_t kPersistBodyLds = 2 * (128 + 64) * 144;   // largest body: the 128x64 pipelined tile
+constexpr uint32_t kPersistMaxLds = 160 * 1024;                // per workgroup on gfx950
+constexpr uint32_t kPersistDefaultSpinLimit = 1u << 22;
+constexpr int32_t kPersistActivationB = 0x100;   // added to a record's kernel id: the second
+                                                 // operand of the contraction is an activation
+struct PersistHeader {            // 64 bytes at the start of the workspace
+  uint32_t reserved0;
+  uint32_t exited;                // workgroups that have left; reset by the last one out
+  uint32_t epoch;                 // launch number (starts at 1); the last workgroup out advances it
+  uint32_t error;                 // sticky: 1 + pos of the operator whose wait ran out
+  uint32_t spin_limit;            // polls one wait may take before it gives up
+  uint64_t trace;                 // device address of the timeline buffer, 0 = off
+  uint32_t reserved[9];
+};
+// Predecessors of one operator as every workgroup keeps them in workgroup memory.
+struct PersistPredsLds { uint16_t n, tiles; uint16_t pos[kPersistMaxPreds]; };   // tiles: of this operator
+constexpr uint32_t persist_lds_bytes(uint32_t n) {
+  return kPersistBodyLds + 16 + 4 * (n + 1) + (uint32_t)sizeof(PersistPredsLds) * n;
+}
+struct PersistOp { int32_t kernel, gx, gy, gz; KernelArgs args; };
+struct PersistArgs {
+  PersistHeader *hdr;
+  uint32_t *done;                 // [n * kPersistCounterStride] tiles finished per operator (every
+                                  // kPersistCounterStride-th word); the workgroup that finishes the
+                                  // last tile sets it back to 0 and raises the operator's flags
+  uint32_t *flags;                // [n * kPersistReplicas * kPersistFlagStride]: copy r of operator p at
+                                  // word (p * kPersistReplicas + r) * kPersistFlagStride holds the
+                                  // number of the last launch in which p completed
+  const int32_t *item_begin;      // [n + 1] first ticket of each operator
+  const PersistPredsLds *preds;   // [n]
+  const PersistOp *rec;           // [n]
+  int32_t n, total;               // operators, work items
+};
+// Kernel ids the persistent kernel can run (256-thread bodies); others map through
+// persist_kernel_id (the 8- and 16-wavefront contractions run their 4-wavefront form).
+int persist_kernel_id(int kernel_id);              // -1: not available
+bool kernel_is_f16(int kernel_id);
+// Workgroups of the persistent kernel the device holds at once (all must be resident).
+hipError_t persist_max_workgroups(bool f16, uint32_t lds_bytes, uint32_t *n_workgroups);
+hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, uint32_t n_workgroups,
+                            uint32_t lds_bytes, hipGraphNode_t *node);
+
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter
 }  // namespace opara

@@ -59,6 +59,7 @@ class Session:
         self.device = device
         self.dag = None
         self.execs = []
+        self._workspaces = []
         self.streams = None
         self.capture_log = []
         self._seq_reference = None
@@ -227,6 +228,44 @@ class Session:
             B.opara_exec_destroy(exe)
         raise RuntimeError("no captured parallel graph reproduced the sequential result: "
                            "the graph runtime keeps dropping dependencies of this DAG")
+
+    def capture_persistent(self, policy=B.ORDER_ALG2, n_workgroups=0):
+        """Capture the whole DAG as one persistent kernel (work items in launch-queue order,
+        dependencies through completion counters).  The workspace is a torch allocation
+        kept alive by the session."""
+        import torch
+        B.opara_order_launch_policy(self.dag, policy)
+        nbytes = B.opara_persistent_workspace_bytes(self.dag)
+        ws = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.device)
+        ptr = (ws.data_ptr() + 255) // 256 * 256
+        torch.cuda.synchronize()
+        exe = B.opara_capture_persistent(self.dag, ptr, nbytes, n_workgroups)
+        self._workspaces.append(ws)
+        self.execs.append(exe)
+        return exe
+
+    def persistent_trace(self, exe):
+        """Replay once with the in-kernel timeline on.  Returns an int64 array [items, 5]:
+        lookup start, predecessors complete, body end (ns since the first event), queue
+        position, workgroup."""
+        import torch
+        items, _ = B.opara_persistent_info(exe)
+        buf = torch.zeros(items * 4, dtype=torch.int64, device=self.device)
+        h = self.make_streams(1).handles[0]
+        torch.cuda.synchronize()
+        B.opara_persistent_set_trace(exe, h, buf.data_ptr(), buf.numel() * 8)
+        self.replay(exe)
+        B.opara_persistent_set_trace(exe, h, 0, 0)
+        raw = buf.cpu().numpy().reshape(items, 4)
+        t = raw[:, :3] * 10                       # 100 MHz ticks -> ns
+        t = t - t.min()
+        return np.concatenate([t, (raw[:, 3:4] >> 32), (raw[:, 3:4] & 0xffffffff)], axis=1)
+
+    def persistent_status(self, exe):
+        return B.opara_persistent_status(exe, self.make_streams(1).handles[0])
+
+    def persistent_reset(self, exe, spin_limit=0):
+        B.opara_persistent_reset(exe, self.make_streams(1).handles[0], spin_limit)
 
     def _matches_sequential(self, exe):
         import torch

@@ -23,6 +23,10 @@ def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlie
             s.clear_outputs()
             if mode == "eager":
                 s.run_eager()
+            elif mode.startswith("persist"):              # "persist" or "persist:<workgroups>"
+                exe = s.capture_persistent(n_workgroups=int(mode.split(":")[1]) if ":" in mode else 0)
+                s.replay(exe)
+                assert s.persistent_status(exe) == 0, f"{wl.name} [{mode}]: a wait inside the kernel ran out"
             else:
                 exe = s.capture({"seq": B.SEQUENTIAL, "par": B.PARALLEL, "capture": B.PARALLEL_CAPTURE}[mode])
                 s.replay(exe)
