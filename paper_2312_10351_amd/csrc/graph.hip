@@ -310,7 +310,7 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     if (t < 1 || t > 65535 || total + t > INT32_MAX) { set_error("opara_capture_persistent: work-item count out of range"); return OPARA_EUNSUPPORTED; }
     tiles[i] = (uint32_t)t;
     begin[i] = (int32_t)total;
-    total += t;
+    total += (t + kPersistItemAlign - 1) / kPersistItemAlign * kPersistItemAlign;
     rec[i].kernel = kid + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
     rec[i].gx = (int32_t)p.gx; rec[i].gy = (int32_t)p.gy; rec[i].gz = (int32_t)p.gz;
     rec[i].args = p.args;
@@ -333,6 +333,7 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     if (wgs == 0) { set_error("opara_capture_persistent: the kernel does not fit a compute unit"); goto fail; }
     if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
     if ((int64_t)wgs > total) wgs = (uint32_t)total;
+    if (wgs > (uint32_t)kPersistItemAlign) wgs -= wgs % kPersistItemAlign;
     HIP_TRY(hipMemcpy(workspace, host.data(), lay.bytes, hipMemcpyHostToDevice));
     PersistArgs pa;
     unsigned char *ws = (unsigned char *)workspace;

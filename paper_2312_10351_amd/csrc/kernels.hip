@@ -39,6 +39,7 @@ template <> struct Vec16<float> { typedef floatx4 type; typedef floatx4 quad; st
 // cache write-back or invalidate.  Weights are never written and stay plain (L2-cached).
 constexpr int kCohAct = 1;     // first operand, residual inputs, row/element inputs, outputs
 constexpr int kCohW = 2;       // second operand too (batched GEMM of two activations)
+constexpr int kCohStore = 4;   // outputs only: loads stay plain and follow a cache invalidate
 
 template <bool COH, typename V, typename P>
 __device__ __forceinline__ V ldg(const P *p) {
@@ -132,7 +133,7 @@ __device__ __forceinline__ void igemm_body(const AR &a, const Blk &b, unsigned c
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wn0 = (wave % WN) * (BN / WN), wm0 = (wave / WN) * (BM / WM);
   const int m0 = b.x * BM, n0 = b.y * BN;
-  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
   const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
   T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
@@ -314,11 +315,11 @@ __device__ __forceinline__ void igemm_body(const AR &a, const Blk &b, unsigned c
       T *dst = y + (int64_t)m * a.ldy + n;
       if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        stg<CA, Q>(dst, q4);
+        stg<CS, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
+          if (n + e < a.N) stg<CS, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -377,7 +378,7 @@ __device__ __forceinline__ void igemm_pipe_body(const AR &a, const Blk &b, unsig
   int tile_x, tile_y;
   xcd_tile(b, tile_x, tile_y);
   const int m0 = tile_x * BM, n0 = tile_y * BN;
-  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
   const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
   T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
@@ -522,11 +523,11 @@ __device__ __forceinline__ void igemm_pipe_body(const AR &a, const Blk &b, unsig
       T *dst = y + (int64_t)m * a.ldy + n;
       if (n + 3 < a.N && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        stg<CA, Q>(dst, q4);
+        stg<CS, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
+          if (n + e < a.N) stg<CS, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -555,7 +556,7 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
   int tile_x, tile_y;
   xcd_tile(b, tile_x, tile_y);
   const int m0 = tile_x * 32, n0 = tile_y * 32;
-  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
   const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
   T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
@@ -692,11 +693,11 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
       T *dst = y + (int64_t)m * a.ldy + n;
       if (full && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
         Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
-        stg<CA, Q>(dst, q4);
+        stg<CS, Q>(dst, q4);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (n + e < a.N) stg<CA, T>(dst + e, (T)v[e]);
+          if (n + e < a.N) stg<CS, T>(dst + e, (T)v[e]);
       }
     }
   }
@@ -711,7 +712,7 @@ __device__ __forceinline__ void gemv_body(const AR &a, const Blk &b, unsigned ch
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = b.x * 4 + wave;
   if (n >= a.N) return;
-  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const T *__restrict__ x = (const T *)a.x;
   const T *__restrict__ wr = (const T *)a.w + (int64_t)n * a.ldb;
   float acc[kGemvMaxM] = {0.f, 0.f, 0.f, 0.f};
@@ -737,7 +738,7 @@ __device__ __forceinline__ void gemv_body(const AR &a, const Blk &b, unsigned ch
       if (a.bias) r += a.bias[n];
       for (int q = 0; q < a.n_extra; ++q) r += (float)ldg<CA, T>((const T *)a.extra[q] + (int64_t)m * a.N + n);
       if (a.relu) r = fmaxf(r, 0.f);
-      stg<CA, T>(y + (int64_t)m * a.ldy + n, (T)r);
+      stg<CS, T>(y + (int64_t)m * a.ldy + n, (T)r);
     }
   }
 }
@@ -747,7 +748,7 @@ __device__ __forceinline__ void gemv_body(const AR &a, const Blk &b, unsigned ch
 // ---------------------------------------------------------------------------------
 template <typename T, int VE, int COH, typename AR>
 __device__ __forceinline__ void pool_body(const AR &a, const Blk &b, unsigned char *lds) {
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const int cch = a.C / VE;
   const int64_t item = (int64_t)b.x * 256 + threadIdx.x;
   if (item >= (int64_t)a.B * a.Ho * a.Wo * cch) return;
@@ -798,8 +799,8 @@ __device__ __forceinline__ void pool_body(const AR &a, const Blk &b, unsigned ch
 #pragma unroll
   for (int e = 0; e < VE; ++e) o[e] = (T)(a.is_avg ? acc[e] * scale : acc[e]);
   T *dst = (T *)a.y + (int64_t)pix * a.C + cc * VE;
-  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
-  else stg<CA, T>(dst, o[0]);
+  if constexpr (VE > 1) stg<CS, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
+  else stg<CS, T>(dst, o[0]);
 }
 
 // Global average pool over [HW][C]: 256 threads = 64 channels x 4 pixel slices; each
@@ -809,7 +810,7 @@ __device__ __forceinline__ void gap_body(const AR &a, const Blk &b, unsigned cha
   float (*part)[64] = (float (*)[64])lds;                                              // [4][64]
   const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int c = b.x * 64 + cl;
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const T *__restrict__ x = (const T *)a.x + (int64_t)b.y * a.HW * a.C;
   float s = 0.f;
   if (c < a.C) {
@@ -824,7 +825,7 @@ __device__ __forceinline__ void gap_body(const AR &a, const Blk &b, unsigned cha
   part[slice][cl] = s;
   __syncthreads();
   if (slice == 0 && c < a.C)
-    stg<CA, T>((T *)a.y + (int64_t)b.y * a.C + c, (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW));
+    stg<CS, T>((T *)a.y + (int64_t)b.y * a.C + c, (T)((part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)a.HW));
 }
 
 // ---------------------------------------------------------------------------------
@@ -856,7 +857,7 @@ __device__ __forceinline__ void row_cached_body(const AR &a, const Blk &b, unsig
   typedef typename Vec16<T>::type V;
   constexpr int VE = Vec16<T>::N;
   float *scratch = (float *)lds;                                                       // [4]
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const int gl = threadIdx.x % G;
   const int row = b.x * (256 / G) + threadIdx.x / G;
   if (G == 64 && row >= a.rows) return;          // whole wavefront leaves together
@@ -922,7 +923,7 @@ __device__ __forceinline__ void row_cached_body(const AR &a, const Blk &b, unsig
       V o;
 #pragma unroll
       for (int e = 0; e < VE; ++e) o[e] = (T)v[c][e];
-      stg<CA, V>((T *)a.y + base + col, o);
+      stg<CS, V>((T *)a.y + base + col, o);
     }
   }
 }
@@ -931,7 +932,7 @@ __device__ __forceinline__ void row_cached_body(const AR &a, const Blk &b, unsig
 template <typename T, bool IS_LN, int COH, typename AR>
 __device__ __forceinline__ void row_generic_body(const AR &a, const Blk &b, unsigned char *lds) {
   float *scratch = (float *)lds;                                                       // [4]
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const int64_t base = (int64_t)b.x * a.cols;
   auto value = [&](int col) {
     float s = 0.f;
@@ -950,7 +951,7 @@ __device__ __forceinline__ void row_generic_body(const AR &a, const Blk &b, unsi
   const float k = IS_LN ? 1.0f / sqrtf(r2 / (float)a.cols + a.eps) : 1.0f / r2;
   for (int col = threadIdx.x; col < a.cols; col += 256) {
     const float d = value(col) - r1;
-    stg<CA, T>((T *)a.y + base + col, (T)(IS_LN ? d * k : expf(d) * k));
+    stg<CS, T>((T *)a.y + base + col, (T)(IS_LN ? d * k : expf(d) * k));
   }
 }
 
@@ -965,7 +966,7 @@ __device__ __forceinline__ float elt_apply(int op, float x) {
 
 template <typename T, int VE, int COH, typename AR>
 __device__ __forceinline__ void elt_body(const AR &a, const Blk &b, unsigned char *lds) {
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const int64_t i = ((int64_t)b.x * 256 + threadIdx.x) * VE;
   if (i >= a.n) return;
   float s[VE];
@@ -983,13 +984,13 @@ __device__ __forceinline__ void elt_body(const AR &a, const Blk &b, unsigned cha
 #pragma unroll
   for (int e = 0; e < VE; ++e) o[e] = (T)elt_apply(a.op, s[e]);
   T *dst = (T *)a.y + i;
-  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
-  else stg<CA, T>(dst, o[0]);
+  if constexpr (VE > 1) stg<CS, typename Vec16<T>::type>(dst, *(const typename Vec16<T>::type *)o);
+  else stg<CS, T>(dst, o[0]);
 }
 
 template <typename T, int VE, int COH, typename AR>
 __device__ __forceinline__ void concat_body(const AR &a, const Blk &b, unsigned char *lds) {
-  constexpr bool CA = (COH & kCohAct) != 0;
+  constexpr bool CA = (COH & kCohAct) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
   const int q = b.y;
   const int cch = a.cols[q] / VE;
   const int64_t item = (int64_t)b.x * 256 + threadIdx.x;
@@ -998,8 +999,8 @@ __device__ __forceinline__ void concat_body(const AR &a, const Blk &b, unsigned 
   const int c = (int)(item % cch) * VE;
   const T *src = (const T *)a.in[q] + r * a.cols[q] + c;
   T *dst = (T *)a.y + r * a.out_cols + a.col_off[q] + c;
-  if constexpr (VE > 1) stg<CA, typename Vec16<T>::type>(dst, ldg<CA, typename Vec16<T>::type>(src));
-  else stg<CA, T>(dst, ldg<CA, T>(src));
+  if constexpr (VE > 1) stg<CS, typename Vec16<T>::type>(dst, ldg<CA, typename Vec16<T>::type>(src));
+  else stg<CS, T>(dst, ldg<CA, T>(src));
 }
 
 }  // namespace opara
@@ -1090,6 +1091,14 @@ template <typename A> __device__ __forceinline__ A load_uniform(const void *p) {
   return u.a;
 }
 
+// Inputs inside the persistent kernel: either every load is device-coherent, or loads are
+// plain and each work item starts with one cache invalidate (acquire at device scope).
+#ifndef OPARA_PERSIST_COHERENT_LOADS
+#define OPARA_PERSIST_COHERENT_LOADS 0
+#endif
+constexpr int kPersistAct = OPARA_PERSIST_COHERENT_LOADS ? kCohAct : kCohStore;
+constexpr int kPersistActW = OPARA_PERSIST_COHERENT_LOADS ? (kCohAct | kCohW) : kCohStore;
+
 template <bool F16>
 __device__ __forceinline__ void persist_run(int kernel, const PersistOp *r, const Blk &b, unsigned char *lds) {
 #define PCASE_(label, Args, call)                             \
@@ -1102,54 +1111,54 @@ __device__ __forceinline__ void persist_run(int kernel, const PersistOp *r, cons
 #define PCASEW(name, Args, call) PCASE_(K_##name + kPersistActivationB, Args, call)
   if (F16) {
     switch (kernel) {
-      PCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kCohAct>(a, b, lds)))
-      PCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kCohAct>(a, b, lds)))
-      PCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 4, kCohAct>(a, b, lds)))
-      PCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kCohAct>(a, b, lds)))
-      PCASEW(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 4, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kCohAct | kCohW>(a, b, lds)))
-      PCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, kCohAct>(a, b, lds)))
-      PCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, kCohAct>(a, b, lds)))
-      PCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, kCohAct>(a, b, lds)))
-      PCASE(gap_f16, GapArgs, (gap_body<half_t, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f16_wave, RowArgs, (row_cached_body<half_t, true, 64, 2, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f16_block, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f16_generic, RowArgs, (row_generic_body<half_t, true, kCohAct>(a, b, lds)))
-      PCASE(softmax_f16_wave, RowArgs, (row_cached_body<half_t, false, 64, 2, kCohAct>(a, b, lds)))
-      PCASE(softmax_f16_block, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
-      PCASE(softmax_f16_generic, RowArgs, (row_generic_body<half_t, false, kCohAct>(a, b, lds)))
-      PCASE(elt_f16_vec, EltArgs, (elt_body<half_t, 8, kCohAct>(a, b, lds)))
-      PCASE(elt_f16_scalar, EltArgs, (elt_body<half_t, 1, kCohAct>(a, b, lds)))
-      PCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, kCohAct>(a, b, lds)))
-      PCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, kCohAct>(a, b, lds)))
+      PCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kPersistAct>(a, b, lds)))
+      PCASEW(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, kPersistActW>(a, b, lds)))
+      PCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, kPersistAct>(a, b, lds)))
+      PCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, kPersistAct>(a, b, lds)))
+      PCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, kPersistAct>(a, b, lds)))
+      PCASE(gap_f16, GapArgs, (gap_body<half_t, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f16_wave, RowArgs, (row_cached_body<half_t, true, 64, 2, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f16_block, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f16_generic, RowArgs, (row_generic_body<half_t, true, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f16_wave, RowArgs, (row_cached_body<half_t, false, 64, 2, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f16_block, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f16_generic, RowArgs, (row_generic_body<half_t, false, kPersistAct>(a, b, lds)))
+      PCASE(elt_f16_vec, EltArgs, (elt_body<half_t, 8, kPersistAct>(a, b, lds)))
+      PCASE(elt_f16_scalar, EltArgs, (elt_body<half_t, 1, kPersistAct>(a, b, lds)))
+      PCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, kPersistAct>(a, b, lds)))
+      PCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, kPersistAct>(a, b, lds)))
       default: break;
     }
   } else {
     switch (kernel) {
-      PCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kCohAct>(a, b, lds)))
-      PCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kCohAct>(a, b, lds)))
-      PCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 4, kCohAct>(a, b, lds)))
-      PCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kCohAct>(a, b, lds)))
-      PCASEW(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 4, kCohAct | kCohW>(a, b, lds)))
-      PCASEW(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kCohAct | kCohW>(a, b, lds)))
-      PCASE(gemv_f32, IgemmArgs, (gemv_body<float, kCohAct>(a, b, lds)))
-      PCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, kCohAct>(a, b, lds)))
-      PCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, kCohAct>(a, b, lds)))
-      PCASE(gap_f32, GapArgs, (gap_body<float, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f32_wave, RowArgs, (row_cached_body<float, true, 64, 2, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f32_block, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
-      PCASE(layernorm_f32_generic, RowArgs, (row_generic_body<float, true, kCohAct>(a, b, lds)))
-      PCASE(softmax_f32_wave, RowArgs, (row_cached_body<float, false, 64, 2, kCohAct>(a, b, lds)))
-      PCASE(softmax_f32_block, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, kCohAct>(a, b, lds)))
-      PCASE(softmax_f32_generic, RowArgs, (row_generic_body<float, false, kCohAct>(a, b, lds)))
-      PCASE(elt_f32_vec, EltArgs, (elt_body<float, 4, kCohAct>(a, b, lds)))
-      PCASE(elt_f32_scalar, EltArgs, (elt_body<float, 1, kCohAct>(a, b, lds)))
-      PCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, kCohAct>(a, b, lds)))
-      PCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, kCohAct>(a, b, lds)))
+      PCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, kPersistAct>(a, b, lds)))
+      PCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kPersistAct>(a, b, lds)))
+      PCASEW(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, kPersistActW>(a, b, lds)))
+      PCASEW(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, kPersistActW>(a, b, lds)))
+      PCASE(gemv_f32, IgemmArgs, (gemv_body<float, kPersistAct>(a, b, lds)))
+      PCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, kPersistAct>(a, b, lds)))
+      PCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, kPersistAct>(a, b, lds)))
+      PCASE(gap_f32, GapArgs, (gap_body<float, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f32_wave, RowArgs, (row_cached_body<float, true, 64, 2, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f32_block, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, kPersistAct>(a, b, lds)))
+      PCASE(layernorm_f32_generic, RowArgs, (row_generic_body<float, true, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f32_wave, RowArgs, (row_cached_body<float, false, 64, 2, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f32_block, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, kPersistAct>(a, b, lds)))
+      PCASE(softmax_f32_generic, RowArgs, (row_generic_body<float, false, kPersistAct>(a, b, lds)))
+      PCASE(elt_f32_vec, EltArgs, (elt_body<float, 4, kPersistAct>(a, b, lds)))
+      PCASE(elt_f32_scalar, EltArgs, (elt_body<float, 1, kPersistAct>(a, b, lds)))
+      PCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, kPersistAct>(a, b, lds)))
+      PCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, kPersistAct>(a, b, lds)))
       default: break;
     }
   }
@@ -1255,6 +1264,9 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
   for (uint32_t item = blockIdx.x; item < (uint32_t)pa.total; item += gridDim.x) {
     const int pos = __builtin_amdgcn_readfirstlane(persist_find(begin, pa.n, item));
     const int tile = (int)(item - (uint32_t)begin[pos]);
+    // Operators start at multiples of kPersistItemAlign in the item space; the items that
+    // pad an operator out denote no tile.
+    const bool padding = tile >= (int)preds[pos].tiles;
     if (tid == 0) {
       if (prev >= 0) {
         persist_publish(pa, preds, prev, epoch);
@@ -1266,28 +1278,36 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
         }
       }
       if (trace) t_begin = wall_clock64();
-      if (!persist_wait(pa, preds + pos, pos, epoch, limit)) ctl[0] = 1;
+      if (!padding && !persist_wait(pa, preds + pos, pos, epoch, limit)) ctl[0] = 1;
       if (trace) t_ready = wall_clock64();
     }
+    if (!OPARA_PERSIST_COHERENT_LOADS && tid < 64)               // one wavefront invalidates the caches this
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");         // workgroup reads through (L1 of the CU, L2 of the XCD)
     __syncthreads();                                             // predecessors complete (or abort)
     if (ctl[0]) { prev = -1; break; }
+    if (padding) { prev = -1; continue; }
     const PersistOp *r = pa.rec + pos;
     const int4 hd = load_uniform<int4>(r);                       // kernel, gx, gy, gz
-    // Touch the next item's record now so that its argument loads find it in the scalar
-    // cache; the values are only summed into a sink that is tested after the loop.
-    const uint32_t nitem = item + gridDim.x;
-    const int npos = nitem < (uint32_t)pa.total ? persist_find(begin, pa.n, nitem) : pos;
-    const unsigned char *nr = (const unsigned char *)(pa.rec + __builtin_amdgcn_readfirstlane(npos));
-    const uint32_t p0 = load_uniform<uint32_t>(nr), p1 = load_uniform<uint32_t>(nr + 64);
-    const uint32_t p2 = load_uniform<uint32_t>(nr + 128), p3 = load_uniform<uint32_t>(nr + 192);
     Blk b;
-    b.gx = hd.y; b.gy = hd.z; b.remap = false;
+    b.gx = hd.y; b.gy = hd.z;
+    // With the workgroup count and every operator's first item multiples of the XCD count,
+    // tile t runs on XCD t % 8 exactly as in an ordinary launch: the same remap applies.
+    b.remap = (gridDim.x % kPersistItemAlign) == 0;
     b.x = tile % hd.y;
     const int rest = tile / hd.y;
     b.y = rest % hd.z;
     b.z = rest / hd.z;
     persist_run<F16>(hd.x, r, b, lds);
-    sink += (p0 ^ p1) + (p2 ^ p3);
+    // While the stores drain: touch the next item's record so that its argument loads find
+    // it in the scalar cache.  The values only feed a sink that is tested after the loop.
+    {
+      const uint32_t nitem = item + gridDim.x;
+      const int npos = nitem < (uint32_t)pa.total ? persist_find(begin, pa.n, nitem) : pos;
+      const unsigned char *nr = (const unsigned char *)(pa.rec + __builtin_amdgcn_readfirstlane(npos));
+      const uint32_t p0 = load_uniform<uint32_t>(nr), p1 = load_uniform<uint32_t>(nr + 64);
+      const uint32_t p2 = load_uniform<uint32_t>(nr + 128), p3 = load_uniform<uint32_t>(nr + 192);
+      sink += (p0 ^ p1) + (p2 ^ p3);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): this wavefront's stores are complete
     __syncthreads();                                             // ... for every wavefront, and ctl has been read
     prev = pos;

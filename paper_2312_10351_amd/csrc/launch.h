@@ -27,6 +27,7 @@ hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNo
 // predecessors have reached their tile counts.  Records live in a caller-owned
 // workspace.  Positions ("pos") index operators in launch-queue order.
 constexpr int kPersistMaxPreds = 8;
+constexpr int kPersistItemAlign = 8;             // XCDs: workgroup w runs on XCD w % 8
 constexpr int kPersistCounterStride = 64;        // uint32 words between completion counters: one per 256 bytes
 constexpr int kPersistReplicas = 32;             // copies of each operator's "complete" flag, 128 bytes apart:
 constexpr int kPersistFlagStride = 32;           // a workgroup polls copy (blockIdx % replicas), so that a

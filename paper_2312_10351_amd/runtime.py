@@ -245,7 +245,7 @@ class Session:
         return exe
 
     def persistent_trace(self, exe):
-        """Replay once with the in-kernel timeline on.  Returns an int64 array [items, 5]:
+        """Replay once with the in-kernel timeline on.  Returns an int64 array [tiles, 5]:
         lookup start, predecessors complete, body end (ns since the first event), queue
         position, workgroup."""
         import torch
@@ -257,6 +257,7 @@ class Session:
         self.replay(exe)
         B.opara_persistent_set_trace(exe, h, 0, 0)
         raw = buf.cpu().numpy().reshape(items, 4)
+        raw = raw[raw[:, 2] != 0]                 # items that only pad an operator's range record nothing
         t = raw[:, :3] * 10                       # 100 MHz ticks -> ns
         t = t - t.min()
         return np.concatenate([t, (raw[:, 3:4] >> 32), (raw[:, 3:4] & 0xffffffff)], axis=1)

@@ -66,7 +66,7 @@ def test_replays_are_identical_and_rewrite_every_output():
         assert B.opara_exec_info(exe) == (1, 0)
         items, wgs = B.opara_persistent_info(exe)
         dem = B.opara_get_demands(s.dag)
-        assert items == sum(d.grid_blocks for d in dem) and 1 <= wgs <= items
+        assert items == sum((d.grid_blocks + 7) // 8 * 8 for d in dem) and 1 <= wgs <= items   # ranges padded to the XCD count
     finally:
         s.close()
 
