@@ -23,8 +23,10 @@ sys.path.insert(0, ROOT)
 
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
-# a streaming kernel of known size (profiles/igemm_f16_direct4_hbm_traffic.md).
-MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): 1493 * 1024}
+# a streaming kernel of known size (profiles/igemm_f16_direct4_hbm_traffic.md,
+# profiles/persist_f16_googlenet_like_hbm_traffic.md).
+MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): 1493 * 1024,
+                          ("googlenet_like", "persist_f16"): (62425 + 31307) * 1024}
 
 
 def percentile(a, q):

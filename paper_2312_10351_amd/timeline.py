@@ -1,0 +1,66 @@
+"""Per-operator timeline of one replay of the persistent executor.
+
+A profiler sees a single kernel, so the executor stamps every work item itself (100 MHz
+device clock).  This tool replays one config with the timeline on and prints, per operator in
+launch-queue order: tiles, when its first tile had its predecessors complete, when its last
+tile was published, and the median tile time; then the overlap summary (operators in flight,
+busy fraction of the workgroups).  It is the counterpart of a kernel-trace timeline for the
+multi-stream graph (paper Sec. 5.3 looks at the same thing through SM utilisation).
+
+  python -m paper_2312_10351_amd.timeline [--config 1] [--policy alg2] [--rows 200]
+"""
+import argparse
+import json
+
+import numpy as np
+
+
+def operator_timeline(session, exe, order):
+    from . import binding as B
+    tr = session.persistent_trace(exe)
+    dem = B.opara_get_demands(session.dag)
+    rows = []
+    for pos, v in enumerate(order):
+        m = tr[:, 3] == pos
+        op = session.wl.ops[v]
+        rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(dem[v].kernel_id)[0],
+                         tiles=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
+                         last_published_us=float(tr[m, 2].max()) / 1e3,
+                         median_tile_us=float(np.median(tr[m, 2] - tr[m, 1])) / 1e3,
+                         median_wait_us=float(np.median(tr[m, 1] - tr[m, 0])) / 1e3))
+    return rows
+
+
+def main():
+    from . import binding as B
+    from .runtime import Session
+    from workloads import build_config
+    import bench
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--policy", default="alg2", choices=list(B.ORDER_POLICY_NAMES))
+    ap.add_argument("--rows", type=int, default=200)
+    a = ap.parse_args()
+    pol = list(B.ORDER_POLICY_NAMES).index(a.policy)
+    s = Session(build_config(a.config))
+    try:
+        exe = s.capture_persistent(policy=pol)
+        for _ in range(5):
+            s.replay(exe)
+        order = B.opara_order_launch_policy(s.dag, pol)
+        rows = operator_timeline(s, exe, order)
+        print("| pos | op | name | kernel | tiles | first ready us | last published us | median tile us | median wait us |")
+        print("|---|---|---|---|---|---|---|---|---|")
+        for r in rows[:a.rows]:
+            print(f"| {r['pos']} | {r['op']} | {r['name']} | {r['kernel']} | {r['tiles']} | {r['first_ready_us']:.1f} | "
+                  f"{r['last_published_us']:.1f} | {r['median_tile_us']:.2f} | {r['median_wait_us']:.2f} |")
+        print()
+        print(json.dumps(bench.timeline_summary(s, exe)))
+        if s.persistent_status(exe) != 0:
+            raise SystemExit("a wait inside the kernel ran out")
+    finally:
+        s.close()
+
+
+if __name__ == "__main__":
+    main()
