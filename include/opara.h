@@ -81,10 +81,13 @@ typedef struct {
 /*
  * Shape parameters.  Which fields an operator reads:
  *   CONV2D            h_in,w_in,c_in, h_out,w_out,c_out, kh,kw,sh,sw,ph,pw, flags(RELU), batch
- *                     (images, 0 = 1; activations are then [batch][H][W][C]).
+ *                     (images, 0 = 1; activations are then [batch][H][W][C]); c_row_stride
+ *                     (0 = c_out): elements between output pixels, for writing a channel
+ *                     slice of a wider tensor.
  *                     y[oh][ow][co] = bias[co] + sum x[oh*sh+i-ph][ow*sw+j-pw][ci]*w[co][i][j][ci],
  *                     zero padding, cross-correlation, floor output size.
- *   GEMM              m,n,k, flags(RELU).  Y[m][n] = X[m][k].W + bias + sum of inputs[1..] viewed [m][n].
+ *   GEMM              m,n,k, flags(RELU), c_row_stride (0 = n: output row stride).
+ *                     Y[m][n] = X[m][k].W + bias + sum of inputs[1..] viewed [m][n].
  *   BGEMM             batch,m,n,k, alpha, the six strides (in elements), flags(B_KMAJOR).
  *                     C_b[m][n] = alpha * A_b[m][k] . B_b ; A = inputs[0], B = inputs[1].
  *   MAXPOOL/AVGPOOL   h_in,w_in,c_in,h_out,w_out, kh,kw,sh,sw,ph,pw, batch.  Max pads with -inf;
@@ -126,6 +129,13 @@ typedef struct {
   const void *weight;                  /* device, caller-owned (CONV2D, GEMM), else NULL    */
   const float *bias;                   /* device fp32, caller-owned, may be NULL            */
   void *out;                           /* device, caller-owned, distinct per operator       */
+  int32_t  n_deps;                     /* 0..OPARA_MAX_INPUTS                               */
+  int32_t  deps[OPARA_MAX_INPUTS];     /* further predecessors (operator ids) whose results
+                                          are not arguments: they reach this operator through
+                                          an external tensor slot that several producers fill
+                                          (zero-copy concatenation: each branch writes its
+                                          channel slice of one buffer).  They follow the
+                                          arguments in the predecessor order.               */
 } opara_op_desc;
 
 /* What opara_get_demands reports per operator. */
@@ -138,7 +148,7 @@ typedef struct {
 
 /*
  * Build the DAG (paper Sec. 3.1).  Validates ids and shapes, drops repeated
- * producers keeping the first, computes the topological order (ready operator with
+ * producers keeping the first (arguments, then deps), computes the topological order (ready operator with
  * the smallest id first), selects a kernel and launch shape per operator and
  * derives its demand record.  ops/ext_inputs are copied; nothing is retained.
  * Errors: EINVAL (null, n_ops <= 0, id out of range, bad n_inputs, bad shape),

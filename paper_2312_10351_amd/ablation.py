@@ -1,6 +1,6 @@
 """Launch-order and interference ablations over the same kernels and graphs.
 
-  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32]
+  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32] [--concat-configs 0,1,2]
 
 Part 1 (paper Sec. 2.3, "GPU blocking"): the parallel graph is captured with each
 launch-order policy of opara_order_launch_policy and replayed; only the queue differs.
@@ -8,6 +8,7 @@ Part 2 (paper Sec. 2.3, "Performance interference"): two independent operators a
 replayed alone, back to back on one stream, and side by side on two streams, for a
 compute-intensive + memory-intensive pair and for two pairs of one class.
 Part 3 (paper Sec. 5.2): batch sweep of the Inception-v3-like DAG.
+Part 4: zero-copy concatenation against explicit concatenation kernels (CNN configs).
 Prints one JSON object per line.
 """
 import argparse
@@ -71,6 +72,26 @@ def batch_sweep(batch, replays):
         s.close()
 
 
+def concat_ablation(index, replays):
+    """Zero-copy concatenation (branches write channel slices in place, the concatenation
+    operators disappear) against explicit concatenation kernels, in all three executors."""
+    from . import binding as B
+    from .runtime import Session
+    from workloads import build_config, concat_elision_plan
+    wl = build_config(index)
+    out = {"ablation": "zero_copy_concat", "workload": wl.name, "concats": sum(o.type == "concat" for o in wl.ops),
+           "elided": len(concat_elision_plan(wl))}
+    for tag, zc in (("explicit", False), ("zero_copy", True)):
+        s = Session(wl, zero_copy_concat=zc)
+        try:
+            out[tag] = {"sequential_us": replay_latency(s, s.capture(B.SEQUENTIAL), replays),
+                        "multi_stream_graph_us": replay_latency(s, s.capture(B.PARALLEL), replays),
+                        "persistent_us": replay_latency(s, s.capture_persistent(), replays)}
+        finally:
+            s.close()
+    return out
+
+
 def _pair(kind_a, kind_b):
     """Two independent operators of the given classes reading the same external tensor."""
     from workloads import Builder
@@ -117,7 +138,10 @@ def main():
     ap.add_argument("--configs", default="0,1,2,3,4")
     ap.add_argument("--replays", type=int, default=300)
     ap.add_argument("--batches", default="1,2,4,8,16,32")
+    ap.add_argument("--concat-configs", default="0,1,2")
     a = ap.parse_args()
+    for idx in [int(x) for x in a.concat_configs.split(",") if x]:
+        print(json.dumps(concat_ablation(idx, a.replays)), flush=True)
     for bsz in [int(x) for x in a.batches.split(",") if x]:
         print(json.dumps(batch_sweep(bsz, max(50, a.replays // 3))), flush=True)
     for idx in [int(x) for x in a.configs.split(",") if x]:

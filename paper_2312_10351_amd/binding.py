@@ -51,7 +51,8 @@ class OpDesc(C.Structure):
                 ("grid_blocks", C.c_uint32), ("block_threads", C.c_uint32),
                 ("lds_bytes", C.c_uint32), ("vgprs", C.c_uint32),
                 ("params", OpParams),
-                ("weight", C.c_void_p), ("bias", C.c_void_p), ("out", C.c_void_p)]
+                ("weight", C.c_void_p), ("bias", C.c_void_p), ("out", C.c_void_p),
+                ("n_deps", C.c_int32), ("deps", C.c_int32 * MAX_INPUTS)]
 
 
 class Demand(C.Structure):

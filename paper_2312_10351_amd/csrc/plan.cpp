@@ -66,14 +66,16 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     a.gather = !(p.kh == 1 && p.kw == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0);
     a.H = p.h_in; a.W = p.w_in; a.Cin = p.c_in; a.Wo = p.w_out;
     a.kh = p.kh; a.kw = p.kw; a.sh = p.sh; a.sw = p.sw; a.ph = p.ph; a.pw = p.pw;
-    a.lda = p.c_in; a.ldb = a.K; a.ldy = p.c_out;
+    if (p.c_row_stride != 0 && p.c_row_stride < p.c_out) return fail("output pixel stride below c_out", op);
+    a.lda = p.c_in; a.ldb = a.K; a.ldy = p.c_row_stride ? p.c_row_stride : p.c_out;
     vec = (p.c_in % ve == 0);
   } else if (op.op_type == OPARA_GEMM) {
     if (!op.weight || op.n_inputs > 4) return fail("GEMM needs a weight and at most 3 extra inputs", op);
     if (p.m <= 0 || p.n <= 0 || p.k <= 0) return fail("bad GEMM shape", op);
     a.w = op.weight;
     a.M = p.m; a.N = p.n; a.K = p.k;
-    a.lda = p.k; a.ldb = p.k; a.ldy = p.n;
+    if (p.c_row_stride != 0 && p.c_row_stride < p.n) return fail("output row stride below n", op);
+    a.lda = p.k; a.ldb = p.k; a.ldy = p.c_row_stride ? p.c_row_stride : p.n;
     a.HoWo = p.m; a.Wo = 1;
     a.n_extra = op.n_inputs - 1;
     for (int i = 0; i < a.n_extra; ++i) a.extra[i] = in[i + 1];

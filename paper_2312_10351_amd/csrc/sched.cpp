@@ -83,11 +83,17 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
         rc = OPARA_EINVAL; break;
       }
       if (!op.out) { set_error("operator %d: null output pointer", v); rc = OPARA_EINVAL; break; }
-      for (int i = 0; i < op.n_inputs; ++i) {
-        const int32_t u = op.inputs[i];
+      if (op.n_deps < 0 || op.n_deps > OPARA_MAX_INPUTS) {
+        set_error("operator %d: n_deps %d outside 0..%d", v, op.n_deps, OPARA_MAX_INPUTS);
+        rc = OPARA_EINVAL; break;
+      }
+      for (int i = 0; i < op.n_inputs + op.n_deps; ++i) {
+        const bool is_dep = i >= op.n_inputs;
+        const int32_t u = is_dep ? op.deps[i - op.n_inputs] : op.inputs[i];
         if (u == v) { set_error("operator %d reads its own output", v); rc = OPARA_ECYCLE; break; }
-        if (u >= n_ops || (u < 0 && -(int64_t)u - 1 >= n_ext)) {
-          set_error("operator %d: input %d refers to %d, out of range", v, i, u);
+        if (u >= n_ops || (u < 0 && (is_dep || -(int64_t)u - 1 >= n_ext))) {
+          set_error("operator %d: %s %d refers to %d, out of range", v, is_dep ? "dependency" : "input",
+                    is_dep ? i - op.n_inputs : i, u);
           rc = OPARA_EINVAL; break;
         }
         if (u < 0) continue;
@@ -95,6 +101,7 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
         for (int32_t j = g->pred_off[v]; j < (int32_t)g->pred.size(); ++j) dup |= (g->pred[j] == u);
         if (!dup) g->pred.push_back(u);
       }
+      if (rc != OPARA_OK) break;
       g->pred_off[v + 1] = (int32_t)g->pred.size();
     }
     if (rc != OPARA_OK) { delete g; return rc; }

@@ -50,11 +50,19 @@ class StreamSet:
 class Session:
     """One workload bound to device buffers and a built DAG handle."""
 
-    def __init__(self, wl, device="cuda:0", demand_override=None, class_override=None, pad_channels=True):
+    def __init__(self, wl, device="cuda:0", demand_override=None, class_override=None, pad_channels=True,
+                 zero_copy_concat=False):
         """pad_channels: an external image whose channel count is not a multiple of the
         16-byte vector width and that feeds convolutions only is stored with zero
         channels appended (and the weights with matching zero taps) - a storage layout,
-        the results are unchanged."""
+        the results are unchanged.
+        zero_copy_concat: a channel concatenation whose inputs are convolutions with no other
+        consumer is not executed: each branch writes its channel slice of the concatenated
+        buffer (output pixel stride = total channels) and the readers of the concatenation
+        depend on the branches directly.  The library then sees a DAG without those
+        operators: `self.lib_ops[i]` is the workload id of library operator i and
+        `self.lib_id[v]` the library id of workload operator v (None if elided).  Outputs are
+        still addressed by workload id."""
         self.wl = wl
         self.device = device
         self.dag = None
@@ -79,17 +87,46 @@ class Session:
                 if a.ndim >= 3 and chans % ve and all(o.type == "conv2d" for o in users.get(slot, [])):
                     self.ext_pad[slot] = (chans + ve - 1) // ve * ve
         self.ext_dev = [self._upload(self._to_physical_input(a, self.ext_pad.get(i))) for i, a in enumerate(wl.ext_inputs)]
-        self.out_dev = []
+        self.out_dev = [None] * len(wl.ops)
         self.w_dev, self.b_dev = {}, {}
+        # zero-copy concatenation: shared buffers become extra external slots
+        from workloads import concat_elision_plan
+        plan = concat_elision_plan(wl) if zero_copy_concat else {}
+        self.elided = plan
+        slice_of = {}                       # producer id -> (concat id, first channel, total channels)
+        concat_slot = {}
+        for c, parts in plan.items():
+            cop = wl.ops[c]
+            total = cop.out_shape[0]
+            rows = cop.out_shape[1] * cop.out_shape[2] * wl.batch
+            buf = self._alloc(rows * total)
+            self.out_dev[c] = buf
+            concat_slot[c] = len(self.ext_dev)
+            self.ext_dev.append(buf)
+            for u, off, ch in parts:
+                slice_of[u] = (c, off, total)
+                self.out_dev[u] = buf + off * self._elsize() if isinstance(buf, int) else buf.view(rows, total)[:, off:off + ch]
+        self.lib_ops = [op.id for op in wl.ops if op.id not in plan]
+        self.lib_id = {v: i for i, v in enumerate(self.lib_ops)}
         descs = []
         for op in wl.ops:
+            if op.id in plan:
+                continue
             d = B.OpDesc()
             d.op_type = B.OP_TYPE_IDS[op.type]
             d.op_class = B.CLASS_DEFAULT if class_override is None else class_override[op.id]
             d.dtype = self.dtype_id
             d.n_inputs = len(op.inputs)
+            deps = []
             for i, u in enumerate(op.inputs):
-                d.inputs[i] = u
+                if u in plan:
+                    d.inputs[i] = -(concat_slot[u] + 1)
+                    deps += [self.lib_id[p] for p, _, _ in plan[u] if self.lib_id[p] not in deps]
+                else:
+                    d.inputs[i] = self.lib_id[u] if u >= 0 else u
+            d.n_deps = len(deps)
+            for i, u in enumerate(deps):
+                d.deps[i] = u
             if demand_override is not None:
                 d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs = demand_override[op.id]
             self._fill_params(op, d.params)
@@ -109,8 +146,12 @@ class Session:
                 self.b_dev[op.id] = self._upload(b.astype(np.float32))
                 d.weight = self._ptr(self.w_dev[op.id])
                 d.bias = self._ptr(self.b_dev[op.id])
-            out = self._alloc(int(np.prod(op.out_shape)) * (wl.batch if _is_image(op) else 1))
-            self.out_dev.append(out)
+            if op.id in slice_of:
+                d.params.c_row_stride = slice_of[op.id][2]
+                out = self.out_dev[op.id]
+            else:
+                out = self._alloc(int(np.prod(op.out_shape)) * (wl.batch if _is_image(op) else 1))
+                self.out_dev[op.id] = out
             d.out = self._ptr(out)
             descs.append(d)
         self.descs = descs
@@ -129,6 +170,9 @@ class Session:
         import torch
         return torch.zeros(numel, dtype=torch.float32 if self.wl.dtype == "f32" else torch.float16,
                            device=self.device)
+
+    def _elsize(self):
+        return 4 if self.wl.dtype == "f32" else 2
 
     def _fake_ptr(self, nbytes):
         p = self._fake
@@ -273,14 +317,14 @@ class Session:
         if self._seq_reference is None:
             seq = B.opara_capture(self.dag, self.make_streams(1).handles[:1], B.SEQUENTIAL)
             self.replay(seq)
-            self._seq_reference = [t.clone() for t in self.out_dev]
+            self._seq_reference = [t.contiguous().clone() for t in self.out_dev]
             B.opara_exec_destroy(seq)
         bits = torch.int32 if self.wl.dtype == "f32" else torch.int16
         for t in self.out_dev:
             t.fill_(float("nan"))
         torch.cuda.synchronize()
         self.replay(exe)
-        return all(torch.equal(t.view(bits), r.view(bits)) for t, r in zip(self.out_dev, self._seq_reference))
+        return all(torch.equal(t.contiguous().view(bits), r.view(bits)) for t, r in zip(self.out_dev, self._seq_reference))
 
     def replay(self, exe, sync=True):
         import torch

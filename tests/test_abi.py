@@ -31,6 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     # sizes the C compiler gives the same records (natural alignment, no packing)
     assert C.sizeof(B.OpParams) == 16 * 4 + 6 * 8 + 8 * 4 + 3 * 4 + 4
+    assert C.sizeof(B.OpDesc) == 4 * 4 + 8 * 4 + 4 * 4 + C.sizeof(B.OpParams) + 3 * 8 + 4 + 8 * 4 + 4
     assert C.sizeof(B.Demand) == 32
     assert C.sizeof(B.Limits) == 16
 
@@ -131,6 +132,52 @@ def test_scheduler_matches_oracle_on_configs(builder):
             assert (d.vgprs, d.lds_bytes) == (vg, lds) and d.grid_blocks > 0
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("builder,kw", [(inception_block, {}), (googlenet_like, {}), (inception_v3_like, {}),
+                                        (googlenet_like, dict(batch=2))])
+def test_zero_copy_concat_dag_matches_oracle_scheduler(builder, kw):
+    """Zero-copy concatenation: the library sees the DAG without the elided concatenations,
+    readers depend on the branches through dependency-only predecessors.  Streams, launch
+    queue and synchronisation edges must be the oracle's on that reduced DAG."""
+    from workloads import concat_elision_plan, reduced_dag
+    wl = builder(**kw)
+    plan = concat_elision_plan(wl)
+    assert len(plan) >= 1 and all(wl.ops[c].type == "concat" for c in plan)
+    s = Session(wl, device=None, zero_copy_concat=True)
+    try:
+        kept, preds = reduced_dag(wl, plan)
+        assert s.lib_ops == kept and B.opara_num_ops(s.dag) == len(kept)
+        so, ns, q, syncs = s.schedule()
+        dem = B.opara_get_demands(s.dag)
+        oso, ons = sched.assign_streams(preds)
+        scal = [sched.demand_scalar((d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs), LIMITS) for d in dem]
+        oq = sched.order_launch(preds, [d.op_class for d in dem], scal)
+        assert (so, ns) == (oso, ons) and q == oq and syncs == sched.sync_edges(preds, so)
+        assert sched.check_schedule(preds, so, q, syncs)
+        # every branch that fills a slice is a predecessor of every reader of the concatenation
+        for c, parts in plan.items():
+            readers = [op.id for op in wl.ops if c in op.inputs]
+            for r in readers:
+                assert set(s.lib_id[p] for p, _, _ in parts) <= set(preds[s.lib_id[r]])
+    finally:
+        s.close()
+
+
+def test_dependency_only_predecessors_are_validated():
+    descs = chain_descs(3, [[-1], [0], [-1]])
+    descs[2].n_deps = 2
+    descs[2].deps[0], descs[2].deps[1] = 1, 0
+    dag = B.opara_build_dag(descs, [0x1000])
+    so, ns = B.opara_assign_streams(dag)
+    assert B.opara_topo_order(dag) == [0, 1, 2] and (so, ns) == sched.assign_streams([[], [0], [1, 0]])
+    B.opara_dag_destroy(dag)
+    for bad in (3, -1, 2):                      # out of range, external slot, itself
+        descs[2].deps[0] = bad
+        assert build_status(descs)[0] in (B.EINVAL, B.ECYCLE)
+    descs[2].deps[0] = 1
+    descs[2].n_deps = 9
+    assert build_status(descs)[0] == B.EINVAL
 
 
 def test_scheduler_matches_oracle_on_random_dags():

@@ -12,11 +12,12 @@ from util import compare_all, literal_fp16_bound_ok
 pytestmark = pytest.mark.gpu
 
 
-def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlier_frac=0.0, pad_channels=True):
+def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlier_frac=0.0, pad_channels=True,
+              zero_copy_concat=False):
     """Run the workload in the given modes; every operator output must match the oracle.
     Returns {mode: {sink id: bytes}} so callers can also compare modes bit for bit."""
     ref = executor.run_dag(wl) if ref is None else ref
-    s = Session(wl, pad_channels=pad_channels)
+    s = Session(wl, pad_channels=pad_channels, zero_copy_concat=zero_copy_concat)
     sinks = {}
     try:
         for mode in modes:
@@ -171,6 +172,21 @@ def test_image_batches(builder, kw):
     wl = builder(**kw)
     sinks = run_modes(wl, modes=("seq", "par"))
     assert sinks["seq"] == sinks["par"]
+
+
+@pytest.mark.parametrize("builder,kw", [
+    (inception_block, dict(random_bias=True)), (inception_block, dict(dtype="f16", batch=3, random_bias=True)),
+    (googlenet_like, dict(he_init=True)), (inception_v3_like, dict(he_init=True)), (googlenet_like, dict(batch=2))])
+def test_zero_copy_concat(builder, kw):
+    """Branches write their channel slices of the concatenated tensor in place; the
+    concatenation operators are not executed.  Every operator output, the elided
+    concatenations included, must still match the oracle, in every executor, and be
+    bit-identical to the run with explicit concatenations (same kernels, same arithmetic)."""
+    wl = builder(**kw)
+    ref = executor.run_dag(wl)
+    plain = run_modes(wl, modes=("seq",), ref=ref, outlier_frac=1e-3)
+    fused = run_modes(wl, modes=("eager", "seq", "par", "persist"), ref=ref, outlier_frac=1e-3, zero_copy_concat=True)
+    assert fused["seq"] == fused["par"] == fused["eager"] == plain["seq"]
 
 
 def test_random_wide_dag_full_size():
