@@ -7,6 +7,11 @@ the product path).
   * sync_edges     : the dependencies that need a synchronisation operator
     (Sec. 3.1 "synchronization operators", Sec. 4 event record / wait).
   * check_schedule : validity of (stream map, launch queue, sync list).
+  * min_streams    : the fewest streams any allocation can use - the comparison system's
+    policy the paper sets Alg. 1 against (Sec. 5.2: 28 streams against 4 on GoogLeNet;
+    Sec. 5.4: cubic matching against the linear greedy pass).
+  * prune_syncs    : the synchronisations that remain once those implied by other
+    dependencies are dropped (Sec. 3.1: every synchronisation costs t_overhead, Eq. 3).
 
 Readings where the paper is silent (all repeated in the design notes):
   - topological order = Kahn with the smallest operator id first;
@@ -181,3 +186,89 @@ def check_schedule(preds, stream_of, q, syncs):
     for (u, v) in syncs:
         assert u in preds[v] and stream_of[u] != stream_of[v], f"spurious sync {u}->{v}"
     return True
+
+
+def _reach(preds):
+    """reach[u] = set of operators reachable from u by one or more edges."""
+    n = len(preds)
+    succ = [[] for _ in range(n)]
+    for v, ps in enumerate(preds):
+        for u in ps:
+            succ[u].append(v)
+    topo = kahn_order(n, _edges(preds))
+    reach = [set() for _ in range(n)]
+    for u in reversed(topo):
+        for v in succ[u]:
+            reach[u].add(v)
+            reach[u] |= reach[v]
+    return reach
+
+
+def min_streams(preds):
+    """Fewest streams: a stream may hold any set of operators that are totally ordered by
+    the dependency relation (a chain), so the minimum is a minimum chain cover, found as
+    n minus a maximum matching between operators and their descendants (Dilworth /
+    Fulkerson).  Returns (stream_of, n_streams); streams are numbered by their first
+    operator in topological order.  The matching is not unique, the count is."""
+    n = len(preds)
+    reach = _reach(preds)
+    topo = kahn_order(n, _edges(preds))
+    match_r = [None] * n          # descendant -> the operator it follows on its stream
+
+    def augment(u, seen):
+        for v in sorted(reach[u]):
+            if v in seen:
+                continue
+            seen.add(v)
+            if match_r[v] is None or augment(match_r[v], seen):
+                match_r[v] = u
+                return True
+        return False
+
+    for u in topo:
+        augment(u, set())
+    stream_of = [None] * n
+    n_streams = 0
+    for v in topo:                # a predecessor on the chain comes earlier in topological order
+        if match_r[v] is None:
+            stream_of[v] = n_streams
+            n_streams += 1
+        else:
+            stream_of[v] = stream_of[match_r[v]]
+    return stream_of, n_streams
+
+
+def execution_edges(preds, stream_of, q):
+    """Ordering constraints of a multi-stream run: every dependency, plus consecutive
+    operators of one stream in launch-queue order."""
+    edges = set(_edges(preds))
+    last = {}
+    for v in q:
+        s = stream_of[v]
+        if s in last:
+            edges.add((last[s], v))
+        last[s] = v
+    return edges
+
+
+def prune_syncs(preds, stream_of, q):
+    """Cross-stream dependencies that still need a synchronisation when every one that is
+    implied by a longer chain of constraints (dependencies and stream order) is dropped.
+    Sorted like sync_edges."""
+    edges = execution_edges(preds, stream_of, q)
+    n = len(preds)
+    succ = [[] for _ in range(n)]
+    for u, v in edges:
+        succ[u].append(v)
+    pos = {v: i for i, v in enumerate(q)}
+    reach = [set() for _ in range(n)]
+    for u in sorted(range(n), key=lambda x: -pos[x]):
+        for v in succ[u]:
+            reach[u].add(v)
+            reach[u] |= reach[v]
+    keep = []
+    for (u, v) in sync_edges(preds, stream_of):
+        implied = any(w != v and v in reach[w] for w in succ[u])
+        if not implied:
+            keep.append((u, v))
+    return keep

@@ -184,3 +184,82 @@ def test_demand_scalar():
     assert sched.demand_scalar((3, 64, 81920, 16), lim) == 3 * 32768       # LDS binds: half a CU
     assert sched.demand_scalar((1, 256, 1024, 128), lim) == 16384          # registers bind: a quarter
     assert sched.demand_scalar((2, 100, 1, 1), lim) == 2 * 3200            # rounds up
+
+
+# ---------------------------------------------------------------- fewest streams, sync pruning
+def closure(n, edges):
+    """Reachability by Warshall's algorithm (independent of the oracle's traversal)."""
+    r = np.zeros((n, n), dtype=bool)
+    for u, v in edges:
+        r[u, v] = True
+    for k in range(n):
+        r |= np.outer(r[:, k], r[k, :])
+    return r
+
+
+def test_googlenet_needs_4_streams_at_least():
+    ms, n = sched.min_streams(preds_of(googlenet_like()))
+    assert n == GOLD["googlenet_min_streams"]["value"]
+    assert sched.min_streams(preds_of(inception_block()))[1] == 4      # four branches
+    chain = [[]] + [[i] for i in range(9)]
+    assert sched.min_streams(chain)[1] == 1
+    assert sched.min_streams([[] for _ in range(5)])[1] == 5           # no edges: one stream each
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_min_streams_is_the_width_of_the_dag(seed):
+    """Dilworth: the fewest chains covering a partial order equal its largest antichain
+    (brute force over all subsets), and every stream must be a chain."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 11))
+    preds = random_preds(rng, n, p_root=0.35)
+    so, ns = sched.min_streams(preds)
+    r = closure(n, [(u, v) for v, ps in enumerate(preds) for u in ps])
+    comparable = r | r.T
+    width = 0
+    for mask in range(1, 1 << n):
+        idx = [i for i in range(n) if mask >> i & 1]
+        if len(idx) > width and not any(comparable[a, b] for a in idx for b in idx if a < b):
+            width = len(idx)
+    assert ns == width
+    assert sorted(set(so)) == list(range(ns))
+    for s_ in range(ns):
+        members = [v for v in range(n) if so[v] == s_]
+        assert all(comparable[a, b] for a in members for b in members if a < b)
+    assert ns <= sched.assign_streams(preds)[1]
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_pruned_syncs_keep_every_ordering_and_are_minimal(seed):
+    rng = np.random.default_rng(2000 + seed)
+    n = int(rng.integers(2, 14))
+    preds = random_preds(rng, n, max_fan_in=4)
+    cls = [int(rng.integers(0, 2)) for _ in range(n)]
+    dem = [int(rng.integers(1, 50)) for _ in range(n)]
+    q = sched.order_launch(preds, cls, dem)
+    for so in (sched.assign_streams(preds)[0], sched.min_streams(preds)[0]):
+        full = sched.sync_edges(preds, so)
+        kept = sched.prune_syncs(preds, so, q)
+        assert set(kept) <= set(full) and kept == [e for e in full if e in set(kept)]
+        order_edges = sched.execution_edges(preds, so, q) - set(full)      # stream order + same-stream dependencies
+        want = closure(n, list(order_edges) + full)
+        assert np.array_equal(closure(n, list(order_edges) + kept), want)
+        for e in kept:                                                     # none of the kept ones is implied
+            rest = [x for x in kept if x != e]
+            assert not closure(n, list(order_edges) + rest)[e[0], e[1]]
+
+
+def test_pruning_special_cases():
+    # diamond on two streams with a shortcut edge 0->3: the shortcut is implied by 0->1->3
+    preds = [[], [0], [0], [1, 2, 0]]
+    so = [0, 0, 1, 0]
+    q = [0, 1, 2, 3]
+    assert sched.sync_edges(preds, so) == [(0, 2), (2, 3)]
+    assert sched.prune_syncs(preds, so, q) == [(0, 2), (2, 3)]
+    so = [0, 1, 2, 3]                     # every operator on its own stream
+    assert sched.sync_edges(preds, so) == [(0, 1), (0, 2), (1, 3), (2, 3), (0, 3)]
+    assert sched.prune_syncs(preds, so, q) == [(0, 1), (0, 2), (1, 3), (2, 3)]
+    # stream order implies a dependency: 0 and 1 on stream A in queue order, 2 on B needs both
+    preds = [[], [], [0, 1]]
+    assert sched.prune_syncs(preds, [0, 0, 1], [0, 1, 2]) == [(1, 2)]
+    assert sched.prune_syncs(preds, [0, 0, 1], [1, 0, 2]) == [(0, 2)]
