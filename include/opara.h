@@ -62,7 +62,7 @@ enum opara_op_type {
 /* Operator table of paper Sec. 3.3 (memory- vs compute-intensive operators). */
 enum opara_class { OPARA_CLASS_DEFAULT = -1, OPARA_MEM = 0, OPARA_COMP = 1 };
 enum opara_dtype { OPARA_F32 = 0, OPARA_F16 = 1 };
-enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_CAPTURE = 2 };
+enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_CAPTURE = 2, OPARA_PARALLEL_PRUNED = 3 };
 
 enum opara_flags {
   OPARA_FLAG_RELU     = 1u,  /* CONV2D / GEMM: clamp the result at zero                    */
@@ -167,6 +167,19 @@ int opara_build_dag(const opara_op_desc *ops, int32_t n_ops,
 int opara_assign_streams(opara_dag *g, int32_t *stream_of, int32_t *n_streams);
 
 /*
+ * Stream-allocation policies.  OPARA_STREAMS_ALG1 is opara_assign_streams.
+ * OPARA_STREAMS_MIN is the policy the paper compares it with (Sec. 5.2: 4 streams
+ * against Alg. 1's 28 on GoogLeNet; Sec. 5.4: cubic against linear time): the fewest
+ * streams any allocation can use, i.e. a minimum cover of the DAG by chains (sets of
+ * operators totally ordered by the dependency relation), from a maximum matching between
+ * operators and their descendants.  The number of streams is unique (the width of the
+ * DAG), the allocation is not; streams are numbered by their first operator in
+ * topological order.  Replaces the stream map later calls use.
+ */
+enum opara_stream_policy { OPARA_STREAMS_ALG1 = 0, OPARA_STREAMS_MIN = 1 };
+int opara_assign_streams_policy(opara_dag *g, int32_t policy, int32_t *stream_of, int32_t *n_streams);
+
+/*
  * Launch order, paper Algorithm 2: two ready lists (memory- and compute-intensive),
  * chosen alternately starting with the memory list (the other one when the
  * preferred list is empty); from the chosen list the operator with the least
@@ -198,6 +211,16 @@ int opara_order_launch_policy(opara_dag *g, int32_t policy, int32_t *order);
  */
 int opara_sync_edges(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges);
 
+/*
+ * The same list without the dependencies that other ordering constraints imply (paper
+ * Sec. 3.1: each synchronisation costs t_overhead, Eq. 3): a cross-stream dependency
+ * (u,v) is dropped when v is reachable from u through two or more constraints, a
+ * constraint being any dependency or two consecutive operators of one stream in
+ * launch-queue order.  The result is unique.  Needs streams and a launch queue (ESTATE).
+ * OPARA_PARALLEL_PRUNED builds the graph with these synchronisations only.
+ */
+int opara_sync_edges_pruned(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges);
+
 /* Demand records (paper Sec. 3.2) and default topological order; host arrays [n_ops]. */
 int opara_get_demands(const opara_dag *g, opara_demand *out);
 int opara_topo_order(const opara_dag *g, int32_t *order);
@@ -222,6 +245,8 @@ int32_t opara_num_ops(const opara_dag *g);
  *                           otherwise); with the ROCm 7.0 runtime, capturing DAGs whose
  *                           streams wait on each other in both directions crashed the
  *                           host process, which is why this is not the default.
+ *   OPARA_PARALLEL_PRUNED   as OPARA_PARALLEL, without the cross-stream edges that
+ *                           opara_sync_edges_pruned drops.
  *   OPARA_SEQUENTIAL        captures the same kernels with the same launch shapes on
  *                           hip_streams[0] alone in default topological order (the
  *                           baseline: paper Sec. 5.1, default sequential graph).

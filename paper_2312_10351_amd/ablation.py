@@ -1,6 +1,6 @@
 """Launch-order and interference ablations over the same kernels and graphs.
 
-  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32] [--concat-configs 0,1,2]
+  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32] [--concat-configs 0,1,2] [--stream-configs 0,1,2,3,4]
 
 Part 1 (paper Sec. 2.3, "GPU blocking"): the parallel graph is captured with each
 launch-order policy of opara_order_launch_policy and replayed; only the queue differs.
@@ -9,6 +9,8 @@ replayed alone, back to back on one stream, and side by side on two streams, for
 compute-intensive + memory-intensive pair and for two pairs of one class.
 Part 3 (paper Sec. 5.2): batch sweep of the Inception-v3-like DAG.
 Part 4: zero-copy concatenation against explicit concatenation kernels (CNN configs).
+Part 5: stream-allocation policies (Alg. 1 / fewest streams) with and without pruning of implied
+        synchronisations: streams, synchronisations, host time, latency.
 Prints one JSON object per line.
 """
 import argparse
@@ -92,6 +94,38 @@ def concat_ablation(index, replays):
     return out
 
 
+def stream_policy_ablation(index, replays):
+    """Alg. 1 against the fewest-streams allocation (the matching-based policy the paper
+    compares with, Sec. 5.2 / 5.4), each with all synchronisations and with the implied ones
+    pruned: streams, synchronisations, graph edges, allocation time on the host, latency."""
+    import time
+    from . import binding as B
+    from .runtime import Session
+    from workloads import build_config
+    wl = build_config(index)
+    s = Session(wl)
+    try:
+        row = {"ablation": "stream_policy", "workload": wl.name, "n_ops": len(wl.ops),
+               "sequential_us": replay_latency(s, s.capture(B.SEQUENTIAL), replays)}
+        for name, pol in (("alg1", B.STREAMS_ALG1), ("min_streams", B.STREAMS_MIN)):
+            best = 1e9
+            for _ in range(5):
+                t0 = time.perf_counter()
+                _, ns = B.opara_assign_streams_policy(s.dag, pol)
+                best = min(best, time.perf_counter() - t0)
+            B.opara_order_launch(s.dag)
+            r = {"n_streams": ns, "assign_ms": best * 1e3, "syncs": len(B.opara_sync_edges(s.dag)),
+                 "syncs_pruned": len(B.opara_sync_edges_pruned(s.dag))}
+            for tag, mode in (("graph", B.PARALLEL), ("graph_pruned", B.PARALLEL_PRUNED)):
+                exe = s.capture(mode, stream_policy=pol)
+                r[tag + "_edges"] = B.opara_exec_info(exe)[1]
+                r[tag + "_us"] = replay_latency(s, exe, replays)
+            row[name] = r
+        return row
+    finally:
+        s.close()
+
+
 def _pair(kind_a, kind_b):
     """Two independent operators of the given classes reading the same external tensor."""
     from workloads import Builder
@@ -139,7 +173,10 @@ def main():
     ap.add_argument("--replays", type=int, default=300)
     ap.add_argument("--batches", default="1,2,4,8,16,32")
     ap.add_argument("--concat-configs", default="0,1,2")
+    ap.add_argument("--stream-configs", default="0,1,2,3,4")
     a = ap.parse_args()
+    for idx in [int(x) for x in a.stream_configs.split(",") if x]:
+        print(json.dumps(stream_policy_ablation(idx, a.replays)), flush=True)
     for idx in [int(x) for x in a.concat_configs.split(",") if x]:
         print(json.dumps(concat_ablation(idx, a.replays)), flush=True)
     for bsz in [int(x) for x in a.batches.split(",") if x]:

@@ -14,7 +14,8 @@ OP_TYPE_IDS = dict(conv2d=CONV2D, gemm=GEMM, bgemm=BGEMM, maxpool=MAXPOOL, avgpo
                    gelu=GELU, relu=RELU, add=ADD)
 CLASS_DEFAULT, MEM, COMP = -1, 0, 1
 F32, F16 = 0, 1
-PARALLEL, SEQUENTIAL, PARALLEL_CAPTURE = 0, 1, 2
+PARALLEL, SEQUENTIAL, PARALLEL_CAPTURE, PARALLEL_PRUNED = 0, 1, 2, 3
+STREAMS_ALG1, STREAMS_MIN = 0, 1
 FLAG_RELU, FLAG_B_KMAJOR = 1, 2
 (ORDER_ALG2, ORDER_ALG2_COMP_FIRST, ORDER_LEAST_DEMAND, ORDER_MOST_DEMAND, ORDER_TOPO,
  ORDER_LEVEL) = range(6)
@@ -61,7 +62,8 @@ class Demand(C.Structure):
                 ("op_class", C.c_int32), ("kernel_id", C.c_int32), ("demand", C.c_uint64)]
 
 
-EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_order_launch", "opara_order_launch_policy", "opara_sync_edges",
+EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_assign_streams_policy", "opara_order_launch",
+           "opara_order_launch_policy", "opara_sync_edges", "opara_sync_edges_pruned",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_set_trace",
@@ -85,6 +87,8 @@ def load():
     lib.opara_build_dag.argtypes = [C.POINTER(OpDesc), C.c_int32, C.POINTER(C.c_void_p), C.c_int32,
                                     C.POINTER(Limits), C.POINTER(vp)]
     lib.opara_assign_streams.argtypes = [vp, i32p, i32p]
+    lib.opara_assign_streams_policy.argtypes = [vp, C.c_int32, i32p, i32p]
+    lib.opara_sync_edges_pruned.argtypes = [vp, i32p, C.c_int32, i32p]
     lib.opara_order_launch.argtypes = [vp, i32p]
     lib.opara_order_launch_policy.argtypes = [vp, C.c_int32, i32p]
     lib.opara_sync_edges.argtypes = [vp, i32p, C.c_int32, i32p]
@@ -147,6 +151,14 @@ def opara_assign_streams(dag):
     return list(so), ns.value
 
 
+def opara_assign_streams_policy(dag, policy):
+    n = opara_num_ops(dag)
+    so = (C.c_int32 * n)()
+    ns = C.c_int32()
+    _check(load().opara_assign_streams_policy(dag, policy, so, C.byref(ns)))
+    return list(so), ns.value
+
+
 def opara_order_launch(dag):
     n = opara_num_ops(dag)
     q = (C.c_int32 * n)()
@@ -166,6 +178,14 @@ def opara_sync_edges(dag):
     _check(load().opara_sync_edges(dag, None, 0, C.byref(ne)))
     uv = (C.c_int32 * max(2 * ne.value, 1))()
     _check(load().opara_sync_edges(dag, uv, ne.value, C.byref(ne)))
+    return [(uv[2 * i], uv[2 * i + 1]) for i in range(ne.value)]
+
+
+def opara_sync_edges_pruned(dag):
+    ne = C.c_int32()
+    _check(load().opara_sync_edges_pruned(dag, None, 0, C.byref(ne)))
+    uv = (C.c_int32 * max(2 * ne.value, 1))()
+    _check(load().opara_sync_edges_pruned(dag, uv, ne.value, C.byref(ne)))
     return [(uv[2 * i], uv[2 * i + 1]) for i in range(ne.value)]
 
 

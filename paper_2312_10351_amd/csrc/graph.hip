@@ -44,7 +44,7 @@ void destroy_exec(opara_exec *e) {
 
 extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams, int32_t mode,
                              opara_exec **out) {
-  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_CAPTURE)) {
+  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_CAPTURE && mode != OPARA_PARALLEL_PRUNED)) {
     set_error("opara_capture: bad argument");
     return OPARA_EINVAL;
   }
@@ -87,9 +87,19 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
   // Default: the graph is assembled node by node.  Each node depends on the previous
   // operator of its stream in launch-queue order and on every cross-stream predecessor;
   // one leaf node without work closes a DAG with several sinks.
-  if (mode == OPARA_PARALLEL) {
+  if (mode == OPARA_PARALLEL || mode == OPARA_PARALLEL_PRUNED) {
     std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(ns, nullptr), deps;
     hipGraphNode_t leaf = nullptr;
+    // pruned: keep_edge[pred slot j] says whether the cross-stream dependency still needs an edge
+    std::vector<uint8_t> keep_edge(g->pred.size(), 1);
+    if (mode == OPARA_PARALLEL_PRUNED) {
+      std::vector<uint8_t> keep;
+      sync_keep_mask(g, &keep);
+      size_t k = 0;
+      for (int32_t v = 0; v < n; ++v)
+        for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j)
+          if (g->stream_of[g->pred[j]] != g->stream_of[v]) keep_edge[j] = keep[k++];
+    }
     HIP_TRY(hipGraphCreate(&e->graph, 0));
     for (int32_t i = 0; i < n; ++i) {
       const int32_t v = q[i], sv = g->stream_of[v];
@@ -97,7 +107,7 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
       if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
       for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
         const int32_t u = g->pred[j];
-        if (g->stream_of[u] != sv) deps.push_back(node_of[u]);
+        if (g->stream_of[u] != sv && keep_edge[j]) deps.push_back(node_of[u]);
       }
       HIP_TRY(add_plan_node(e->graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
       last_on_stream[sv] = node_of[v];

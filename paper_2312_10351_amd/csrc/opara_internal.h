@@ -28,6 +28,10 @@ extern const KernelResource kKernelResources[K_COUNT];
 
 void set_error(const char *fmt, ...);
 
+// One flag per entry of the opara_sync_edges list (same order): 0 = the dependency is
+// implied by other ordering constraints and needs no synchronisation of its own.
+int sync_keep_mask(const opara_dag *g, std::vector<uint8_t> *keep);
+
 // Chooses the kernel, grid and arguments for operator `v`; `in[i]` are the resolved
 // device pointers of its inputs.  Returns an opara_status.
 int plan_op(const opara_op_desc &op, const void *const *in, KernelPlan *out);

@@ -192,6 +192,135 @@ extern "C" int opara_assign_streams(opara_dag *g, int32_t *stream_of, int32_t *n
   return OPARA_OK;
 }
 
+namespace {
+
+// Bit matrix: row u holds the operators reachable from u.
+struct Reach {
+  int32_t n = 0, words = 0;
+  std::vector<uint64_t> bits;
+  void init(int32_t n_) { n = n_; words = (n_ + 63) / 64; bits.assign((size_t)n * words, 0); }
+  uint64_t *row(int32_t u) { return bits.data() + (size_t)u * words; }
+  const uint64_t *row(int32_t u) const { return bits.data() + (size_t)u * words; }
+  bool get(int32_t u, int32_t v) const { return row(u)[v >> 6] >> (v & 63) & 1; }
+  void set(int32_t u, int32_t v) { row(u)[v >> 6] |= 1ull << (v & 63); }
+  void merge(int32_t u, int32_t v) { uint64_t *a = row(u); const uint64_t *b = row(v); for (int32_t w = 0; w < words; ++w) a[w] |= b[w]; }
+};
+
+// Kuhn's augmenting path over "v is a descendant of u"; match_r[v] = the operator v follows.
+bool augment(const Reach &r, int32_t u, std::vector<int32_t> &match_r, std::vector<uint8_t> &seen) {
+  for (int32_t v = 0; v < r.n; ++v) {
+    if (!r.get(u, v) || seen[v]) continue;
+    seen[v] = 1;
+    if (match_r[v] < 0 || augment(r, match_r[v], match_r, seen)) { match_r[v] = u; return true; }
+  }
+  return false;
+}
+
+}  // namespace
+
+// Fewest streams: a stream can hold any set of operators totally ordered by the dependency
+// relation, so the minimum is a minimum chain cover = n - maximum matching between
+// operators and their descendants (the matching-based allocation the paper compares
+// Alg. 1 with, Sec. 5.2 and 5.4: cubic in n).
+static int assign_min_streams(opara_dag *g) {
+  const int32_t n = g->n;
+  Reach r;
+  r.init(n);
+  for (int32_t i = n - 1; i >= 0; --i) {
+    const int32_t u = g->topo[i];
+    for (int32_t j = g->succ_off[u]; j < g->succ_off[u + 1]; ++j) { r.set(u, g->succ[j]); r.merge(u, g->succ[j]); }
+  }
+  std::vector<int32_t> match_r(n, -1);
+  std::vector<uint8_t> seen(n);
+  for (int32_t i = 0; i < n; ++i) {
+    std::fill(seen.begin(), seen.end(), 0);
+    augment(r, g->topo[i], match_r, seen);
+  }
+  g->stream_of.assign(n, -1);
+  int32_t ns = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t v = g->topo[i];
+    g->stream_of[v] = match_r[v] < 0 ? ns++ : g->stream_of[match_r[v]];
+  }
+  g->n_streams = ns;
+  return OPARA_OK;
+}
+
+extern "C" int opara_assign_streams_policy(opara_dag *g, int32_t policy, int32_t *stream_of, int32_t *n_streams) {
+  if (policy == OPARA_STREAMS_ALG1) return opara_assign_streams(g, stream_of, n_streams);
+  if (!g || !stream_of || !n_streams) { set_error("opara_assign_streams_policy: null pointer"); return OPARA_EINVAL; }
+  if (policy != OPARA_STREAMS_MIN) { set_error("opara_assign_streams_policy: unknown policy %d", policy); return OPARA_EINVAL; }
+  try {
+    assign_min_streams(g);
+  } catch (const std::bad_alloc &) {
+    set_error("out of memory");
+    return OPARA_ENOMEM;
+  }
+  std::memcpy(stream_of, g->stream_of.data(), sizeof(int32_t) * g->n);
+  *n_streams = g->n_streams;
+  return OPARA_OK;
+}
+
+// keep[k] for the k-th entry of the opara_sync_edges list: false if the dependency is implied
+// by a longer chain of ordering constraints (dependencies + stream order in the queue).
+int opara::sync_keep_mask(const opara_dag *g, std::vector<uint8_t> *keep) {
+  const int32_t n = g->n;
+  std::vector<std::vector<int32_t>> succ(n);
+  for (int32_t v = 0; v < n; ++v)
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) succ[g->pred[j]].push_back(v);
+  {
+    std::vector<int32_t> last(g->n_streams, -1);
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = g->order[i], sv = g->stream_of[v];
+      if (last[sv] >= 0) succ[last[sv]].push_back(v);
+      last[sv] = v;
+    }
+  }
+  Reach r;
+  r.init(n);
+  for (int32_t i = n - 1; i >= 0; --i) {
+    const int32_t u = g->order[i];
+    for (int32_t v : succ[u]) { r.set(u, v); r.merge(u, v); }
+  }
+  keep->clear();
+  for (int32_t v = 0; v < n; ++v)
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+      const int32_t u = g->pred[j];
+      if (g->stream_of[u] == g->stream_of[v]) continue;
+      bool implied = false;
+      for (int32_t w : succ[u]) implied = implied || (w != v && r.get(w, v));
+      keep->push_back(!implied);
+    }
+  return OPARA_OK;
+}
+
+extern "C" int opara_sync_edges_pruned(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges) {
+  if (!g || !n_edges || cap < 0 || (cap > 0 && !uv)) { set_error("opara_sync_edges_pruned: bad argument"); return OPARA_EINVAL; }
+  if (g->stream_of.empty() || g->order.empty()) {
+    set_error("opara_sync_edges_pruned: call opara_assign_streams and opara_order_launch first");
+    return OPARA_ESTATE;
+  }
+  std::vector<uint8_t> keep;
+  try {
+    sync_keep_mask(g, &keep);
+  } catch (const std::bad_alloc &) {
+    set_error("out of memory");
+    return OPARA_ENOMEM;
+  }
+  int32_t k = 0, e = 0;
+  for (int32_t v = 0; v < g->n; ++v)
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+      const int32_t u = g->pred[j];
+      if (g->stream_of[u] == g->stream_of[v]) continue;
+      if (keep[e++]) {
+        if (k < cap) { uv[2 * k] = u; uv[2 * k + 1] = v; }
+        ++k;
+      }
+    }
+  *n_edges = k;
+  return OPARA_OK;
+}
+
 extern "C" int opara_order_launch_policy(opara_dag *g, int32_t policy, int32_t *order) {
   if (!g || !order) { set_error("opara_order_launch: null pointer"); return OPARA_EINVAL; }
   if (policy < 0 || policy >= OPARA_N_ORDER_POLICIES) {

@@ -235,8 +235,8 @@ class Session:
             p.eps = q.get("eps", 0.0)
 
     # ---- the path
-    def schedule(self, policy=B.ORDER_ALG2):
-        so, ns = B.opara_assign_streams(self.dag)
+    def schedule(self, policy=B.ORDER_ALG2, stream_policy=B.STREAMS_ALG1):
+        so, ns = B.opara_assign_streams_policy(self.dag, stream_policy)
         order = B.opara_order_launch_policy(self.dag, policy)
         return so, ns, order, B.opara_sync_edges(self.dag)
 
@@ -247,7 +247,7 @@ class Session:
             self.streams = StreamSet(n, self.device)
         return self.streams
 
-    def capture(self, mode, policy=B.ORDER_ALG2, validate=True, max_attempts=6):
+    def capture(self, mode, policy=B.ORDER_ALG2, validate=True, max_attempts=6, stream_policy=B.STREAMS_ALG1):
         """Capture a graph.  Parallel graphs are validated before they are handed out: the
         graph runtime has been seen to drop single dependencies of irregular DAGs
         (depending on node order and allocation addresses), so the captured graph is
@@ -262,7 +262,7 @@ class Session:
         attempts = [policy, policy, policy] + [p for p in (B.ORDER_TOPO, B.ORDER_LEVEL, B.ORDER_LEAST_DEMAND)
                                                if p != policy]
         for i, pol in enumerate(attempts[:max_attempts]):
-            _, ns, _, _ = self.schedule(pol)
+            _, ns, _, _ = self.schedule(pol, stream_policy)
             st = self.make_streams(max(ns, 1))
             exe = B.opara_capture(self.dag, st.handles[:ns], mode)
             if not validate or self.device is None or self._matches_sequential(exe):

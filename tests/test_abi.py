@@ -180,6 +180,64 @@ def test_dependency_only_predecessors_are_validated():
     assert build_status(descs)[0] == B.EINVAL
 
 
+def _closure(n, edges):
+    r = np.zeros((n, n), dtype=bool)
+    for u, v in edges:
+        r[u, v] = True
+    for k in range(n):
+        r |= np.outer(r[:, k], r[k, :])
+    return r
+
+
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like])
+def test_min_streams_and_pruned_syncs_match_oracle_on_configs(builder):
+    wl = builder()
+    s = Session(wl, device=None)
+    try:
+        preds = sched.dedup_preds([o.inputs for o in wl.ops])
+        n = len(preds)
+        q = B.opara_order_launch(s.dag)
+        for policy, oracle_fn in ((B.STREAMS_ALG1, sched.assign_streams), (B.STREAMS_MIN, sched.min_streams)):
+            so, ns = B.opara_assign_streams_policy(s.dag, policy)
+            oso, ons = oracle_fn(preds)
+            assert ns == ons                                   # the count is unique
+            if policy == B.STREAMS_ALG1:
+                assert so == oso
+            else:                                              # the matching is not: check it is a chain cover
+                reach = _closure(n, [(u, v) for v, ps in enumerate(preds) for u in ps])
+                assert sorted(set(so)) == list(range(ns))
+                for st in range(ns):
+                    m = [v for v in range(n) if so[v] == st]
+                    assert all(reach[a, b] or reach[b, a] for a in m for b in m if a < b)
+            assert B.opara_sync_edges(s.dag) == sched.sync_edges(preds, so)
+            assert B.opara_sync_edges_pruned(s.dag) == sched.prune_syncs(preds, so, q)
+    finally:
+        s.close()
+
+
+def test_min_streams_and_pruned_syncs_match_oracle_on_random_dags():
+    rng = np.random.default_rng(77)
+    for trial in range(300):
+        n = int(rng.integers(1, 60))
+        inputs = [[-1]]
+        for v in range(1, n):
+            k = int(rng.integers(0, 4))
+            ins = [int(u) for u in rng.choice(v, size=min(k, v), replace=False)] or [-1]
+            inputs.append(ins)
+        dag = B.opara_build_dag(chain_descs(n, inputs), [0x1000])
+        try:
+            preds = sched.dedup_preds(inputs)
+            pol = int(rng.integers(0, len(B.ORDER_POLICY_NAMES)))
+            q = B.opara_order_launch_policy(dag, pol)
+            for policy, oracle_fn in ((B.STREAMS_ALG1, sched.assign_streams), (B.STREAMS_MIN, sched.min_streams)):
+                so, ns = B.opara_assign_streams_policy(dag, policy)
+                assert ns == oracle_fn(preds)[1]
+                assert B.opara_sync_edges_pruned(dag) == sched.prune_syncs(preds, so, q)
+                assert sched.check_schedule(preds, so, q, B.opara_sync_edges(dag))
+        finally:
+            B.opara_dag_destroy(dag)
+
+
 def test_scheduler_matches_oracle_on_random_dags():
     """>= 10^4 seeded random DAGs with n <= 12 and caller-supplied demand records."""
     rng = np.random.default_rng(20231210)

@@ -189,6 +189,31 @@ def test_zero_copy_concat(builder, kw):
     assert fused["seq"] == fused["par"] == fused["eager"] == plain["seq"]
 
 
+@pytest.mark.parametrize("make", [lambda: googlenet_like(he_init=True), lambda: bert_base_like(),
+                                  lambda: random_small_dag(2, "f16", n_ops=60, max_width=8),
+                                  lambda: random_small_dag(4, "f32", n_ops=60, max_width=8)])
+def test_stream_policies_and_pruned_synchronisations(make):
+    """Fewest-streams allocation and the graph without implied cross-stream edges compute the
+    same bits as the sequential graph (validated captures over NaN-poisoned outputs)."""
+    wl = make()
+    ref = executor.run_dag(wl)
+    s = Session(wl)
+    try:
+        s.replay(s.capture(B.SEQUENTIAL))
+        assert not compare_all(s, ref, outlier_frac=1e-3)
+        want = {v: s.output(v).tobytes() for v in wl.sinks()}
+        for stream_policy in (B.STREAMS_ALG1, B.STREAMS_MIN):
+            for mode in (B.PARALLEL, B.PARALLEL_PRUNED):
+                exe = s.capture(mode, stream_policy=stream_policy)
+                s.clear_outputs()
+                s.replay(exe)
+                assert {v: s.output(v).tobytes() for v in wl.sinks()} == want
+                nodes, edges = B.opara_exec_info(exe)
+                assert nodes >= len(wl.ops)
+    finally:
+        s.close()
+
+
 def test_random_wide_dag_full_size():
     wl = random_wide_dag()
     ref = executor.run_dag(wl)
