@@ -298,7 +298,10 @@ int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violati
  * of the waiting operator), which opara_persistent_status reads after synchronising
  * `hip_stream`.  opara_persistent_reset synchronises the stream, clears counters, flags
  * and error word and sets the spin limit (0 = default).  Replays of one executor must not
- * overlap (same stream, or ordered by the caller).
+ * overlap (same stream, or ordered by the caller).  Several persistent executors, or one
+ * beside other kernels, may run at the same time: they share the device's workgroup slots,
+ * and a launch whose workgroups are not all resident yet makes progress as the others
+ * finish (its waits are long, not unbounded).
  * Errors: ESTATE without a launch queue, EINVAL (workspace), EUNSUPPORTED (more than 8
  * predecessors or 65535 tiles per operator, more than about 2,600 operators, mixed
  * element types), EHIP.
