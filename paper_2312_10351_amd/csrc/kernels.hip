@@ -6,6 +6,7 @@
 // with wavefront (64-lane) reductions where rows are reduced.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 #include "kernel_args.h"
 #include "launch.h"
 
@@ -627,16 +628,20 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
       }
     }
 
-  for (int ds = ds_begin; ds < ds_end; ds += U) {
-    V wa[U][2][2], xb[U][2][2];
-    bool kok[U][2], inb[U][2][2];
+  // One round = UU K steps requested together, then multiplied.  Full rounds of U steps,
+  // then a shorter last round: steps past the end of a wavefront's K range would only
+  // move bytes that are never used, and at these sizes the bytes set the time.
+  auto round = [&](auto uu_tag, int ds) {
+    constexpr int UU = decltype(uu_tag)::value;
+    V wa[UU][2][2], xb[UU][2][2];
+    bool kok[UU][2], inb[UU][2][2];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < UU; ++u) {
       KPos pc = pos;                       // position of chunk 0 of this step
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int k = (ds + u) * DS + grp * 2 * VE + c * VE;
-        kok[u][c] = ds + u < ds_end && k < a.K;
+        kok[u][c] = k < a.K;
         const int ks = kok[u][c] ? k : 0;
 #pragma unroll
         for (int i = 0; i < 2; ++i) wa[u][i][c] = ldg<CW, V>(wrow[i] + ks);
@@ -657,7 +662,7 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
       if (a.gather) kpos_advance(pos, DS, a.Cin, a.kw);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < UU; ++u)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
 #pragma unroll
@@ -671,6 +676,16 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j] = mma16<T>(wa[u][i][c], xb[u][j][c], acc[i][j]);
       }
+  };
+  {
+    int ds = ds_begin;
+    for (; ds + U <= ds_end; ds += U) round(std::integral_constant<int, U>{}, ds);
+    if constexpr (U > 2) {
+      if (ds + 2 <= ds_end) { round(std::integral_constant<int, 2>{}, ds); ds += 2; }
+    }
+    if constexpr (U > 1) {
+      if (ds < ds_end) round(std::integral_constant<int, 1>{}, ds);
+    }
   }
 
   // ---- meet in LDS: lane holds channels n = i*16 + grp*4 + e of pixel m = j*16 + r16

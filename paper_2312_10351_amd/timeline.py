@@ -7,7 +7,7 @@ tile was published, and the median tile time; then the overlap summary (operator
 busy fraction of the workgroups).  It is the counterpart of a kernel-trace timeline for the
 multi-stream graph (paper Sec. 5.3 looks at the same thing through SM utilisation).
 
-  python -m paper_2312_10351_amd.timeline [--config 1] [--policy alg2] [--rows 200]
+  python -m paper_2312_10351_amd.timeline [--config 1] [--policy alg2] [--rows 200] [--zero-copy-concat]
 """
 import argparse
 import json
@@ -22,7 +22,7 @@ def operator_timeline(session, exe, order):
     rows = []
     for pos, v in enumerate(order):
         m = tr[:, 3] == pos
-        op = session.wl.ops[v]
+        op = session.wl.ops[session.lib_ops[v]]
         rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(dem[v].kernel_id)[0],
                          tiles=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
                          last_published_us=float(tr[m, 2].max()) / 1e3,
@@ -40,9 +40,10 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--policy", default="alg2", choices=list(B.ORDER_POLICY_NAMES))
     ap.add_argument("--rows", type=int, default=200)
+    ap.add_argument("--zero-copy-concat", action="store_true")
     a = ap.parse_args()
     pol = list(B.ORDER_POLICY_NAMES).index(a.policy)
-    s = Session(build_config(a.config))
+    s = Session(build_config(a.config), zero_copy_concat=a.zero_copy_concat)
     try:
         exe = s.capture_persistent(policy=pol)
         for _ in range(5):
