@@ -265,7 +265,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--configs", type=str, default="0,2,3,4", help="extra configs reported beside the headline one")
+    ap.add_argument("--configs", type=str, default="0,2,3,4,5",
+                    help="extra configs reported beside the headline one (5 = NASNet-cell-like DAG, not in BASELINE.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch a 64 MiB streaming kernel 10 times (scale for rocprofv3 --pmc traffic counters)")

@@ -46,8 +46,14 @@ def _view(buf, shape):
 _IMAGE_OPS = ("conv2d", "maxpool", "avgpool", "gavgpool")
 
 
+_ELEMENTWISE_OPS = ("add", "relu", "gelu")
+
+
 def is_image_op(op):
-    return op.type in _IMAGE_OPS or (op.type == "concat" and op.params.get("axis") == 0)
+    """Operators whose tensors are [C, H, W] images (one per batch entry): the image
+    operators proper, channel concatenation, and element-wise operators stated on 3-D shapes."""
+    return op.type in _IMAGE_OPS or (op.type == "concat" and op.params.get("axis") == 0) \
+        or (op.type in _ELEMENTWISE_OPS and len(op.out_shape) == 3)
 
 
 def run_op(op, ins, wts):

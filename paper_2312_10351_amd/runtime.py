@@ -14,7 +14,8 @@ _IMAGE_TYPES = ("conv2d", "maxpool", "avgpool", "gavgpool")
 
 
 def _is_image(op):
-    return op.type in _IMAGE_TYPES or (op.type == "concat" and op.params.get("axis") == 0)
+    return op.type in _IMAGE_TYPES or (op.type == "concat" and op.params.get("axis") == 0) \
+        or (op.type in ("add", "relu", "gelu") and len(op.out_shape) == 3)
 
 
 def _hip():
@@ -230,6 +231,9 @@ class Session:
             for i, c in enumerate(cols):
                 p.in_cols[i] = c
             p.n = sum(cols)
+        elif len(op.out_shape) == 3:   # gelu, relu, add on images: element-wise over [B][H][W][C]
+            c, h, w = op.out_shape
+            p.m, p.n = h * w * self.wl.batch, c
         else:                          # layernorm, softmax, gelu, relu, add
             p.m, p.n = op.in_shapes[0]
             p.eps = q.get("eps", 0.0)

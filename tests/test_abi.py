@@ -10,7 +10,7 @@ from oracle import sched
 from paper_2312_10351_amd import binding as B
 from paper_2312_10351_amd.runtime import Session
 from workloads import (Builder, inception_block, googlenet_like, inception_v3_like, bert_base_like,
-                       random_small_dag)
+                       random_small_dag, nasnet_like)
 from util import LIMITS
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -110,7 +110,7 @@ def oracle_schedule(wl, dem):
     return preds, so, ns, q, sched.sync_edges(preds, so), scal
 
 
-@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like])
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like, nasnet_like])
 def test_scheduler_matches_oracle_on_configs(builder):
     wl = builder()
     s = Session(wl, device=None)
@@ -189,7 +189,7 @@ def _closure(n, edges):
     return r
 
 
-@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like])
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like, nasnet_like])
 def test_min_streams_and_pruned_syncs_match_oracle_on_configs(builder):
     wl = builder()
     s = Session(wl, device=None)

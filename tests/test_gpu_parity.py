@@ -6,7 +6,7 @@ from oracle import executor, sched
 from paper_2312_10351_amd import binding as B
 from paper_2312_10351_amd.runtime import Session
 from workloads import (Builder, inception_block, googlenet_like, inception_v3_like, bert_base_like,
-                       random_wide_dag, random_small_dag)
+                       random_wide_dag, random_small_dag, nasnet_like)
 from util import compare_all, literal_fp16_bound_ok
 
 pytestmark = pytest.mark.gpu
@@ -212,6 +212,16 @@ def test_stream_policies_and_pruned_synchronisations(make):
                 assert nodes >= len(wl.ops)
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("kw", [dict(he_init=True), dict(dtype="f32", cells=3, width=16, hw=17, he_init=True),
+                                dict(he_init=True, batch=3, cells=2)])
+def test_nasnet_cell_like_dag(kw):
+    """A second irregular workload (skip connections across cells, element-wise sums of
+    image tensors), in every executor."""
+    wl = nasnet_like(**kw)
+    sinks = run_modes(wl, modes=("eager", "seq", "par", "persist"), outlier_frac=1e-3)
+    assert sinks["seq"] == sinks["par"] == sinks["eager"]
 
 
 def test_random_wide_dag_full_size():

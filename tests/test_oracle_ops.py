@@ -243,3 +243,27 @@ def test_executor_batch_is_per_image():
     g = googlenet_like(batch=2, he_init=True)
     og = executor.run_dag(g, keep=g.sinks())
     assert og[80].shape == (2, 1000) and not np.array_equal(og[80][0], og[80][1])
+
+
+def test_elementwise_on_images_and_nasnet_like_wiring():
+    """Element-wise operators stated on [C, H, W] shapes act per image; the NASNet-cell-like
+    DAG feeds every cell from the two cells before it (skip connections across cells)."""
+    from workloads import nasnet_like, Builder
+    b = Builder("img_add", "f32", batch=2)
+    x, y = b.ext((3, 4, 5)), b.ext((3, 4, 5))
+    b.add_images([x, y])
+    wl = b.build(9)
+    out = executor.run_dag(wl)[0]
+    assert out.shape == (2, 3, 4, 5)
+    assert np.array_equal(out, (wl.ext_inputs[0].astype(np.float64) + wl.ext_inputs[1].astype(np.float64)).astype(np.float32))
+    wl = nasnet_like(cells=3, width=8, hw=9, dtype="f32", he_init=True)
+    cats = [op for op in wl.ops if op.type == "concat"]
+    assert len(cats) == 3 and all(len(c.inputs) == 5 and c.out_shape == (40, 9, 9) for c in cats)
+    # cell 2 reads cell 0's and cell 1's outputs
+    readers_of = lambda v: [op.name for op in wl.ops if v in op.inputs]
+    assert any(n.startswith("c2.sq_prev") for n in readers_of(cats[0].id))
+    assert any(n.startswith("c2.sq_cur") for n in readers_of(cats[1].id))
+    o1 = executor.run_dag(wl)
+    o2 = executor.run_dag(nasnet_like(cells=3, width=8, hw=9, dtype="f32", he_init=True, batch=2))
+    sink = wl.sinks()[0]
+    assert o2[sink].shape == (2, 100) and np.isfinite(o2[sink]).all() and np.abs(o1[sink]).max() > 1e-3

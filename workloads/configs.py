@@ -13,7 +13,7 @@ from .dag import Op, Workload
 
 BASE_SEED = 231210351
 CONFIG_NAMES = ("inception_block", "googlenet_like", "inception_v3_like",
-                "bert_base_like", "random_wide_dag")
+                "bert_base_like", "random_wide_dag", "nasnet_like")
 
 
 class Builder:
@@ -69,6 +69,12 @@ class Builder:
     def gemm(self, x, m, k, n, extras=(), relu=False, name=""):
         p = dict(m=m, k=k, n=n, relu=bool(relu))
         return self.add("gemm", [x] + list(extras), [(m, k)] + [(m, n)] * len(extras), (m, n), p, name)
+
+    def add_images(self, xs, name=""):
+        """Element-wise sum of image tensors of one shape ([C, H, W] each)."""
+        shp = self.shape(xs[0])
+        assert len(shp) == 3 and all(self.shape(x) == shp for x in xs)
+        return self.add("add", list(xs), [shp] * len(xs), shp, {}, name)
 
     def rowwise(self, kind, xs, r, c, params=None, name=""):
         return self.add(kind, xs, [(r, c)] * len(xs), (r, c), params or {}, name)
@@ -246,6 +252,39 @@ def bert_base_like(seed=BASE_SEED + 3, dtype="f16", layers=12, seq=128, hidden=7
 _MEM_KINDS = ("add", "gelu", "layernorm", "softmax", "concat")
 
 
+def nasnet_like(seed=BASE_SEED + 5, dtype="f16", cells=6, width=32, hw=28, he_init=False, batch=1):
+    """An irregular cell-structured CNN in the manner of NASNet-A's normal cell (the paper
+    evaluates NASNet, Sec. 5.1): every cell takes the outputs of the two previous cells,
+    squeezes each with a 1x1 convolution, forms five blocks add(op(a), op(b)) with operators
+    drawn from {3x3 conv, 5x5 conv, 3x3 average pool, 3x3 max pool, identity}, and
+    concatenates the five sums.  Ordinary convolutions stand in for NASNet's separable ones
+    (this operator set has no depthwise convolution); the wiring is what matters here."""
+    b = Builder("nasnet_like", dtype, batch)
+    x = b.ext((3, hw, hw))
+    stem = b.conv(x, 5 * width, 3, pad=1, name="stem")
+    prev, cur = stem, stem
+    for c in range(cells):
+        t = f"c{c}"
+        hp = b.conv(prev, width, 1, name=t + ".sq_prev")
+        hc = b.conv(cur, width, 1, name=t + ".sq_cur")
+        conv3 = lambda v, n: b.conv(v, width, 3, pad=1, relu=False, name=n)
+        conv5 = lambda v, n: b.conv(v, width, 5, pad=2, relu=False, name=n)
+        avg = lambda v, n: b.pool("avgpool", v, 3, 1, 1, name=n)
+        mx = lambda v, n: b.pool("maxpool", v, 3, 1, 1, name=n)
+        blocks = [
+            b.add_images([conv3(hc, t + ".b0.c3"), hc], name=t + ".b0"),
+            b.add_images([conv3(hp, t + ".b1.c3"), conv5(hc, t + ".b1.c5")], name=t + ".b1"),
+            b.add_images([avg(hc, t + ".b2.avg"), hp], name=t + ".b2"),
+            b.add_images([avg(hp, t + ".b3.avg"), mx(hp, t + ".b3.max")], name=t + ".b3"),
+            b.add_images([conv5(hp, t + ".b4.c5"), conv3(hp, t + ".b4.c3")], name=t + ".b4"),
+        ]
+        out = b.concat_c(blocks, name=t + ".cat")
+        prev, cur = cur, out
+    g = b.gavgpool(cur, name="gap")
+    b.gemm(g, batch, 5 * width, 100, name="fc")
+    return b.build(seed, he_init=he_init)
+
+
 def _numel(shape):
     n = 1
     for s in shape:
@@ -341,4 +380,4 @@ def appendix_example_edges():
 
 def build_config(index):
     return (inception_block, googlenet_like, inception_v3_like, bert_base_like,
-            random_wide_dag)[index]()
+            random_wide_dag, nasnet_like)[index]()
