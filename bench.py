@@ -26,8 +26,8 @@ sys.path.insert(0, ROOT)
 # a streaming kernel of known size (profiles/igemm_f16_direct4_hbm_traffic.md,
 # profiles/persist_f16_googlenet_like_hbm_traffic.md).
 MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): 1493 * 1024,
-                          ("googlenet_like", "persist_f16"): (62425 + 31307) * 1024,
-                          ("googlenet_like", "persist_f16+zero_copy_concat"): (59846 + 26437) * 1024}
+                          ("googlenet_like", "persist_f16"): (61874 + 22603) * 1024,
+                          ("googlenet_like", "persist_f16+zero_copy_concat"): (59299 + 17733) * 1024}
 
 
 def percentile(a, q):
