@@ -112,7 +112,7 @@ def timeline_summary(session, exe):
         cur += d
         peak = max(peak, cur)
     total = sum(hist.values()) or 1.0
-    return dict(span_us=span / 1e3, workgroups=wgs, tiles=int(len(tr)), workgroup_busy_fraction=float(run.sum() / (span * wgs)),
+    return dict(span_us=span / 1e3, workgroups=wgs, work_items=int(len(tr)), workgroup_busy_fraction=float(run.sum() / (span * wgs)),
                 operators_in_flight_peak=peak, operators_in_flight_mean=area / total,
                 time_share_by_operators_in_flight={str(k): round(v / total, 4) for k, v in sorted(hist.items())},
                 median_tile_us=float(np.median(run)) / 1e3,

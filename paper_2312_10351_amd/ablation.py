@@ -51,6 +51,8 @@ def order_ablation(index, replays):
         row["sequential_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
         for pid, name in enumerate(B.ORDER_POLICY_NAMES):
             row[name + "_us"] = replay_latency(s, s.capture(B.PARALLEL, policy=pid), replays)
+        for pid, name in enumerate(B.ORDER_POLICY_NAMES):      # the same queues as work-item orders
+            row["persistent_" + name + "_us"] = replay_latency(s, s.capture_persistent(policy=pid), replays)
         return row
     finally:
         s.close()
@@ -67,8 +69,10 @@ def batch_sweep(batch, replays):
     try:
         seq = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
         par = replay_latency(s, s.capture(B.PARALLEL), replays)
+        per = replay_latency(s, s.capture_persistent(), replays)
         return {"ablation": "batch_sweep", "workload": wl.name, "batch": batch, "sequential_us": seq,
-                "parallel_us": par, "speedup": seq / par, "parallel_images_per_s": batch * 1e6 / par,
+                "parallel_us": par, "persistent_us": per, "speedup": seq / par, "speedup_persistent": seq / per,
+                "parallel_images_per_s": batch * 1e6 / par, "persistent_images_per_s": batch * 1e6 / per,
                 "sequential_images_per_s": batch * 1e6 / seq}
     finally:
         s.close()
@@ -150,6 +154,7 @@ def interference(kind_a, kind_b, replays):
     try:
         row["sequential_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
         row["parallel_us"] = replay_latency(s, s.capture(B.PARALLEL), replays)
+        row["persistent_us"] = replay_latency(s, s.capture_persistent(), replays)
     finally:
         s.close()
     for tag, kind in (("a", kind_a), ("b", kind_b)):

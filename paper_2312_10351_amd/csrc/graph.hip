@@ -295,6 +295,20 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     set_error("opara_capture_persistent: %d operators exceed the ticket table held in workgroup memory", n);
     return OPARA_EUNSUPPORTED;
   }
+  // Workgroups the device holds at once: the launch size, and the tiles per work item of
+  // operators that have more tiles than that.
+  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan[g->order[0]].kernel));
+  uint32_t wgs = 0;
+  {
+    hipError_t err = persist_max_workgroups(f16, lds_bytes, &wgs);
+    if (err != hipSuccess) {
+      set_error("opara_capture_persistent: occupancy query failed: %s", hipGetErrorString(err));
+      (void)hipGetLastError();
+      return OPARA_EHIP;
+    }
+  }
+  if (wgs == 0) { set_error("opara_capture_persistent: the kernel does not fit a compute unit"); return OPARA_EHIP; }
+  if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
   // Records in launch-queue order.
   std::vector<unsigned char> host(lay.bytes, 0);
   PersistHeader *hdr = (PersistHeader *)host.data();
@@ -306,21 +320,20 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
   std::vector<int32_t> pos_of(n, -1);
   std::vector<uint32_t> tiles(n, 0);
   int64_t total = 0;
-  bool f16 = false;
   for (int32_t i = 0; i < n; ++i) {
     const int32_t v = g->order[i];
     const KernelPlan &p = g->plan[v];
     const int kid = persist_kernel_id(p.kernel);
     if (kid < 0) { set_error("opara_capture_persistent: operator %d has no persistent kernel", v); return OPARA_EUNSUPPORTED; }
-    const bool is16 = kernel_is_f16(kid);
-    if (i > 0 && is16 != f16) { set_error("opara_capture_persistent: mixed element types"); return OPARA_EUNSUPPORTED; }
-    f16 = is16;
+    if (kernel_is_f16(kid) != f16) { set_error("opara_capture_persistent: mixed element types"); return OPARA_EUNSUPPORTED; }
     pos_of[v] = i;
     const int64_t t = (int64_t)p.gx * p.gy * p.gz;
     if (t < 1 || t > 65535 || total + t > INT32_MAX) { set_error("opara_capture_persistent: work-item count out of range"); return OPARA_EUNSUPPORTED; }
     tiles[i] = (uint32_t)t;
     begin[i] = (int32_t)total;
-    total += (t + kPersistItemAlign - 1) / kPersistItemAlign * kPersistItemAlign;
+    const int64_t chunk = (t + wgs - 1) / wgs;                  // 1 unless the operator has more tiles than workgroups
+    const int64_t items = (t + chunk - 1) / chunk;
+    total += (items + kPersistItemAlign - 1) / kPersistItemAlign * kPersistItemAlign;
     rec[i].kernel = kid + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
     rec[i].gx = (int32_t)p.gx; rec[i].gy = (int32_t)p.gy; rec[i].gz = (int32_t)p.gz;
     rec[i].args = p.args;
@@ -328,6 +341,7 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     if (np > kPersistMaxPreds) { set_error("opara_capture_persistent: operator %d has %d predecessors (limit %d)", v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
     preds[i].n = (uint16_t)np;
     preds[i].tiles = (uint16_t)t;
+    preds[i].chunk = (uint16_t)chunk;
     for (int32_t j = 0; j < np; ++j) {
       const int32_t u = pos_of[g->pred[g->pred_off[v] + j]];
       if (u < 0) { set_error("opara_capture_persistent: launch queue is not topological"); return OPARA_ESTATE; }
@@ -338,10 +352,6 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
   opara_exec *e = new (std::nothrow) opara_exec();
   if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
   {
-    uint32_t wgs = 0;
-    HIP_TRY(persist_max_workgroups(f16, lds_bytes, &wgs));       // all workgroups must be resident
-    if (wgs == 0) { set_error("opara_capture_persistent: the kernel does not fit a compute unit"); goto fail; }
-    if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
     if ((int64_t)wgs > total) wgs = (uint32_t)total;
     if (wgs > (uint32_t)kPersistItemAlign) wgs -= wgs % kPersistItemAlign;
     HIP_TRY(hipMemcpy(workspace, host.data(), lay.bytes, hipMemcpyHostToDevice));

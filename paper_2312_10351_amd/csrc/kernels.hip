@@ -1207,13 +1207,14 @@ __device__ __forceinline__ bool persist_wait(const PersistArgs &pa, const Persis
   return true;
 }
 
-// Thread 0 only, after the workgroup's stores are complete: count one finished tile of
+// Thread 0 only, after the workgroup's stores are complete: count the finished tiles of
 // the operator at `pos`; whoever counts the last tile clears the counter for the next
 // launch and raises every copy of the operator's flag.
-__device__ __forceinline__ void persist_publish(const PersistArgs &pa, const PersistPredsLds *preds, int pos, uint32_t epoch) {
+__device__ __forceinline__ void persist_publish(const PersistArgs &pa, const PersistPredsLds *preds, int pos, uint32_t count,
+                                                uint32_t epoch) {
   uint32_t *d = pa.done + (size_t)pos * kPersistCounterStride;
-  const uint32_t before = __hip_atomic_fetch_add(d, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (before + 1u == (uint32_t)preds[pos].tiles) {
+  const uint32_t before = __hip_atomic_fetch_add(d, count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (before + count == (uint32_t)preds[pos].tiles) {
     __hip_atomic_store(d, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t *f = pa.flags + (size_t)pos * (kPersistReplicas * kPersistFlagStride);
 #pragma unroll
@@ -1275,16 +1276,21 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
   }
   __syncthreads();
   int prev = -1;
-  uint32_t sink = 0;
+  uint32_t prev_count = 0, sink = 0;
   for (uint32_t item = blockIdx.x; item < (uint32_t)pa.total; item += gridDim.x) {
     const int pos = __builtin_amdgcn_readfirstlane(persist_find(begin, pa.n, item));
-    const int tile = (int)(item - (uint32_t)begin[pos]);
+    // A work item is `chunk` consecutive tiles of one operator (operators with more tiles
+    // than the launch has workgroups: one acquire, one record, one publication for the lot).
     // Operators start at multiples of kPersistItemAlign in the item space; the items that
     // pad an operator out denote no tile.
-    const bool padding = tile >= (int)preds[pos].tiles;
+    const int chunk = preds[pos].chunk;
+    const int tile0 = (int)(item - (uint32_t)begin[pos]) * chunk;
+    const int op_tiles = preds[pos].tiles;
+    const bool padding = tile0 >= op_tiles;
+    const int ntiles = padding ? 0 : min(chunk, op_tiles - tile0);
     if (tid == 0) {
       if (prev >= 0) {
-        persist_publish(pa, preds, prev, epoch);
+        persist_publish(pa, preds, prev, prev_count, epoch);
         if (trace) {
           uint64_t *rec = trace + 4 * (uint64_t)(item - gridDim.x);
           const uint64_t t_end = wall_clock64();
@@ -1306,13 +1312,19 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
     Blk b;
     b.gx = hd.y; b.gy = hd.z;
     // With the workgroup count and every operator's first item multiples of the XCD count,
-    // tile t runs on XCD t % 8 exactly as in an ordinary launch: the same remap applies.
-    b.remap = (gridDim.x % kPersistItemAlign) == 0;
-    b.x = tile % hd.y;
-    const int rest = tile / hd.y;
-    b.y = rest % hd.z;
-    b.z = rest / hd.z;
-    persist_run<F16>(hd.x, r, b, lds);
+    // tile t of an unchunked operator runs on XCD t % 8 exactly as in an ordinary launch:
+    // the same remap applies.  A chunk keeps consecutive tiles (neighbours that share
+    // operand rows) in one workgroup instead.
+    b.remap = chunk == 1 && (gridDim.x % kPersistItemAlign) == 0;
+    for (int k = 0; k < ntiles; ++k) {
+      const int tile = tile0 + k;
+      b.x = tile % hd.y;
+      const int rest = tile / hd.y;
+      b.y = rest % hd.z;
+      b.z = rest / hd.z;
+      if (k > 0) __syncthreads();                                // the previous tile is done with workgroup memory
+      persist_run<F16>(hd.x, r, b, lds);
+    }
     // While the stores drain: touch the next item's record so that its argument loads find
     // it in the scalar cache.  The values only feed a sink that is tested after the loop.
     {
@@ -1326,12 +1338,13 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
     __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): this wavefront's stores are complete
     __syncthreads();                                             // ... for every wavefront, and ctl has been read
     prev = pos;
+    prev_count = (uint32_t)ntiles;
   }
   // Leave: publish the last item; the last workgroup out clears the counters (nobody is
   // left to read them) and advances the launch number.
   if (tid == 0) {
     if (prev >= 0) {
-      persist_publish(pa, preds, prev, epoch);
+      persist_publish(pa, preds, prev, prev_count, epoch);
       if (trace) {
         // the loop has advanced `item` past the end: the last item of this workgroup is the
         // largest g + k*G below total

@@ -47,7 +47,11 @@ struct PersistHeader {            // 64 bytes at the start of the workspace
   uint32_t reserved[9];
 };
 // Predecessors of one operator as every workgroup keeps them in workgroup memory.
-struct PersistPredsLds { uint16_t n, tiles; uint16_t pos[kPersistMaxPreds]; };   // tiles: of this operator
+struct PersistPredsLds {
+  uint16_t n, tiles;               // predecessors; tiles of this operator
+  uint16_t chunk, pad;             // consecutive tiles one work item runs (>= 1)
+  uint16_t pos[kPersistMaxPreds];
+};
 constexpr uint32_t persist_lds_bytes(uint32_t n) {
   return kPersistBodyLds + 16 + 4 * (n + 1) + (uint32_t)sizeof(PersistPredsLds) * n;
 }

@@ -24,7 +24,7 @@ def operator_timeline(session, exe, order):
         m = tr[:, 3] == pos
         op = session.wl.ops[session.lib_ops[v]]
         rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(dem[v].kernel_id)[0],
-                         tiles=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
+                         tiles=int(dem[v].grid_blocks), items=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
                          last_published_us=float(tr[m, 2].max()) / 1e3,
                          median_tile_us=float(np.median(tr[m, 2] - tr[m, 1])) / 1e3,
                          median_wait_us=float(np.median(tr[m, 1] - tr[m, 0])) / 1e3))
