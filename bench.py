@@ -141,7 +141,15 @@ def bench_config(index, steps, warmup, with_kernels, zero_copy_concat=False):
         t4 = time.perf_counter()
         seq = s.capture(B.SEQUENTIAL)
         t5 = time.perf_counter()
-        per = s.capture_persistent()
+        # work-item order of the persistent executor: Alg. 2 queue or wave by wave, whichever a short
+        # probe finds faster (static dealing of tiles favours level order on very wide DAGs)
+        probe = {}
+        for pol in (B.ORDER_ALG2, B.ORDER_LEVEL):
+            exe = s.capture_persistent(policy=pol)
+            probe[pol] = time_replays(s, exe, 40, 10)["median_us"]
+        per_policy = min(probe, key=probe.get)
+        t5 = time.perf_counter()
+        per = s.capture_persistent(policy=per_policy)
         t6 = time.perf_counter()
         r_par = time_replays(s, par, steps, warmup)
         r_seq = time_replays(s, seq, steps, warmup)
@@ -155,7 +163,8 @@ def bench_config(index, steps, warmup, with_kernels, zero_copy_concat=False):
                    n_ops_launched=len(s.lib_ops), n_streams=ns, n_sync_edges=len(syncs),
                    graph_nodes_edges=B.opara_exec_info(par),
                    assign_streams_ms=(t1 - t0) * 1e3, order_launch_ms=(t2 - t1) * 1e3, capture_ms=(t4 - t3) * 1e3,
-                   persistent_capture_ms=(t6 - t5) * 1e3,
+                   persistent_capture_ms=(t6 - t5) * 1e3, persistent_queue=B.ORDER_POLICY_NAMES[per_policy],
+                   persistent_queue_probe_us={B.ORDER_POLICY_NAMES[k]: v for k, v in probe.items()},
                    parallel=r_par, sequential=r_seq, persistent=r_per,
                    persistent_timeline=timeline_summary(s, per), best_mode=best, best=r_best,
                    speedup_vs_sequential=r_seq["median_us"] / r_best["median_us"],
@@ -295,8 +304,8 @@ def main():
                    "concatenation": ("zero-copy: the branches write their channel slices of the concatenated tensor, "
                                      "%d of 81 operators are launched; the sequential baseline uses the same layout"
                                      % head["n_ops_launched"]) if head["zero_copy_concat"] else "explicit concatenation kernels",
-                   "mode": {"persistent": "persistent executor: one-kernel hipGraph replay (Alg. 2 launch order, "
-                                          "dependencies as completion flags)",
+                   "mode": {"persistent": "persistent executor: one-kernel hipGraph replay (work items in %s order, "
+                                          "dependencies as completion flags)" % head["persistent_queue"],
                             "multi_stream_graph": "multi-stream hipGraph replay (Alg. 1 streams, Alg. 2 launch order)"
                             }[head["best_mode"]]},
         "throughput_inferences_per_s": 1e6 / head["best"]["back_to_back_us"],
