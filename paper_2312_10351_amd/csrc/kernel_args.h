@@ -69,13 +69,15 @@ struct ConcatArgs {
   X(igemm_f16_t64x64, IgemmArgs)        \
   X(igemm_f16_direct4, IgemmArgs)       \
   X(igemm_f16_direct8, IgemmArgs)       \
-  X(igemm_f16_direct16, IgemmArgs)      \
+  X(igemm_f16_quad4, IgemmArgs)         \
+  X(igemm_f16_quad8, IgemmArgs)         \
   X(igemm_f16_t64x64_scalar, IgemmArgs) \
   X(igemm_f32_t128x64, IgemmArgs)       \
   X(igemm_f32_t64x64, IgemmArgs)        \
   X(igemm_f32_direct4, IgemmArgs)       \
   X(igemm_f32_direct8, IgemmArgs)       \
-  X(igemm_f32_direct16, IgemmArgs)      \
+  X(igemm_f32_quad4, IgemmArgs)         \
+  X(igemm_f32_quad8, IgemmArgs)         \
   X(igemm_f32_t64x64_scalar, IgemmArgs) \
   X(gemv_f16, IgemmArgs)                \
   X(gemv_f32, IgemmArgs)                \
@@ -136,6 +138,7 @@ constexpr IgemmTile kTile128x64{128, 64, 256};   // 128 output columns x 64 rows
 constexpr double kTiledMinFlops = 2.0e9;         // lighter contractions use the latency-oriented kernel
 constexpr int kTiledMinTiles = 80;               // ... and so do contractions with fewer 128x64 tiles
 constexpr IgemmTile kTile64{64, 64, 256};
+constexpr int64_t kQuadMinRowBytes = 1024;   // rows of K at least this long take the quad-coalesced variant
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)

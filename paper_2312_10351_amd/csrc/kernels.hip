@@ -718,6 +718,274 @@ __device__ __forceinline__ void igemm_direct_body(const AR &a, const Blk &b, uns
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Quad transposition.  The texture path serves a 16-byte-per-lane load at full rate only
+// when four adjacent lanes read 64 contiguous bytes; lanes that each touch a different
+// line are served one lane at a time (measured on gfx950: 14 against 43 bytes per clock
+// and compute unit).  An MFMA operand wants adjacent lanes on different rows.  So a lane
+// group of four loads four rows, 64 contiguous bytes of one row per instruction, and this
+// 4 x 4 exchange inside the group (two butterfly stages of cross-lane moves) hands every
+// lane the four pieces of its own row: afterwards register t of lane i holds what
+// register i of lane t held.  All cross-lane moves are unconditional; only the selects
+// depend on the lane.
+// ---------------------------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ uint32_t quad_move(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xf, 0xf, true);
+}
+template <int T> __device__ __forceinline__ int quad_broadcast(int v) {
+  return __builtin_amdgcn_mov_dpp(v, T * 0x55, 0xf, 0xf, true);
+}
+template <typename V> __device__ __forceinline__ void quad_transpose(V (&r)[4], bool odd, bool hi) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  static_assert(sizeof(V) == 16, "fragment size");
+  u32x4 u[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) u[t] = __builtin_bit_cast(u32x4, r[t]);
+#pragma unroll
+  for (int p = 0; p < 2; ++p)              // lane bit 0 <-> register bit 0
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t a0 = u[2 * p][d], b0 = u[2 * p + 1][d];
+      const uint32_t pa = quad_move<0xB1>(a0), pb = quad_move<0xB1>(b0);   // lanes [1,0,3,2]
+      u[2 * p][d] = odd ? pb : a0;
+      u[2 * p + 1][d] = odd ? b0 : pa;
+    }
+#pragma unroll
+  for (int p = 0; p < 2; ++p)              // lane bit 1 <-> register bit 1
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t a0 = u[p][d], b0 = u[p + 2][d];
+      const uint32_t pa = quad_move<0x4E>(a0), pb = quad_move<0x4E>(b0);   // lanes [2,3,0,1]
+      u[p][d] = hi ? pb : a0;
+      u[p + 2][d] = hi ? b0 : pa;
+    }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) r[t] = __builtin_bit_cast(V, u[t]);
+}
+
+// ---------------------------------------------------------------------------------
+// Latency-oriented implicit GEMM for small problems (batch-1 convolutions, skinny
+// GEMMs): a workgroup owns a 32 x 32 output tile and its WAVES wavefronts split K
+// between them in steps of 256 bytes per row.  Operands come straight from global
+// memory, no LDS and no barrier inside the K loop: in one load instruction a group of
+// four lanes reads 64 contiguous bytes of one row (see quad_transpose), the next step's
+// loads are in flight while the current one is transposed and multiplied.  Partial tiles
+// meet in LDS once, at the end, where 256 threads apply the epilogue and write 8/16-byte
+// pieces of output rows.
+// ---------------------------------------------------------------------------------
+template <typename T, int WAVES, int COH, typename AR>
+__device__ __forceinline__ void igemm_quad_body(const AR &a, const Blk &b, unsigned char *lds) {
+  typedef typename Vec16<T>::type V;
+  typedef typename Vec16<T>::quad Q;
+  constexpr int VE = Vec16<T>::N;
+  constexpr int DS = 16 * VE;              // K elements per step: 4 lane groups x 4 pieces of 16 bytes
+  constexpr int PITCH = 36;                // floats per pixel row of a partial tile in LDS
+  float (*part)[32][PITCH] = (float (*)[32][PITCH])lds;                                // [WAVES][32][PITCH]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int grp = lane >> 4, r16 = lane & 15, qd = (lane >> 2) & 3, pc = lane & 3;
+  const bool odd = (lane & 1) != 0, hi = (lane & 2) != 0;
+  int tile_x, tile_y;
+  xcd_tile(b, tile_x, tile_y);
+  const int m0 = tile_x * 32, n0 = tile_y * 32;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
+
+  const int nds = (a.K + DS - 1) / DS;
+  const int per_wave = (nds + WAVES - 1) / WAVES;
+  const int ds_begin = wave * per_wave;
+  const int ds_end = min(nds, ds_begin + per_wave);
+  // Only the last step of K can be partial; it runs apart from the pipelined steps.
+  const bool owns_tail = a.K % DS != 0 && ds_begin < nds && ds_end == nds;
+  const int main_end = owns_tail ? ds_end - 1 : ds_end;
+  const int kc = (grp * 4 + pc) * VE;      // this lane's 16-byte piece inside a step
+
+  // Register t of block i loads row 16*i + 4*qd + t (clamped into range; results of
+  // clamped rows are never stored).  Offsets are elements from the operand's base and fit
+  // 32 bits (the host selects this kernel only for operands below 2^31 elements).
+  int woff[2][4], xoff[2][4], ihq[2][4], iwq[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      woff[i][tt] = min(n0 + i * 16 + qd * 4 + tt, a.N - 1) * (int)a.ldb + kc;
+      xoff[i][tt] = min(m0 + i * 16 + qd * 4 + tt, a.M - 1) * (int)a.lda + kc;
+    }
+  KPos pos = {0, 0, 0};
+  if (a.gather) {
+    // Pixel geometry of this lane's own row, then of the group's four rows by broadcast.
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int m = min(m0 + j * 16 + r16, a.M - 1);
+      const int img = m / a.HoWo, pix = m - img * a.HoWo;
+      const int oh = pix / a.Wo, ow = pix - oh * a.Wo;
+      const int ih0 = oh * a.sh - a.ph, iw0 = ow * a.sw - a.pw, im0 = img * (int)a.img_stride;
+      ihq[j][0] = quad_broadcast<0>(ih0); ihq[j][1] = quad_broadcast<1>(ih0);
+      ihq[j][2] = quad_broadcast<2>(ih0); ihq[j][3] = quad_broadcast<3>(ih0);
+      iwq[j][0] = quad_broadcast<0>(iw0); iwq[j][1] = quad_broadcast<1>(iw0);
+      iwq[j][2] = quad_broadcast<2>(iw0); iwq[j][3] = quad_broadcast<3>(iw0);
+      xoff[j][0] = quad_broadcast<0>(im0); xoff[j][1] = quad_broadcast<1>(im0);
+      xoff[j][2] = quad_broadcast<2>(im0); xoff[j][3] = quad_broadcast<3>(im0);
+    }
+    if (ds_begin < ds_end) {
+      const int k = ds_begin * DS + kc;
+      pos.ci = k % a.Cin;
+      const int rs = k / a.Cin;
+      pos.s = rs % a.kw;
+      pos.r = rs / a.kw;
+    }
+  }
+
+  floatx4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const V vzero = {};
+
+  // Epilogue operands of this thread's output piece (bias, residual inputs) are requested
+  // before the K walk, so that their latency is hidden behind it.
+  const int pm = t >> 3, pn = (t & 7) * 4;
+  const int m = m0 + pm, n = n0 + pn;
+  const bool full = n + 3 < a.N;           // whole group of four channels inside the tensor
+  const bool live = t < 256 && m < a.M && n < a.N;
+  floatx4 badd = {0.f, 0.f, 0.f, 0.f};
+  if (live && a.bias) {
+    if (full && ((uintptr_t)(a.bias + n) & 15) == 0) badd = *(const floatx4 *)(a.bias + n);
+    else
+      for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] = a.bias[n + e];
+  }
+  if (live)
+    for (int q = 0; q < a.n_extra; ++q) {
+      const T *ex = (const T *)a.extra[q] + (int64_t)m * a.N + n;
+      if (full && ((uintptr_t)ex & (4 * sizeof(T) - 1)) == 0) {
+        const Q v = ldg<CA, Q>(ex);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) badd[e] += (float)v[e];
+      } else {
+        for (int e = 0; e < 4; ++e) if (n + e < a.N) badd[e] += (float)ldg<CA, T>(ex + e);
+      }
+    }
+
+  struct Frag { V w[2][4], x[2][4]; };
+  // Requests one step.  In the partial step a lane whose piece lies past the end of K
+  // requests nothing and contributes zeros; padding taps of a convolution read a valid
+  // address and are zeroed after arrival.
+  auto issue = [&](auto tail_tag, int ds, Frag &f) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int kb = ds * DS;
+    const bool kok = !TAIL || kb + kc < a.K;
+    unsigned inb = 0xffu;
+    int xo[2][4];
+    if (a.gather) {
+      inb = 0;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          const int ih = ihq[j][tt] + pos.r, iw = iwq[j][tt] + pos.s;
+          const bool in = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+          inb |= in ? 1u << (j * 4 + tt) : 0u;
+          xo[j][tt] = in ? xoff[j][tt] + (ih * a.W + iw) * a.Cin + pos.ci : 0;
+        }
+      kpos_advance(pos, DS, a.Cin, a.kw);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) xo[j][tt] = xoff[j][tt] + kb;
+    }
+    if (kok) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) f.w[i][tt] = ldg<CW, V>(w + woff[i][tt] + kb);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) f.x[j][tt] = ldg<CA, V>(x + xo[j][tt]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) { f.w[i][tt] = vzero; f.x[i][tt] = vzero; }
+    }
+    return inb;
+  };
+  auto compute = [&](Frag &f, unsigned inb) {
+    if (a.gather) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) f.x[j][tt] = ((inb >> (j * 4 + tt)) & 1u) ? f.x[j][tt] : vzero;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      quad_transpose(f.w[i], odd, hi);
+      quad_transpose(f.x[i], odd, hi);
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mma16<T>(f.w[i][tt], f.x[j][tt], acc[i][j]);
+  };
+  if (ds_begin < main_end) {
+    // Two register sets: the loads of step ds+1 are requested before step ds is
+    // transposed and multiplied.  Inside the loop the request is unconditional (after a
+    // conditional one the compiler waits for everything in flight), and the empty
+    // statement pins the order: nothing else keeps a plain load from sinking to its use.
+    Frag cur, nxt;
+    unsigned inb_cur = issue(std::false_type{}, ds_begin, cur), inb_nxt;
+#pragma nounroll
+    for (int ds = ds_begin + 1; ds < main_end; ++ds) {
+      inb_nxt = issue(std::false_type{}, ds, nxt);
+      asm volatile("" ::: "memory");
+      compute(cur, inb_cur);
+      cur = nxt;
+      inb_cur = inb_nxt;
+    }
+    compute(cur, inb_cur);
+  }
+  if (owns_tail) {
+    Frag f;
+    const unsigned inb = issue(std::true_type{}, main_end, f);
+    compute(f, inb);
+  }
+
+  // ---- meet in LDS: lane holds channels n = i*16 + grp*4 + e of pixel m = j*16 + r16
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) *(floatx4 *)&part[wave][j * 16 + r16][i * 16 + grp * 4] = acc[i][j];
+  __syncthreads();
+  if (t < 256) {
+    floatx4 sum = *(const floatx4 *)&part[0][pm][pn];
+#pragma unroll
+    for (int q = 1; q < WAVES; ++q) sum += *(const floatx4 *)&part[q][pm][pn];
+    if (live) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float r = sum[e] * a.alpha + badd[e];
+        v[e] = a.relu ? fmaxf(r, 0.f) : r;
+      }
+      T *dst = y + (int64_t)m * a.ldy + n;
+      if (full && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+        Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+        stg<CS, Q>(dst, q4);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < a.N) stg<CS, T>(dst + e, (T)v[e]);
+      }
+    }
+  }
+}
+
 // Matrix-vector shaped GEMM (M <= kGemvMaxM rows): one wavefront per output column,
 // 16-byte loads along K, shuffle reduction.  Weight-bandwidth bound by construction.
 template <typename T, int COH, typename AR>
@@ -1046,13 +1314,15 @@ KDEF2(igemm_f16_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<
 KDEF(igemm_f16_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
 KDEF(igemm_f16_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0>(a, b, lds)))
 KDEF(igemm_f16_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<half_t, 8, 2, 0>(a, b, lds)))
-KDEF(igemm_f16_direct16, 1024, lds_direct(16), IgemmArgs, (igemm_direct_body<half_t, 16, 2, 0>(a, b, lds)))
+KDEF(igemm_f16_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<half_t, 4, 0>(a, b, lds)))
+KDEF(igemm_f16_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<half_t, 8, 0>(a, b, lds)))
 KDEF(igemm_f16_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF2(igemm_f32_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
 KDEF(igemm_f32_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<float, 4, 2, 0>(a, b, lds)))
 KDEF(igemm_f32_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<float, 8, 2, 0>(a, b, lds)))
-KDEF(igemm_f32_direct16, 1024, lds_direct(16), IgemmArgs, (igemm_direct_body<float, 16, 2, 0>(a, b, lds)))
+KDEF(igemm_f32_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<float, 4, 0>(a, b, lds)))
+KDEF(igemm_f32_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<float, 8, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF(gemv_f16, 256, kLdsNone, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
 KDEF(gemv_f32, 256, kLdsNone, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
@@ -1463,8 +1733,10 @@ hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNo
 
 int persist_kernel_id(int id) {
   switch (id) {
-    case K_igemm_f16_direct8: case K_igemm_f16_direct16: return K_igemm_f16_direct4;
-    case K_igemm_f32_direct8: case K_igemm_f32_direct16: return K_igemm_f32_direct4;
+    // One tile shape, one workgroup size: inside the persistent kernel every
+    // latency-oriented contraction runs the four-wavefront fragment-loading body.
+    case K_igemm_f16_direct8: case K_igemm_f16_quad4: case K_igemm_f16_quad8: return K_igemm_f16_direct4;
+    case K_igemm_f32_direct8: case K_igemm_f32_quad4: case K_igemm_f32_quad8: return K_igemm_f32_direct4;
     default: return (id >= 0 && id < K_COUNT) ? id : -1;
   }
 }

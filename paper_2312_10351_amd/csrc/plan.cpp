@@ -18,6 +18,14 @@ namespace {
 
 // Tuning knob (read once): OPARA_TILED_MIN_FLOPS moves the hand-over point between the
 // latency-oriented and the tiled contraction kernel.
+int64_t quad_min_row_bytes() {
+  static const int64_t v = [] {
+    const char *e = std::getenv("OPARA_QUAD_MIN_ROW_BYTES");
+    return e ? (int64_t)std::atoll(e) : kQuadMinRowBytes;
+  }();
+  return v;
+}
+
 double tiled_min_flops() {
   static const double v = [] {
     const char *e = std::getenv("OPARA_TILED_MIN_FLOPS");
@@ -117,6 +125,9 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     const double flops = 2.0 * a.M * a.N * a.K * (double)batch;
     const int64_t tiles = (int64_t)cdiv(a.M, kTile128x64.bm) * cdiv(a.N, kTile128x64.bn) * batch;
     (void)n128;
+    const int64_t lim32 = (int64_t)1 << 31;
+    const bool fits32 = (int64_t)a.M * a.lda < lim32 && (int64_t)a.N * a.ldb < lim32 &&
+                        (!a.gather || (int64_t)(a.M / a.HoWo) * a.img_stride < lim32);
     if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= tiled_min_flops()) {
       // Throughput-oriented tiled kernel (128 output columns x 64 rows per workgroup):
       // pays once the contraction is heavy and has enough tiles to occupy the device.
@@ -125,14 +136,22 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     } else if (a.b_kmajor) {           // [K][N] operand: staged (and transposed) through LDS
       t = kTile64;
       kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64;
+    } else if (!fits32) {              // the latency-oriented kernel keeps 32-bit element offsets
+      t = kTile64;
+      kernel = f16 ? K_igemm_f16_t64x64 : K_igemm_f32_t64x64;
     } else {
-      // Latency-oriented kernel; more wavefronts share K the deeper it is, so that no
-      // wavefront walks more than two pairs of 64-byte steps.
-      const int nds = (int)cdiv(a.K, 8 * ve);
-      const int waves = nds <= 16 ? 4 : nds <= 32 ? 8 : 16;
-      static const int ids[2][3] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_direct16},
-                                    {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_direct16}};
-      out->kernel = ids[f16][waves == 4 ? 0 : waves == 8 ? 1 : 2];
+      // Latency-oriented kernels, one 32 x 32 tile per workgroup, K split between its
+      // wavefronts.  Deep contractions take the variant whose loads are coalesced in lane
+      // groups of four (three times the load rate, paid for with a register transposition
+      // per 256-byte step); shallow ones, where a wavefront walks a step or two, the
+      // variant that loads MFMA fragments as they are.
+      static const int ids[2][4] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_quad4, K_igemm_f32_quad8},
+                                    {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_quad4, K_igemm_f16_quad8}};
+      const bool quad = (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
+      int waves;
+      if (quad) waves = cdiv(a.K, 16 * ve) <= 8 ? 4 : 8;       // 256-byte steps, at most four per wavefront up to K = 8192 B
+      else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
+      out->kernel = ids[f16][(quad ? 2 : 0) + (waves == 8 ? 1 : 0)];
       out->gx = cdiv(a.M, kDirectTile);
       out->gy = cdiv(a.N, kDirectTile);
       out->gz = (uint32_t)batch;

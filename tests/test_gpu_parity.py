@@ -48,7 +48,11 @@ CONV_CASES = [  # cin, h, w, cout, k, stride, pad
     (24, 15, 15, 33, 3, 2, 0), (8, 10, 9, 16, (1, 7), 1, (0, 3)), (8, 9, 10, 16, (7, 1), 1, (3, 0)),
     (16, 8, 8, 72, (1, 3), 1, (0, 1)), (16, 8, 8, 72, (3, 1), 1, (1, 0)), (5, 7, 6, 7, 3, 1, 1),
     (64, 28, 28, 96, 3, 1, 1), (40, 20, 20, 130, 1, 1, 0), (8, 40, 40, 136, 3, 1, 1),
-    (128, 56, 56, 256, 3, 1, 1), (96, 47, 45, 200, 5, 2, 2)]   # large enough for the tiled split-K kernel
+    (128, 56, 56, 256, 3, 1, 1), (96, 47, 45, 200, 5, 2, 2),   # large enough for the tiled split-K kernel
+    # deep K on few pixels: the quad-coalesced kernels, with a partial last K step, idle wavefronts, padding taps,
+    # strides, and pixel / channel counts that are no multiples of four
+    (24, 15, 15, 33, 5, 1, 2), (48, 7, 7, 40, 5, 1, 2), (72, 9, 9, 35, 3, 2, 1), (160, 5, 6, 50, 3, 1, 1),
+    (32, 6, 5, 18, (1, 7), 1, (0, 3)), (264, 3, 3, 21, 3, 1, 1), (520, 7, 7, 30, 1, 1, 0)]
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
@@ -66,6 +70,7 @@ def test_conv(case, dtype):
 
 
 GEMM_CASES = [(1, 64, 40), (3, 200, 17), (5, 96, 64), (37, 72, 50), (64, 256, 64), (130, 136, 200),
+              (37, 520, 50), (5, 1032, 33), (70, 4104, 96), (130, 8200, 40),      # quad-coalesced kernels, K tails
               (128, 768, 768), (512, 320, 1024), (33, 7, 9), (1, 1024, 1000),
               (256, 2048, 1024), (512, 4096, 512), (200, 1544, 2048), (384, 512, 4096), (1100, 264, 2000)]
 
@@ -137,6 +142,23 @@ def test_rowwise_and_elementwise(r, c, dtype):
 
 
 # ------------------------------------------------------------------ whole DAGs
+def test_deep_contractions_take_the_quad_coalesced_kernels():
+    """The cases above that are meant for the quad-coalesced kernels really are planned onto them."""
+    from paper_2312_10351_amd.runtime import Session
+    for dtype in ("f16", "f32"):
+        b = Builder("pick", dtype)
+        x = b.ext((72, 9, 9)); b.conv(x, 35, 3, stride=2, pad=1)
+        g = b.ext((70, 4104)); b.gemm(g, 70, 4104, 96)
+        h = b.ext((64, 64)); b.gemm(h, 64, 64, 64)
+        s = Session(b.build(1))
+        try:
+            names = [B.opara_kernel_info(d.kernel_id)[0] for d in B.opara_get_demands(s.dag)]
+        finally:
+            s.close()
+        first = "quad4" if dtype == "f16" else "quad8"       # K = 648: six or eleven 256-byte steps
+        assert names == [f"igemm_{dtype}_{first}", f"igemm_{dtype}_quad8", f"igemm_{dtype}_direct4"], names
+
+
 def test_inception_block_fp32_all_modes():
     wl = inception_block()
     sinks = run_modes(wl, modes=("eager", "seq", "par"))
