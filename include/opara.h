@@ -314,6 +314,15 @@ int opara_persistent_status(opara_exec *e, void *hip_stream, uint32_t *error_wor
 /* Work items and workgroups of a persistent executor (host int32 each). */
 int opara_persistent_info(const opara_exec *e, int32_t *n_items, int32_t *n_workgroups);
 /*
+ * Tiles (workgroup-sized pieces) and kernel id of every operator as the persistent
+ * executor runs it: tiles[n_ops], kernel_ids[n_ops] (host, either may be NULL).  The
+ * persistent executor has one workgroup size and its own hand-over point between the
+ * contraction kernels, so these can differ from the graph executors' launch grids that
+ * opara_get_demands reports (paper Sec. 3.2 profiles one kernel per operator; here an
+ * operator has one per executor kind).  No HIP call.
+ */
+int opara_persistent_plan(const opara_dag *g, int32_t *tiles, int32_t *kernel_ids);
+/*
  * Timeline of the following replays (tracing; the one kernel hides the operators from
  * a profiler).  trace: device memory, caller-owned, 8-byte aligned, 32 bytes per work
  * item, or NULL to switch tracing off.  Work item i (launch-queue order, tiles of an

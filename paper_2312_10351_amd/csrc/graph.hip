@@ -297,7 +297,7 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
   }
   // Workgroups the device holds at once: the launch size, and the tiles per work item of
   // operators that have more tiles than that.
-  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan[g->order[0]].kernel));
+  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan_persist[g->order[0]].kernel));
   uint32_t wgs = 0;
   {
     hipError_t err = persist_max_workgroups(f16, lds_bytes, &wgs);
@@ -322,7 +322,7 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
   int64_t total = 0;
   for (int32_t i = 0; i < n; ++i) {
     const int32_t v = g->order[i];
-    const KernelPlan &p = g->plan[v];
+    const KernelPlan &p = g->plan_persist[v];
     const int kid = persist_kernel_id(p.kernel);
     if (kid < 0) { set_error("opara_capture_persistent: operator %d has no persistent kernel", v); return OPARA_EUNSUPPORTED; }
     if (kernel_is_f16(kid) != f16) { set_error("opara_capture_persistent: mixed element types"); return OPARA_EUNSUPPORTED; }

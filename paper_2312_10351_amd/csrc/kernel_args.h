@@ -135,7 +135,8 @@ struct KernelPlan {
 // Tile geometry of the implicit-GEMM kernels (output columns x rows per workgroup).
 struct IgemmTile { int bn, bm, threads; };
 constexpr IgemmTile kTile128x64{128, 64, 256};   // 128 output columns x 64 rows
-constexpr double kTiledMinFlops = 6.0e9;         // lighter contractions use the latency-oriented kernel
+constexpr double kTiledMinFlops = 6.0e9;          // lighter contractions use the latency-oriented kernels
+constexpr double kTiledMinFlopsPersistent = 2.0e9;   // inside the persistent kernel (four wavefronts per tile whatever K is)
 constexpr int kTiledMinTiles = 80;               // ... and so do contractions with fewer 128x64 tiles
 constexpr IgemmTile kTile64{64, 64, 256};
 constexpr int64_t kQuadMinRowBytes = 1024;   // rows of K at least this long take the quad-coalesced variant

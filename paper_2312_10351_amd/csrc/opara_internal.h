@@ -14,7 +14,8 @@ struct opara_dag {
   // CSR adjacency over operator ids; predecessors in argument order, deduplicated.
   std::vector<int32_t> pred_off, pred, succ_off, succ;
   std::vector<int32_t> topo, tindex;
-  std::vector<opara::KernelPlan> plan;
+  std::vector<opara::KernelPlan> plan;          // graph executors (and the demand table)
+  std::vector<opara::KernelPlan> plan_persist;  // persistent executor
   std::vector<opara_demand> dem;
   std::vector<int32_t> stream_of;   // empty until opara_assign_streams
   int32_t n_streams = 0;
@@ -33,7 +34,10 @@ void set_error(const char *fmt, ...);
 int sync_keep_mask(const opara_dag *g, std::vector<uint8_t> *keep);
 
 // Chooses the kernel, grid and arguments for operator `v`; `in[i]` are the resolved
-// device pointers of its inputs.  Returns an opara_status.
-int plan_op(const opara_op_desc &op, const void *const *in, KernelPlan *out);
+// device pointers of its inputs.  `persistent` asks for the plan the persistent executor
+// runs (one workgroup size, its own hand-over point to the tiled contraction kernel); the
+// other plan is the one the graph executors launch and the demand table describes.
+// Returns an opara_status.
+int plan_op(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out);
 
 }  // namespace opara

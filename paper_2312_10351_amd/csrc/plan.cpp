@@ -42,7 +42,7 @@ int fail(const char *what, const opara_op_desc &op) {
   return OPARA_EINVAL;
 }
 
-int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out) {
   const opara_op_params &p = op.params;
   const bool f16 = op.dtype == OPARA_F16;
   const int ve = f16 ? 8 : 4;
@@ -128,7 +128,7 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
     const int64_t lim32 = (int64_t)1 << 31;
     const bool fits32 = (int64_t)a.M * a.lda < lim32 && (int64_t)a.N * a.ldb < lim32 &&
                         (!a.gather || (int64_t)(a.M / a.HoWo) * a.img_stride < lim32);
-    if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= tiled_min_flops()) {
+    if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= (persistent ? kTiledMinFlopsPersistent : tiled_min_flops())) {
       // Throughput-oriented tiled kernel (128 output columns x 64 rows per workgroup):
       // pays once the contraction is heavy and has enough tiles to occupy the device.
       t = kTile128x64;
@@ -147,7 +147,7 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, KernelPlan *out) 
       // variant that loads MFMA fragments as they are.
       static const int ids[2][4] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_quad4, K_igemm_f32_quad8},
                                     {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_quad4, K_igemm_f16_quad8}};
-      const bool quad = (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
+      const bool quad = !persistent && (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
       int waves;
       if (quad) waves = cdiv(a.K, 16 * ve) <= 8 ? 4 : 8;       // 256-byte steps, at most four per wavefront up to K = 8192 B
       else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
@@ -282,11 +282,11 @@ int plan_concat(const opara_op_desc &op, const void *const *in, KernelPlan *out)
 
 }  // namespace
 
-int plan_op(const opara_op_desc &op, const void *const *in, KernelPlan *out) {
+int plan_op(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out) {
   std::memset(out, 0, sizeof *out);
   int rc;
   switch (op.op_type) {
-    case OPARA_CONV2D: case OPARA_GEMM: case OPARA_BGEMM: rc = plan_igemm(op, in, out); break;
+    case OPARA_CONV2D: case OPARA_GEMM: case OPARA_BGEMM: rc = plan_igemm(op, in, persistent, out); break;
     case OPARA_MAXPOOL: case OPARA_AVGPOOL: rc = plan_pool(op, in, out); break;
     case OPARA_GAVGPOOL: rc = plan_gap(op, in, out); break;
     case OPARA_LAYERNORM: case OPARA_SOFTMAX: rc = plan_row(op, in, out); break;

@@ -138,6 +138,7 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
     }
     // ---- kernel plan + demand record per operator
     g->plan.resize(n_ops);
+    g->plan_persist.resize(n_ops);
     g->dem.resize(n_ops);
     for (int v = 0; v < n_ops; ++v) {
       const opara_op_desc &op = g->ops[v];
@@ -147,7 +148,8 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
         in[i] = u < 0 ? g->ext[-(int64_t)u - 1] : g->ops[u].out;
         if (!in[i]) { set_error("operator %d: input %d resolves to a null pointer", v, i); delete g; return OPARA_EINVAL; }
       }
-      rc = plan_op(op, in, &g->plan[v]);
+      rc = plan_op(op, in, false, &g->plan[v]);
+      if (rc == OPARA_OK) rc = plan_op(op, in, true, &g->plan_persist[v]);
       if (rc != OPARA_OK) { delete g; return rc; }
       const KernelPlan &p = g->plan[v];
       const KernelResource &r = kKernelResources[p.kernel];
@@ -406,6 +408,16 @@ extern "C" int32_t opara_num_ops(const opara_dag *g) { return g ? g->n : 0; }
 extern "C" void opara_dag_destroy(opara_dag *g) { delete g; }
 
 extern "C" int32_t opara_kernel_count(void) { return K_COUNT; }
+
+extern "C" int opara_persistent_plan(const opara_dag *g, int32_t *tiles, int32_t *kernel_ids) {
+  if (!g) { set_error("opara_persistent_plan: null graph"); return OPARA_EINVAL; }
+  for (int32_t v = 0; v < g->n; ++v) {
+    const KernelPlan &p = g->plan_persist[v];
+    if (tiles) tiles[v] = (int32_t)((int64_t)p.gx * p.gy * p.gz);
+    if (kernel_ids) kernel_ids[v] = p.kernel;
+  }
+  return OPARA_OK;
+}
 
 extern "C" int opara_kernel_info(int32_t id, const char **name, uint32_t *vgprs, uint32_t *lds_bytes) {
   if (id < 0 || id >= K_COUNT) { set_error("opara_kernel_info: id %d out of range", id); return OPARA_EINVAL; }

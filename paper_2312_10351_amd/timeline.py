@@ -18,13 +18,13 @@ import numpy as np
 def operator_timeline(session, exe, order):
     from . import binding as B
     tr = session.persistent_trace(exe)
-    dem = B.opara_get_demands(session.dag)
+    tiles, kernels = B.opara_persistent_plan(session.dag)
     rows = []
     for pos, v in enumerate(order):
         m = tr[:, 3] == pos
         op = session.wl.ops[session.lib_ops[v]]
-        rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(dem[v].kernel_id)[0],
-                         tiles=int(dem[v].grid_blocks), items=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
+        rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(kernels[v])[0],
+                         tiles=int(tiles[v]), items=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
                          last_published_us=float(tr[m, 2].max()) / 1e3,
                          median_tile_us=float(np.median(tr[m, 2] - tr[m, 1])) / 1e3,
                          median_wait_us=float(np.median(tr[m, 1] - tr[m, 0])) / 1e3))

@@ -65,10 +65,10 @@ def test_replays_are_identical_and_rewrite_every_output():
         assert all(torch.equal(a, t.view(torch.int16)) for a, t in zip(bits[0], s.out_dev))
         assert B.opara_exec_info(exe) == (1, 0)
         items, wgs = B.opara_persistent_info(exe)
-        dem = B.opara_get_demands(s.dag)
+        tiles, _ = B.opara_persistent_plan(s.dag)
         # an operator with more tiles than workgroups runs ceil(tiles / workgroups) tiles per item;
         # every operator's item range is padded to the XCD count
-        per_op = [-(-d.grid_blocks // -(-d.grid_blocks // wgs)) for d in dem]
+        per_op = [-(-t // -(-t // wgs)) for t in tiles]
         assert items == sum((i + 7) // 8 * 8 for i in per_op) and 1 <= wgs <= items
     finally:
         s.close()
@@ -131,13 +131,13 @@ def test_timeline_is_consistent_with_the_dag():
         assert s.persistent_status(exe) == 0
         order = B.opara_order_launch_policy(s.dag, B.ORDER_ALG2)
         pos_of = {v: i for i, v in enumerate(order)}
-        dem = B.opara_get_demands(s.dag)
+        plan_tiles, _ = B.opara_persistent_plan(s.dag)
         _, wgs = B.opara_persistent_info(exe)
         assert np.all(tr[:, 0] <= tr[:, 1]) and np.all(tr[:, 1] <= tr[:, 2])
         first_ready, last_start, last_end = {}, {}, {}
         for p in range(len(order)):
             m = tr[:, 3] == p
-            tiles = dem[order[p]].grid_blocks
+            tiles = plan_tiles[order[p]]
             assert m.sum() == -(-tiles // -(-tiles // wgs))            # items = ceil(tiles / chunk)
             first_ready[p], last_start[p], last_end[p] = tr[m, 1].min(), tr[m, 1].max(), tr[m, 2].max()
         stamp_delay_ns = 3000
