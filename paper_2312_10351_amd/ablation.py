@@ -1,6 +1,6 @@
 """Launch-order and interference ablations over the same kernels and graphs.
 
-  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32] [--concat-configs 0,1,2] [--stream-configs 0,1,2,3,4]
+  python -m paper_2312_10351_amd.ablation [--configs 0,1,2,3,4] [--replays 300] [--batches 1,2,4,8,16,32] [--concat-configs 0,1,2] [--stream-configs 0,1,2,3,4] [--markdown]
 
 Part 1 (paper Sec. 2.3, "GPU blocking"): the parallel graph is captured with each
 launch-order policy of opara_order_launch_policy and replayed; only the queue differs.
@@ -11,7 +11,7 @@ Part 3 (paper Sec. 5.2): batch sweep of the Inception-v3-like DAG.
 Part 4: zero-copy concatenation against explicit concatenation kernels (CNN configs).
 Part 5: stream-allocation policies (Alg. 1 / fewest streams) with and without pruning of implied
         synchronisations: streams, synchronisations, host time, latency.
-Prints one JSON object per line.
+Prints one JSON object per line (and, with --markdown, the same records as tables at the end).
 """
 import argparse
 import json
@@ -172,6 +172,55 @@ def interference(kind_a, kind_b, replays):
     return row
 
 
+def render_markdown(records):
+    """The records of one run as markdown tables (microseconds), one section per ablation."""
+    from . import binding as B
+    out = []
+    by = lambda kind: [r for r in records if r["ablation"] == kind]
+    pol = list(B.ORDER_POLICY_NAMES)
+    if by("launch_order"):
+        for title, prefix in (("Launch order, multi-stream graph", ""), ("Launch order, persistent executor", "persistent_")):
+            out += ["", f"### {title}", "", "| workload | sequential graph | " + " | ".join(pol) + " |", "|---|---|" + "---|" * len(pol)]
+            for r in by("launch_order"):
+                out.append(f"| {r['workload']} ({r['n_ops']}) | {r['sequential_us']:.1f} | " +
+                           " | ".join(f"{r[prefix + n + '_us']:.1f}" for n in pol) + " |")
+    if by("interference"):
+        out += ["", "### Interference pairs", "",
+                "| pair | A alone | B alone | one stream, back to back | two streams (graph) | gain | persistent executor |",
+                "|---|---|---|---|---|---|---|"]
+        for r in by("interference"):
+            out.append(f"| {r['pair']} | {r['alone_a_us']:.1f} | {r['alone_b_us']:.1f} | {r['sequential_us']:.1f} | "
+                       f"{r['parallel_us']:.1f} | {r['overlap_gain']:.2f}x | {r['persistent_us']:.1f} |")
+    if by("batch_sweep"):
+        out += ["", "### Batch sweep", "",
+                "| batch | sequential us | multi-stream graph us | persistent us | graph speed-up | persistent speed-up | best images/s |",
+                "|---:|---:|---:|---:|---:|---:|---:|"]
+        for r in by("batch_sweep"):
+            best = max(r["parallel_images_per_s"], r["persistent_images_per_s"], r["sequential_images_per_s"])
+            out.append(f"| {r['batch']} | {r['sequential_us']:.0f} | {r['parallel_us']:.0f} | {r['persistent_us']:.0f} | "
+                       f"{r['speedup']:.2f} | {r['speedup_persistent']:.2f} | {best:,.0f} |")
+    if by("zero_copy_concat"):
+        out += ["", "### Zero-copy concatenation", "",
+                "| workload | concats | elided | layout | sequential graph | multi-stream graph | persistent executor |",
+                "|---|---|---|---|---|---|---|"]
+        for r in by("zero_copy_concat"):
+            for tag in ("explicit", "zero_copy"):
+                t = r[tag]
+                out.append(f"| {r['workload']} | {r['concats']} | {r['elided']} | {tag} | {t['sequential_us']:.0f} | "
+                           f"{t['multi_stream_graph_us']:.0f} | {t['persistent_us']:.0f} |")
+    if by("stream_policy"):
+        out += ["", "### Stream policies and synchronisation pruning", "",
+                "| workload | ops | sequential | policy | streams | alloc us | syncs | after pruning | graph edges | graph us | pruned graph us |",
+                "|---|---|---|---|---|---|---|---|---|---|---|"]
+        for r in by("stream_policy"):
+            for name in ("alg1", "min_streams"):
+                q = r[name]
+                out.append(f"| {r['workload']} | {r['n_ops']} | {r['sequential_us']:.0f} | {name} | {q['n_streams']} | "
+                           f"{q['assign_ms'] * 1e3:.1f} | {q['syncs']} | {q['syncs_pruned']} | "
+                           f"{q['graph_edges']} -> {q['graph_pruned_edges']} | {q['graph_us']:.0f} | {q['graph_pruned_us']:.0f} |")
+    return "\n".join(out)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="0,1,2,3,4")
@@ -179,17 +228,25 @@ def main():
     ap.add_argument("--batches", default="1,2,4,8,16,32")
     ap.add_argument("--concat-configs", default="0,1,2")
     ap.add_argument("--stream-configs", default="0,1,2,3,4")
+    ap.add_argument("--markdown", action="store_true", help="after the JSON lines, print the same records as tables")
     a = ap.parse_args()
+    records = []
+
+    def emit(r):
+        records.append(r)
+        print(json.dumps(r), flush=True)
     for idx in [int(x) for x in a.stream_configs.split(",") if x]:
-        print(json.dumps(stream_policy_ablation(idx, a.replays)), flush=True)
+        emit(stream_policy_ablation(idx, a.replays))
     for idx in [int(x) for x in a.concat_configs.split(",") if x]:
-        print(json.dumps(concat_ablation(idx, a.replays)), flush=True)
+        emit(concat_ablation(idx, a.replays))
     for bsz in [int(x) for x in a.batches.split(",") if x]:
-        print(json.dumps(batch_sweep(bsz, max(50, a.replays // 3))), flush=True)
+        emit(batch_sweep(bsz, max(50, a.replays // 3)))
     for idx in [int(x) for x in a.configs.split(",") if x]:
-        print(json.dumps(order_ablation(idx, a.replays)), flush=True)
+        emit(order_ablation(idx, a.replays))
     for pair in (("comp", "mem"), ("mem", "mem"), ("comp", "comp")):
-        print(json.dumps(interference(*pair, max(50, a.replays // 3))), flush=True)
+        emit(interference(*pair, max(50, a.replays // 3)))
+    if a.markdown:
+        print(render_markdown(records))
 
 
 if __name__ == "__main__":
