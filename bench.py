@@ -23,11 +23,12 @@ sys.path.insert(0, ROOT)
 
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
-# a streaming kernel of known size (profiles/igemm_f16_direct4_hbm_traffic.md,
+# a streaming kernel of known size (profiles/googlenet_like_graph_kernels_hbm_traffic.md,
 # profiles/persist_f16_googlenet_like_hbm_traffic.md).
-MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): 1493 * 1024,
-                          ("googlenet_like", "persist_f16"): (61874 + 22603) * 1024,
-                          ("googlenet_like", "persist_f16+zero_copy_concat"): (59299 + 17733) * 1024}
+MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): (973 + 189) * 1024,
+                          ("googlenet_like", "igemm_f16_quad4"): (1109 + 76) * 1024,
+                          ("googlenet_like", "persist_f16"): (67684 + 38451) * 1024,
+                          ("googlenet_like", "persist_f16+zero_copy_concat"): (65112 + 33581) * 1024}
 
 
 def percentile(a, q):
