@@ -71,6 +71,8 @@ struct ConcatArgs {
   X(igemm_f16_direct8, IgemmArgs)       \
   X(igemm_f16_quad4, IgemmArgs)         \
   X(igemm_f16_quad8, IgemmArgs)         \
+  X(igemm_f16_quad64x4, IgemmArgs)      \
+  X(igemm_f16_quad64x8, IgemmArgs)      \
   X(igemm_f16_t64x64_scalar, IgemmArgs) \
   X(igemm_f32_t128x64, IgemmArgs)       \
   X(igemm_f32_t64x64, IgemmArgs)        \
@@ -78,6 +80,8 @@ struct ConcatArgs {
   X(igemm_f32_direct8, IgemmArgs)       \
   X(igemm_f32_quad4, IgemmArgs)         \
   X(igemm_f32_quad8, IgemmArgs)         \
+  X(igemm_f32_quad64x4, IgemmArgs)      \
+  X(igemm_f32_quad64x8, IgemmArgs)      \
   X(igemm_f32_t64x64_scalar, IgemmArgs) \
   X(gemv_f16, IgemmArgs)                \
   X(gemv_f32, IgemmArgs)                \
@@ -140,6 +144,8 @@ constexpr double kTiledMinFlopsPersistent = 2.0e9;   // inside the persistent ke
 constexpr int kTiledMinTiles = 80;               // ... and so do contractions with fewer 128x64 tiles
 constexpr IgemmTile kTile64{64, 64, 256};
 constexpr int64_t kQuadMinRowBytes = 1024;   // rows of K at least this long take the quad-coalesced variant
+constexpr int kQuad64MinTiles = 128;             // GEMM-shaped operands with at least this many 64 x 64 tiles take them
+constexpr double kQuad64MaxFlops = 4.0e10;       // ... up to this weight (measured up to 1.7e10)
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)

@@ -986,6 +986,131 @@ __device__ __forceinline__ void igemm_quad_body(const AR &a, const Blk &b, unsig
   }
 }
 
+// ---------------------------------------------------------------------------------
+// 64 x 64-tile form of the quad-coalesced contraction, for GEMM-shaped operands (no
+// im2col gather) with enough rows to fill such tiles: every wavefront of the workgroup
+// multiplies the whole tile over its share of K, so each 16-byte piece a lane loads feeds
+// four MFMAs instead of two and the loads and exchanges per multiply-add halve.  The
+// fragments of one step take 128 registers, the accumulators 64: one register set, no
+// prefetch across steps (two workgroups per CU overlap instead), row offsets recomputed
+// per load.  Partial tiles meet in LDS; each thread finishes four 4-channel pieces.
+// ---------------------------------------------------------------------------------
+template <typename T, int WAVES, int COH, typename AR>
+__device__ __forceinline__ void igemm_quad64_body(const AR &a, const Blk &b, unsigned char *lds) {
+  typedef typename Vec16<T>::type V;
+  typedef typename Vec16<T>::quad Q;
+  constexpr int VE = Vec16<T>::N;
+  constexpr int DS = 16 * VE;              // K elements per step
+  constexpr int PITCH = 68;                // floats per row of a partial tile in LDS
+  float (*part)[64][PITCH] = (float (*)[64][PITCH])lds;                                // [WAVES][64][PITCH]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int grp = lane >> 4, r16 = lane & 15, qd = (lane >> 2) & 3, pc = lane & 3;
+  const bool odd = (lane & 1) != 0, hi = (lane & 2) != 0;
+  int tile_x, tile_y;
+  xcd_tile(b, tile_x, tile_y);
+  const int m0 = tile_x * 64, n0 = tile_y * 64;
+  constexpr bool CA = (COH & kCohAct) != 0, CW = (COH & kCohW) != 0, CS = (COH & (kCohAct | kCohStore)) != 0;
+  const T *__restrict__ x = (const T *)a.x + (int64_t)b.z * a.a_bs;
+  const T *__restrict__ w = (const T *)a.w + (int64_t)b.z * a.b_bs;
+  T *__restrict__ y = (T *)a.y + (int64_t)b.z * a.y_bs;
+
+  const int nds = (a.K + DS - 1) / DS;
+  const int per_wave = (nds + WAVES - 1) / WAVES;
+  const int ds_begin = wave * per_wave;
+  const int ds_end = min(nds, ds_begin + per_wave);
+  const bool owns_tail = a.K % DS != 0 && ds_begin < nds && ds_end == nds;
+  const int main_end = owns_tail ? ds_end - 1 : ds_end;
+  const int kc = (grp * 4 + pc) * VE;      // this lane's 16-byte piece inside a step
+  const int lda = (int)a.lda, ldb = (int)a.ldb;
+  const int nq = n0 + qd * 4, mq = m0 + qd * 4;
+
+  floatx4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const V vzero = {};
+
+  struct Frag { V w[4][4], x[4][4]; };
+  // Register tt of block i holds row 16*i + 4*qd + tt (clamped into range; results of
+  // clamped rows are never stored), offsets in elements (below 2^31 by the host's choice).
+  auto step = [&](auto tail_tag, int ds) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int kb = ds * DS + kc;
+    const bool kok = !TAIL || kb < a.K;
+    Frag f;
+    if (kok) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) f.w[i][tt] = ldg<CW, V>(w + (min(nq + i * 16 + tt, a.N - 1) * ldb + kb));
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) f.x[j][tt] = ldg<CA, V>(x + (min(mq + j * 16 + tt, a.M - 1) * lda + kb));
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) { f.w[i][tt] = vzero; f.x[i][tt] = vzero; }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      quad_transpose(f.w[i], odd, hi);
+      quad_transpose(f.x[i], odd, hi);
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = mma16<T>(f.w[i][tt], f.x[j][tt], acc[i][j]);
+  };
+#pragma nounroll
+  for (int ds = ds_begin; ds < main_end; ++ds) step(std::false_type{}, ds);
+  if (owns_tail) step(std::true_type{}, main_end);
+
+  // ---- meet in LDS: lane holds channels n = i*16 + grp*4 + e of row m = j*16 + r16
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(floatx4 *)&part[wave][j * 16 + r16][i * 16 + grp * 4] = acc[i][j];
+  __syncthreads();
+  if (t < 256) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int idx = t + p * 256;
+      const int pm = idx >> 4, pn = (idx & 15) * 4;
+      const int m = m0 + pm, n = n0 + pn;
+      if (m >= a.M || n >= a.N) continue;
+      const bool full = n + 3 < a.N;
+      floatx4 sum = *(const floatx4 *)&part[0][pm][pn];
+#pragma unroll
+      for (int q = 1; q < WAVES; ++q) sum += *(const floatx4 *)&part[q][pm][pn];
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float r = sum[e] * a.alpha;
+        if (n + e < a.N) {
+          if (a.bias) r += a.bias[n + e];
+          for (int q = 0; q < a.n_extra; ++q) r += (float)ldg<CA, T>((const T *)a.extra[q] + (int64_t)m * a.N + n + e);
+        }
+        v[e] = a.relu ? fmaxf(r, 0.f) : r;
+      }
+      T *dst = y + (int64_t)m * a.ldy + n;
+      if (full && ((uintptr_t)dst & (4 * sizeof(T) - 1)) == 0) {
+        Q q4 = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+        stg<CS, Q>(dst, q4);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < a.N) stg<CS, T>(dst + e, (T)v[e]);
+      }
+    }
+  }
+}
+
 // Matrix-vector shaped GEMM (M <= kGemvMaxM rows): one wavefront per output column,
 // 16-byte loads along K, shuffle reduction.  Weight-bandwidth bound by construction.
 template <typename T, int COH, typename AR>
@@ -1294,6 +1419,7 @@ using namespace opara;
 constexpr int lds_igemm(int bn, int bm) { return 2 * (bn + bm) * 80; }
 constexpr int lds_pipe(int bn, int bm) { return 2 * (bn + bm) * 144; }
 constexpr int lds_direct(int waves) { return waves * 32 * 36 * 4; }
+constexpr int lds_quad64(int waves) { return waves * 64 * 68 * 4; }
 constexpr int kLdsGap = 4 * 64 * 4, kLdsRow = 16, kLdsNone = 0;
 
 #define KDEF(name, threads, ldsb, Args, call)                                            \
@@ -1316,6 +1442,8 @@ KDEF(igemm_f16_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<half_t
 KDEF(igemm_f16_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<half_t, 8, 2, 0>(a, b, lds)))
 KDEF(igemm_f16_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<half_t, 4, 0>(a, b, lds)))
 KDEF(igemm_f16_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<half_t, 8, 0>(a, b, lds)))
+KDEF2(igemm_f16_quad64x4, 256, 2, lds_quad64(4), IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
+KDEF(igemm_f16_quad64x8, 512, lds_quad64(8), IgemmArgs, (igemm_quad64_body<half_t, 8, 0>(a, b, lds)))
 KDEF(igemm_f16_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF2(igemm_f32_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
@@ -1323,6 +1451,8 @@ KDEF(igemm_f32_direct4, 256, lds_direct(4), IgemmArgs, (igemm_direct_body<float,
 KDEF(igemm_f32_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<float, 8, 2, 0>(a, b, lds)))
 KDEF(igemm_f32_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<float, 4, 0>(a, b, lds)))
 KDEF(igemm_f32_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<float, 8, 0>(a, b, lds)))
+KDEF2(igemm_f32_quad64x4, 256, 2, lds_quad64(4), IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
+KDEF(igemm_f32_quad64x8, 512, lds_quad64(8), IgemmArgs, (igemm_quad64_body<float, 8, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF(gemv_f16, 256, kLdsNone, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
 KDEF(gemv_f32, 256, kLdsNone, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
@@ -1737,6 +1867,8 @@ int persist_kernel_id(int id) {
     // latency-oriented contraction runs the four-wavefront fragment-loading body.
     case K_igemm_f16_direct8: case K_igemm_f16_quad4: case K_igemm_f16_quad8: return K_igemm_f16_direct4;
     case K_igemm_f32_direct8: case K_igemm_f32_quad4: case K_igemm_f32_quad8: return K_igemm_f32_direct4;
+    case K_igemm_f16_quad64x4: case K_igemm_f16_quad64x8: case K_igemm_f32_quad64x4: case K_igemm_f32_quad64x8:
+      return -1;                          // never in a persistent plan
     default: return (id >= 0 && id < K_COUNT) ? id : -1;
   }
 }

@@ -16,12 +16,20 @@ const KernelResource kKernelResources[K_COUNT] = {
 
 namespace {
 
-// Tuning knob (read once): OPARA_TILED_MIN_FLOPS moves the hand-over point between the
+// Tuning knobs (read once): OPARA_QUAD_MIN_ROW_BYTES, OPARA_QUAD64_MIN_TILES; OPARA_TILED_MIN_FLOPS moves the hand-over point between the
 // latency-oriented and the tiled contraction kernel.
 int64_t quad_min_row_bytes() {
   static const int64_t v = [] {
     const char *e = std::getenv("OPARA_QUAD_MIN_ROW_BYTES");
     return e ? (int64_t)std::atoll(e) : kQuadMinRowBytes;
+  }();
+  return v;
+}
+
+int quad64_min_tiles() {
+  static const int v = [] {
+    const char *e = std::getenv("OPARA_QUAD64_MIN_TILES");
+    return e ? std::atoi(e) : kQuad64MinTiles;
   }();
   return v;
 }
@@ -128,6 +136,22 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, 
     const int64_t lim32 = (int64_t)1 << 31;
     const bool fits32 = (int64_t)a.M * a.lda < lim32 && (int64_t)a.N * a.ldb < lim32 &&
                         (!a.gather || (int64_t)(a.M / a.HoWo) * a.img_stride < lim32);
+    const bool quad64 = !persistent && !a.b_kmajor && !a.gather && fits32 && flops < kQuad64MaxFlops &&
+                        (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * batch >= quad64_min_tiles() &&
+                        (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
+    if (quad64) {
+      // GEMM-shaped and at least one 64 x 64 tile per compute unit: the quad-coalesced
+      // kernel whose wavefronts each multiply a whole tile over their share of K.
+      const int waves = cdiv(a.K, 16 * ve) <= 16 ? 4 : 8;
+      out->kernel = f16 ? (waves == 4 ? K_igemm_f16_quad64x4 : K_igemm_f16_quad64x8)
+                        : (waves == 4 ? K_igemm_f32_quad64x4 : K_igemm_f32_quad64x8);
+      out->gx = cdiv(a.M, 64);
+      out->gy = cdiv(a.N, 64);
+      out->gz = (uint32_t)batch;
+      out->block = waves * 64;
+      out->args.igemm = a;
+      return OPARA_OK;
+    }
     if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= (persistent ? kTiledMinFlopsPersistent : tiled_min_flops())) {
       // Throughput-oriented tiled kernel (128 output columns x 64 rows per workgroup):
       // pays once the contraction is heavy and has enough tiles to occupy the device.

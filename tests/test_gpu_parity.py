@@ -71,6 +71,7 @@ def test_conv(case, dtype):
 
 GEMM_CASES = [(1, 64, 40), (3, 200, 17), (5, 96, 64), (37, 72, 50), (64, 256, 64), (130, 136, 200),
               (37, 520, 50), (5, 1032, 33), (70, 4104, 96), (130, 8200, 40),      # quad-coalesced kernels, K tails
+              (256, 520, 2000), (456, 2056, 1100),                                 # ... their 64 x 64-tile form, ragged
               (128, 768, 768), (512, 320, 1024), (33, 7, 9), (1, 1024, 1000),
               (256, 2048, 1024), (512, 4096, 512), (200, 1544, 2048), (384, 512, 4096), (1100, 264, 2000)]
 
@@ -150,13 +151,16 @@ def test_deep_contractions_take_the_quad_coalesced_kernels():
         x = b.ext((72, 9, 9)); b.conv(x, 35, 3, stride=2, pad=1)
         g = b.ext((70, 4104)); b.gemm(g, 70, 4104, 96)
         h = b.ext((64, 64)); b.gemm(h, 64, 64, 64)
+        q = b.ext((256, 2048)); b.gemm(q, 256, 2048, 2048)
         s = Session(b.build(1))
         try:
             names = [B.opara_kernel_info(d.kernel_id)[0] for d in B.opara_get_demands(s.dag)]
         finally:
             s.close()
         first = "quad4" if dtype == "f16" else "quad8"       # K = 648: six or eleven 256-byte steps
-        assert names == [f"igemm_{dtype}_{first}", f"igemm_{dtype}_quad8", f"igemm_{dtype}_direct4"], names
+        last = "quad64x4" if dtype == "f16" else "quad64x8"  # 128 tiles of 64 x 64; K = 2048: 16 or 32 steps
+        assert names == [f"igemm_{dtype}_{first}", f"igemm_{dtype}_quad8", f"igemm_{dtype}_direct4",
+                         f"igemm_{dtype}_{last}"], names
 
 
 def test_inception_block_fp32_all_modes():
