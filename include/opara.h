@@ -290,12 +290,15 @@ int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violati
  * to a few hundred operators); a smaller positive count is honoured, a larger one is cut
  * to that maximum, because every workgroup must be resident.  Items follow a topological
  * order, so the holder of the lowest unfinished item can always run.
- * Operators planned on 8- or 16-wavefront contraction kernels run the 4-wavefront form
- * (same tiles, longer K walk per wavefront): results may differ from the other modes in
- * the last bits, and are identical from replay to replay.
+ * The executor has its own kernel plan (opara_persistent_plan: one workgroup size, so
+ * the 8-wavefront and quad-coalesced contractions run the 4-wavefront fragment-loading
+ * form), and the serial prefix of the queue runs as ordinary kernel nodes ahead of the
+ * persistent kernel (opara_persistent_prefix): results may differ from the other modes
+ * in the last bits, and are identical from replay to replay.
  * Every wait inside the kernel is bounded (spin_limit polls, default 2^22); a wait that
- * runs out makes all workgroups leave and sets a sticky error word (1 + queue position
- * of the waiting operator), which opara_persistent_status reads after synchronising
+ * runs out makes all workgroups leave and sets a sticky error word (1 + queue position,
+ * counted from the first operator inside the kernel, of an operator whose wait ran out;
+ * it stays non-zero until reset), which opara_persistent_status reads after synchronising
  * `hip_stream`.  opara_persistent_reset synchronises the stream, clears counters, flags
  * and error word and sets the spin limit (0 = default).  Replays of one executor must not
  * overlap (same stream, or ordered by the caller).  Several persistent executors, or one
@@ -322,6 +325,24 @@ int opara_persistent_info(const opara_exec *e, int32_t *n_items, int32_t *n_work
  * operator has one per executor kind).  No HIP call.
  */
 int opara_persistent_plan(const opara_dag *g, int32_t *tiles, int32_t *kernel_ids);
+/*
+ * Number of leading launch-queue operators that the executor launches as ordinary kernel
+ * nodes ahead of the persistent kernel, in one chain inside the same hipGraph: those that
+ * nothing else can run beside (every other operator depends on each of them, a network's
+ * stem; the paper's Fig. 1 DAGs start with such a chain).  They run the graph executors'
+ * kernels.  Work items, and the queue positions in the timeline, start at the first
+ * operator after them.  (Setting OPARA_PERSIST_SERIAL_PREFIX=0 in the environment at
+ * capture keeps every operator inside the persistent kernel, for comparison.)
+ */
+int opara_persistent_prefix(const opara_exec *e, int32_t *n_prefix);
+/*
+ * Measurement aid: launches the persistent kernel alone (an ordinary launch with the
+ * executor's arguments, without the kernel nodes of the serial prefix, whose outputs a
+ * previous replay has left in place) `launches` times on `hip_stream`, each between two
+ * HIP events on that stream, and returns the mean event-to-event time in microseconds
+ * (host float).  Synchronises the stream.  At least one replay must have completed.
+ */
+int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int32_t launches, float *avg_us);
 /*
  * Timeline of the following replays (tracing; the one kernel hides the operators from
  * a profiler).  trace: device memory, caller-owned, 8-byte aligned, 32 bytes per work

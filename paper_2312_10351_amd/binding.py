@@ -66,7 +66,8 @@ EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_assign_streams_poli
            "opara_order_launch_policy", "opara_sync_edges", "opara_sync_edges_pruned",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
-           "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_set_trace",
+           "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
+           "opara_persistent_set_trace",
            "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
@@ -103,6 +104,8 @@ def load():
     lib.opara_persistent_reset.argtypes = [vp, vp, C.c_uint32]
     lib.opara_persistent_info.argtypes = [vp, i32p, i32p]
     lib.opara_persistent_plan.argtypes = [vp, i32p, i32p]
+    lib.opara_persistent_prefix.argtypes = [vp, i32p]
+    lib.opara_persistent_time_kernel.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_float)]
     lib.opara_persistent_set_trace.argtypes = [vp, vp, vp, C.c_uint64]
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
@@ -234,6 +237,20 @@ def opara_persistent_info(exe):
     a, b = C.c_int32(), C.c_int32()
     _check(load().opara_persistent_info(exe, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def opara_persistent_prefix(exe):
+    """Leading queue operators launched as ordinary kernels ahead of the persistent kernel."""
+    a = C.c_int32()
+    _check(load().opara_persistent_prefix(exe, C.byref(a)))
+    return a.value
+
+
+def opara_persistent_time_kernel(exe, stream_handle, launches):
+    """Mean duration (us) of the persistent kernel launched alone, between HIP events on the stream."""
+    a = C.c_float()
+    _check(load().opara_persistent_time_kernel(exe, C.c_void_p(stream_handle), launches, C.byref(a)))
+    return a.value
 
 
 def opara_persistent_plan(dag):

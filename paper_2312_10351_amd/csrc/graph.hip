@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <new>
+#include <cstdlib>
 #include <vector>
 #include "launch.h"
 #include "opara_internal.h"
@@ -16,7 +17,10 @@ struct opara_exec {
   int32_t n_nodes = 0, n_edges = 0;
   // persistent executor only: caller-owned workspace and the size of its counter block
   void *workspace = nullptr;
-  int32_t persist_ops = 0, persist_items = 0, persist_workgroups = 0;
+  int32_t persist_ops = 0, persist_items = 0, persist_workgroups = 0, persist_prefix = 0;
+  opara::PersistArgs persist_args{};   // the persistent kernel's launch: arguments, element type, LDS
+  bool persist_f16 = false;
+  uint32_t persist_lds = 0;
 };
 
 using namespace opara;
@@ -270,6 +274,37 @@ PersistLayout persist_layout(int32_t n) {
   return l;
 }
 
+// Number of leading launch-queue operators that nothing else can run beside: every other
+// operator is a descendant of each of them (a network's stem).  They gain nothing from the
+// persistent kernel's flags and lose its one-tile-shape restriction, so they are launched
+// as ordinary kernel nodes ahead of it.  At least one operator is left for the kernel.
+int32_t serial_prefix(const opara_dag *g) {
+  const char *e = std::getenv("OPARA_PERSIST_SERIAL_PREFIX");
+  if (e && std::atoi(e) == 0) return 0;
+  const int32_t n = g->n;
+  std::vector<char> seen((size_t)n);
+  std::vector<int32_t> stack;
+  int32_t prefix = 0;
+  for (int32_t i = 0; i + 1 < n; ++i) {
+    const int32_t v = g->order[i];
+    std::fill(seen.begin(), seen.end(), 0);
+    stack.assign(1, v);
+    seen[v] = 1;
+    int32_t reached = 0;
+    while (!stack.empty()) {
+      const int32_t u = stack.back(); stack.pop_back();
+      for (int32_t j = g->succ_off[u]; j < g->succ_off[u + 1]; ++j) {
+        const int32_t w = g->succ[j];
+        if (!seen[w]) { seen[w] = 1; ++reached; stack.push_back(w); }
+      }
+    }
+    // The earlier prefix operators are ancestors of v by the same test; the rest must be below it.
+    if (reached != n - 1 - i) break;
+    prefix = i + 1;
+  }
+  return prefix;
+}
+
 }  // namespace
 
 extern "C" int opara_persistent_workspace_bytes(const opara_dag *g, uint64_t *bytes) {
@@ -290,14 +325,16 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
               (unsigned long long)workspace_bytes, (unsigned long long)lay.bytes);
     return OPARA_EINVAL;
   }
-  const uint32_t lds_bytes = persist_lds_bytes((uint32_t)n);
+  const int32_t prefix = serial_prefix(g);                      // run as ordinary kernel nodes
+  const int32_t np_ops = n - prefix;                            // operators inside the persistent kernel
+  const uint32_t lds_bytes = persist_lds_bytes((uint32_t)np_ops);
   if (lds_bytes > kPersistMaxLds || n > 65535) {
     set_error("opara_capture_persistent: %d operators exceed the ticket table held in workgroup memory", n);
     return OPARA_EUNSUPPORTED;
   }
   // Workgroups the device holds at once: the launch size, and the tiles per work item of
   // operators that have more tiles than that.
-  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan_persist[g->order[0]].kernel));
+  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan_persist[g->order[prefix]].kernel));
   uint32_t wgs = 0;
   {
     hipError_t err = persist_max_workgroups(f16, lds_bytes, &wgs);
@@ -320,8 +357,10 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
   std::vector<int32_t> pos_of(n, -1);
   std::vector<uint32_t> tiles(n, 0);
   int64_t total = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    const int32_t v = g->order[i];
+  std::vector<char> in_prefix((size_t)n, 0);                    // complete before the kernel starts
+  for (int32_t q = 0; q < prefix; ++q) in_prefix[g->order[q]] = 1;
+  for (int32_t i = 0; i < np_ops; ++i) {
+    const int32_t v = g->order[prefix + i];
     const KernelPlan &p = g->plan_persist[v];
     const int kid = persist_kernel_id(p.kernel);
     if (kid < 0) { set_error("opara_capture_persistent: operator %d has no persistent kernel", v); return OPARA_EUNSUPPORTED; }
@@ -339,16 +378,18 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     rec[i].args = p.args;
     const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
     if (np > kPersistMaxPreds) { set_error("opara_capture_persistent: operator %d has %d predecessors (limit %d)", v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
-    preds[i].n = (uint16_t)np;
+    int32_t kept = 0;
+    for (int32_t j = 0; j < np; ++j) {
+      const int32_t pu = g->pred[g->pred_off[v] + j];
+      const int32_t u = pos_of[pu];
+      if (u >= 0) { preds[i].pos[kept++] = (uint16_t)u; continue; }
+      if (!in_prefix[pu]) { set_error("opara_capture_persistent: launch queue is not topological"); return OPARA_ESTATE; }
+    }
+    preds[i].n = (uint16_t)kept;
     preds[i].tiles = (uint16_t)t;
     preds[i].chunk = (uint16_t)chunk;
-    for (int32_t j = 0; j < np; ++j) {
-      const int32_t u = pos_of[g->pred[g->pred_off[v] + j]];
-      if (u < 0) { set_error("opara_capture_persistent: launch queue is not topological"); return OPARA_ESTATE; }
-      preds[i].pos[j] = (uint16_t)u;
-    }
   }
-  begin[n] = (int32_t)total;
+  begin[np_ops] = (int32_t)total;
   opara_exec *e = new (std::nothrow) opara_exec();
   if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
   {
@@ -363,15 +404,23 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
     pa.item_begin = (const int32_t *)(ws + lay.begin);
     pa.preds = (const PersistPredsLds *)(ws + lay.preds);
     pa.rec = (const PersistOp *)(ws + lay.rec);
-    pa.n = n;
+    pa.n = np_ops;
     pa.total = (int32_t)total;
-    hipGraphNode_t node = nullptr;
+    hipGraphNode_t node = nullptr, last = nullptr;
     HIP_TRY(hipGraphCreate(&e->graph, 0));
-    HIP_TRY(add_persist_node(e->graph, f16, pa, wgs, lds_bytes, &node));
+    for (int32_t q = 0; q < prefix; ++q) {                      // the serial prefix: a chain of ordinary launches
+      HIP_TRY(add_plan_node(e->graph, g->plan[g->order[q]], last ? &last : nullptr, last ? 1 : 0, &node));
+      last = node;
+    }
+    HIP_TRY(add_persist_node(e->graph, f16, pa, wgs, lds_bytes, last ? &last : nullptr, last ? 1 : 0, &node));
     HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
-    e->n_nodes = 1;
-    e->n_edges = 0;
+    e->n_nodes = prefix + 1;
+    e->n_edges = prefix;
     e->workspace = workspace;
+    e->persist_prefix = prefix;
+    e->persist_args = pa;
+    e->persist_f16 = f16;
+    e->persist_lds = lds_bytes;
     e->persist_ops = n;
     e->persist_items = (int32_t)total;
     e->persist_workgroups = (int32_t)wgs;
@@ -402,6 +451,40 @@ extern "C" int opara_persistent_info(const opara_exec *e, int32_t *n_items, int3
   if (n_items) *n_items = e->persist_items;
   if (n_workgroups) *n_workgroups = e->persist_workgroups;
   return OPARA_OK;
+}
+
+extern "C" int opara_persistent_prefix(const opara_exec *e, int32_t *n_prefix) {
+  if (!e || !e->workspace || !n_prefix) { set_error("opara_persistent_prefix: not a persistent executor"); return OPARA_EINVAL; }
+  *n_prefix = e->persist_prefix;
+  return OPARA_OK;
+}
+
+extern "C" int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int32_t launches, float *avg_us) {
+  if (!e || !e->workspace || !avg_us || launches < 1) { set_error("opara_persistent_time_kernel: bad argument"); return OPARA_EINVAL; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  double sum_ms = 0.0;
+  HIP_TRY(hipEventCreate(&t0));
+  HIP_TRY(hipEventCreate(&t1));
+  HIP_TRY(hipStreamSynchronize(st));
+  for (int32_t i = 0; i < launches; ++i) {
+    float ms = 0.f;
+    HIP_TRY(hipEventRecord(t0, st));
+    HIP_TRY(launch_persist(e->persist_f16, e->persist_args, (uint32_t)e->persist_workgroups, e->persist_lds, st));
+    HIP_TRY(hipEventRecord(t1, st));
+    HIP_TRY(hipEventSynchronize(t1));
+    HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
+    sum_ms += ms;
+  }
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  *avg_us = (float)(sum_ms * 1e3 / launches);
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  return OPARA_EHIP;
 }
 
 extern "C" int opara_persistent_set_trace(opara_exec *e, void *hip_stream, void *trace, uint64_t trace_bytes) {

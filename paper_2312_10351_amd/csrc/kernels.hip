@@ -1899,7 +1899,7 @@ hipError_t persist_max_workgroups(bool f16, uint32_t lds_bytes, uint32_t *n_work
 }
 
 hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, uint32_t n_workgroups,
-                            uint32_t lds_bytes, hipGraphNode_t *node) {
+                            uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
   PersistArgs args = a;
   void *kparams[1] = {&args};
   hipKernelNodeParams np = {};
@@ -1908,7 +1908,13 @@ hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, ui
   np.blockDim = dim3(256);
   np.sharedMemBytes = lds_bytes;
   np.kernelParams = kparams;
-  return hipGraphAddKernelNode(node, graph, nullptr, 0, &np);
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups, uint32_t lds_bytes, hipStream_t s) {
+  if (f16) hipLaunchKernelGGL(opara_k_persist_f16, dim3(n_workgroups), dim3(256), lds_bytes, s, a);
+  else hipLaunchKernelGGL(opara_k_persist_f32, dim3(n_workgroups), dim3(256), lds_bytes, s, a);
+  return hipGetLastError();
 }
 
 hipError_t verify_reset(hipStream_t s) {

@@ -76,7 +76,9 @@ bool kernel_is_f16(int kernel_id);
 // Workgroups of the persistent kernel the device holds at once (all must be resident).
 hipError_t persist_max_workgroups(bool f16, uint32_t lds_bytes, uint32_t *n_workgroups);
 hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, uint32_t n_workgroups,
-                            uint32_t lds_bytes, hipGraphNode_t *node);
+                            uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
+// The same kernel as an ordinary launch on `s` (for timing it apart from the graph it belongs to).
+hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups, uint32_t lds_bytes, hipStream_t s);
 
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter

@@ -295,7 +295,8 @@ class Session:
     def persistent_trace(self, exe):
         """Replay once with the in-kernel timeline on.  Returns an int64 array [tiles, 5]:
         lookup start, predecessors complete, body end (ns since the first event), queue
-        position, workgroup."""
+        position, workgroup.  Operators of the serial prefix (ordinary kernels ahead of the
+        persistent one) have no rows."""
         import torch
         items, _ = B.opara_persistent_info(exe)
         buf = torch.zeros(items * 4, dtype=torch.int64, device=self.device)
@@ -308,7 +309,9 @@ class Session:
         raw = raw[raw[:, 2] != 0]                 # items that only pad an operator's range record nothing
         t = raw[:, :3] * 10                       # 100 MHz ticks -> ns
         t = t - t.min()
-        return np.concatenate([t, (raw[:, 3:4] >> 32), (raw[:, 3:4] & 0xffffffff)], axis=1)
+        # the kernel counts queue positions from the first operator it runs itself
+        pos = (raw[:, 3:4] >> 32) + B.opara_persistent_prefix(exe)
+        return np.concatenate([t, pos, (raw[:, 3:4] & 0xffffffff)], axis=1)
 
     def persistent_status(self, exe):
         return B.opara_persistent_status(exe, self.make_streams(1).handles[0])

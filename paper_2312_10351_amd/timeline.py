@@ -20,9 +20,15 @@ def operator_timeline(session, exe, order):
     tr = session.persistent_trace(exe)
     tiles, kernels = B.opara_persistent_plan(session.dag)
     rows = []
+    prefix = B.opara_persistent_prefix(exe)
     for pos, v in enumerate(order):
         m = tr[:, 3] == pos
         op = session.wl.ops[session.lib_ops[v]]
+        if pos < prefix:                   # an ordinary kernel node ahead of the persistent kernel: no stamps
+            rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel="(kernel node)", tiles=0, items=0,
+                             first_ready_us=float("nan"), last_published_us=float("nan"),
+                             median_tile_us=float("nan"), median_wait_us=float("nan")))
+            continue
         rows.append(dict(pos=pos, op=v, name=op.name or op.type, kernel=B.opara_kernel_info(kernels[v])[0],
                          tiles=int(tiles[v]), items=int(m.sum()), first_ready_us=float(tr[m, 1].min()) / 1e3,
                          last_published_us=float(tr[m, 2].max()) / 1e3,

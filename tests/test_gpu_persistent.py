@@ -63,12 +63,15 @@ def test_replays_are_identical_and_rewrite_every_output():
         s.make_streams(1).torch_streams[0].synchronize()
         assert s.persistent_status(exe) == 0
         assert all(torch.equal(a, t.view(torch.int16)) for a, t in zip(bits[0], s.out_dev))
-        assert B.opara_exec_info(exe) == (1, 0)
+        prefix = B.opara_persistent_prefix(exe)               # ordinary kernel nodes in a chain, then the one kernel
+        assert B.opara_exec_info(exe) == (prefix + 1, prefix)
         items, wgs = B.opara_persistent_info(exe)
         tiles, _ = B.opara_persistent_plan(s.dag)
         # an operator with more tiles than workgroups runs ceil(tiles / workgroups) tiles per item;
         # every operator's item range is padded to the XCD count
-        per_op = [-(-t // -(-t // wgs)) for t in tiles]
+        order = B.opara_order_launch_policy(s.dag, B.ORDER_ALG2)
+        inside = order[B.opara_persistent_prefix(exe):]      # the serial prefix runs as ordinary kernel nodes
+        per_op = [-(-tiles[v] // -(-tiles[v] // wgs)) for v in inside]
         assert items == sum((i + 7) // 8 * 8 for i in per_op) and 1 <= wgs <= items
     finally:
         s.close()
@@ -105,8 +108,8 @@ def test_bounded_wait_reports_and_recovers():
         s.replay(exe)
         word = s.persistent_status(exe)
         assert 1 <= word <= len(wl.ops)
-        s.replay(exe)                                  # sticky: later launches leave at once
-        assert s.persistent_status(exe) == word
+        s.replay(exe)                                  # sticky: the word stays set (any wait that ran out may name itself)
+        assert 1 <= s.persistent_status(exe) <= len(wl.ops)
         s.persistent_reset(exe)
         for t in s.out_dev:
             t.fill_(float("nan"))
@@ -135,15 +138,65 @@ def test_timeline_is_consistent_with_the_dag():
         _, wgs = B.opara_persistent_info(exe)
         assert np.all(tr[:, 0] <= tr[:, 1]) and np.all(tr[:, 1] <= tr[:, 2])
         first_ready, last_start, last_end = {}, {}, {}
-        for p in range(len(order)):
+        prefix = B.opara_persistent_prefix(exe)
+        assert not np.any(tr[:, 3] < prefix)
+        for p in range(prefix, len(order)):
             m = tr[:, 3] == p
             tiles = plan_tiles[order[p]]
             assert m.sum() == -(-tiles // -(-tiles // wgs))            # items = ceil(tiles / chunk)
             first_ready[p], last_start[p], last_end[p] = tr[m, 1].min(), tr[m, 1].max(), tr[m, 2].max()
         stamp_delay_ns = 3000
         for u, v in wl.edges():
+            if pos_of[u] < prefix:         # a kernel node ahead of the persistent kernel: complete before it starts
+                continue
             assert first_ready[pos_of[v]] >= last_start[pos_of[u]]
             assert first_ready[pos_of[v]] + stamp_delay_ns >= last_end[pos_of[u]]
+    finally:
+        s.close()
+
+
+def test_serial_prefix_runs_as_kernel_nodes(monkeypatch):
+    """The stem of a network (operators every other operator depends on) is launched as ordinary kernel nodes
+    ahead of the persistent kernel; DAGs that start with a fork have no such prefix; the switch keeps everything
+    inside the kernel.  Results hold either way."""
+    expect = {"googlenet_like": 5, "inception_block": 0, "bert_base_like": 0}
+    for make in (lambda: googlenet_like(he_init=True), inception_block, lambda: bert_base_like(layers=2)):
+        wl = make()
+        ref = executor.run_dag(wl)
+        for switch in ("1", "0"):
+            monkeypatch.setenv("OPARA_PERSIST_SERIAL_PREFIX", switch)
+            s = Session(wl)
+            try:
+                exe = s.capture_persistent()
+                prefix = B.opara_persistent_prefix(exe)
+                assert prefix == (expect[wl.name] if switch == "1" else 0), (wl.name, switch, prefix)
+                assert B.opara_exec_info(exe) == (prefix + 1, prefix)
+                for t in s.out_dev:
+                    t.fill_(float("nan"))
+                torch.cuda.synchronize()
+                s.replay(exe)
+                assert s.persistent_status(exe) == 0
+                assert not compare_all(s, ref, outlier_frac=1e-3)
+            finally:
+                s.close()
+
+
+def test_kernel_alone_can_be_timed():
+    """The measurement aid launches the persistent kernel by itself: plausible time, no error, same outputs."""
+    wl = googlenet_like(he_init=True)
+    s = Session(wl)
+    try:
+        exe = s.capture_persistent()
+        s.replay(exe)
+        before = [t.clone() for t in s.out_dev]
+        h = s.make_streams(1).handles[0]
+        us = B.opara_persistent_time_kernel(exe, h, 5)
+        assert 20.0 < us < 5000.0
+        assert s.persistent_status(exe) == 0
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(before, s.out_dev))
+        s.replay(exe)                                       # the graph still replays after the ordinary launches
+        assert s.persistent_status(exe) == 0
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(before, s.out_dev))
     finally:
         s.close()
 
