@@ -25,10 +25,10 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
 # a streaming kernel of known size (profiles/googlenet_like_graph_kernels_hbm_traffic.md,
 # profiles/persist_f16_googlenet_like_hbm_traffic.md).
-MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): (973 + 189) * 1024,
-                          ("googlenet_like", "igemm_f16_quad4"): (1109 + 76) * 1024,
-                          ("googlenet_like", "persist_f16"): (67684 + 38451) * 1024,
-                          ("googlenet_like", "persist_f16+zero_copy_concat"): (65112 + 33581) * 1024}
+MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): (1054 + 345) * 1024,
+                          ("googlenet_like", "igemm_f16_quad4"): (1220 + 136) * 1024,
+                          ("googlenet_like", "persist_f16"): (52811 + 33904) * 1024,
+                          ("googlenet_like", "persist_f16+zero_copy_concat"): (50225 + 29035) * 1024}
 
 
 def percentile(a, q):

@@ -338,9 +338,10 @@ int opara_persistent_prefix(const opara_exec *e, int32_t *n_prefix);
 /*
  * Measurement aid: launches the persistent kernel alone (an ordinary launch with the
  * executor's arguments, without the kernel nodes of the serial prefix, whose outputs a
- * previous replay has left in place) `launches` times on `hip_stream`, each between two
- * HIP events on that stream, and returns the mean event-to-event time in microseconds
- * (host float).  Synchronises the stream.  At least one replay must have completed.
+ * previous replay has left in place) `launches` times back to back on `hip_stream`,
+ * between two HIP events on that stream, and returns the elapsed time per launch in
+ * microseconds (host float).  Synchronises the stream.  At least one replay must have
+ * completed.
  */
 int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int32_t launches, float *avg_us);
 /*

@@ -463,22 +463,19 @@ extern "C" int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int
   if (!e || !e->workspace || !avg_us || launches < 1) { set_error("opara_persistent_time_kernel: bad argument"); return OPARA_EINVAL; }
   hipStream_t st = (hipStream_t)hip_stream;
   hipEvent_t t0 = nullptr, t1 = nullptr;
-  double sum_ms = 0.0;
+  float ms = 0.f;
   HIP_TRY(hipEventCreate(&t0));
   HIP_TRY(hipEventCreate(&t1));
   HIP_TRY(hipStreamSynchronize(st));
-  for (int32_t i = 0; i < launches; ++i) {
-    float ms = 0.f;
-    HIP_TRY(hipEventRecord(t0, st));
+  HIP_TRY(hipEventRecord(t0, st));
+  for (int32_t i = 0; i < launches; ++i)
     HIP_TRY(launch_persist(e->persist_f16, e->persist_args, (uint32_t)e->persist_workgroups, e->persist_lds, st));
-    HIP_TRY(hipEventRecord(t1, st));
-    HIP_TRY(hipEventSynchronize(t1));
-    HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
-    sum_ms += ms;
-  }
+  HIP_TRY(hipEventRecord(t1, st));
+  HIP_TRY(hipEventSynchronize(t1));
+  HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
   (void)hipEventDestroy(t0);
   (void)hipEventDestroy(t1);
-  *avg_us = (float)(sum_ms * 1e3 / launches);
+  *avg_us = ms * 1e3f / (float)launches;
   return OPARA_OK;
 fail:
   (void)hipGetLastError();

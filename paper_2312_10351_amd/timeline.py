@@ -59,6 +59,9 @@ def main():
         print("| pos | op | name | kernel | tiles | first ready us | last published us | median tile us | median wait us |")
         print("|---|---|---|---|---|---|---|---|---|")
         for r in rows[:a.rows]:
+            if r["items"] == 0:
+                print(f"| {r['pos']} | {r['op']} | {r['name']} | {r['kernel']} | - | - | - | - | - |")
+                continue
             print(f"| {r['pos']} | {r['op']} | {r['name']} | {r['kernel']} | {r['tiles']} | {r['first_ready_us']:.1f} | "
                   f"{r['last_published_us']:.1f} | {r['median_tile_us']:.2f} | {r['median_wait_us']:.2f} |")
         print()
