@@ -170,6 +170,9 @@ def bench_config(index, steps, warmup, with_kernels, zero_copy_concat=False):
                    persistent_queue_probe_us={B.ORDER_POLICY_NAMES[k]: v for k, v in probe.items()},
                    parallel=r_par, sequential=r_seq, persistent=r_per,
                    persistent_timeline=timeline_summary(s, per), best_mode=best, best=r_best,
+                   # what runtime.Session.capture_best() would hand out: the sequential graph is a candidate too
+                   fastest_executor=min((("sequential_graph", r_seq), ("multi_stream_graph", r_par), ("persistent", r_per)),
+                                        key=lambda kv: kv[1]["median_us"])[0],
                    speedup_vs_sequential=r_seq["median_us"] / r_best["median_us"],
                    speedup_multi_stream_graph=r_seq["median_us"] / r_par["median_us"],
                    speedup_persistent=r_seq["median_us"] / r_per["median_us"],

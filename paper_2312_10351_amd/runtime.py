@@ -292,6 +292,38 @@ class Session:
         self.execs.append(exe)
         return exe
 
+    def capture_best(self, probe_replays=30):
+        """Capture the sequential graph, the multi-stream graph and the persistent executor
+        (under the Alg. 2 and the wave-by-wave work-item order), time `probe_replays` replays of
+        each and return (executor, name, {name: median microseconds}).  Which one wins depends
+        on the DAG: operator parallelism pays only where branch work exceeds what a
+        synchronisation costs on this runtime (paper Eq. 3), so chains of large operators are
+        best left to the sequential graph."""
+        import time
+        h = self.make_streams(1)
+        handle, ts = h.handles[0], h.torch_streams[0]
+        cands = {"sequential_graph": lambda: self.capture(B.SEQUENTIAL),
+                 "multi_stream_graph": lambda: self.capture(B.PARALLEL),
+                 "persistent_alg2": lambda: self.capture_persistent(policy=B.ORDER_ALG2),
+                 "persistent_level": lambda: self.capture_persistent(policy=B.ORDER_LEVEL)}
+        exes, med = {}, {}
+        for name, make in cands.items():
+            exe = exes[name] = make()
+            for _ in range(5):
+                B.opara_replay(exe, handle)
+            ts.synchronize()
+            lat = []
+            for _ in range(probe_replays):
+                t0 = time.perf_counter()
+                B.opara_replay(exe, handle)
+                ts.synchronize()
+                lat.append((time.perf_counter() - t0) * 1e6)
+            med[name] = float(np.median(lat))
+            if name.startswith("persistent") and self.persistent_status(exe) != 0:
+                med[name] = float("inf")           # a wait ran out: not a candidate
+        best = min(med, key=med.get)
+        return exes[best], best, med
+
     def persistent_trace(self, exe):
         """Replay once with the in-kernel timeline on.  Returns an int64 array [tiles, 5]:
         lookup start, predecessors complete, body end (ns since the first event), queue

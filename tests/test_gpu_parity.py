@@ -163,6 +163,22 @@ def test_deep_contractions_take_the_quad_coalesced_kernels():
                          f"igemm_{dtype}_{last}"], names
 
 
+def test_capture_best_picks_a_working_executor():
+    """The autotuned capture returns one of the executors, with its timings, and that executor reproduces the oracle."""
+    from paper_2312_10351_amd.runtime import Session
+    for wl in (inception_block(), bert_base_like(layers=2)):
+        ref = executor.run_dag(wl)
+        s = Session(wl)
+        try:
+            exe, name, med = s.capture_best(probe_replays=10)
+            assert name in med and len(med) == 4 and med[name] == min(med.values())
+            s.clear_outputs()
+            s.replay(exe)
+            assert not compare_all(s, ref, outlier_frac=1e-3), name
+        finally:
+            s.close()
+
+
 def test_inception_block_fp32_all_modes():
     wl = inception_block()
     sinks = run_modes(wl, modes=("eager", "seq", "par"))
