@@ -27,8 +27,8 @@ sys.path.insert(0, ROOT)
 # profiles/persist_f16_googlenet_like_hbm_traffic.md).
 MEASURED_TRAFFIC_BYTES = {("googlenet_like", "igemm_f16_direct4"): (1054 + 345) * 1024,
                           ("googlenet_like", "igemm_f16_quad4"): (1220 + 136) * 1024,
-                          ("googlenet_like", "persist_f16"): (52811 + 33904) * 1024,
-                          ("googlenet_like", "persist_f16+zero_copy_concat"): (50225 + 29035) * 1024}
+                          ("googlenet_like", "persist_f16"): (51762 + 17008) * 1024,
+                          ("googlenet_like", "persist_f16+zero_copy_concat"): (49159 + 12139) * 1024}
 
 
 def percentile(a, q):
