@@ -72,7 +72,6 @@ struct ConcatArgs {
   X(igemm_f16_quad4, IgemmArgs)         \
   X(igemm_f16_quad8, IgemmArgs)         \
   X(igemm_f16_quad64x4, IgemmArgs)      \
-  X(igemm_f16_quad64x8, IgemmArgs)      \
   X(igemm_f16_t64x64_scalar, IgemmArgs) \
   X(igemm_f32_t128x64, IgemmArgs)       \
   X(igemm_f32_t64x64, IgemmArgs)        \
@@ -81,7 +80,6 @@ struct ConcatArgs {
   X(igemm_f32_quad4, IgemmArgs)         \
   X(igemm_f32_quad8, IgemmArgs)         \
   X(igemm_f32_quad64x4, IgemmArgs)      \
-  X(igemm_f32_quad64x8, IgemmArgs)      \
   X(igemm_f32_t64x64_scalar, IgemmArgs) \
   X(gemv_f16, IgemmArgs)                \
   X(gemv_f32, IgemmArgs)                \

@@ -1008,8 +1008,9 @@ __device__ __forceinline__ void igemm_quad_body(const AR &a, const Blk &b, unsig
 // multiplies the whole tile over its share of K, so each 16-byte piece a lane loads feeds
 // four MFMAs instead of two and the loads and exchanges per multiply-add halve.  The
 // fragments of one step take 128 registers, the accumulators 64: one register set, no
-// prefetch across steps (two workgroups per CU overlap instead), row offsets recomputed
-// per load.  Partial tiles meet in LDS; each thread finishes four 4-channel pieces.
+// prefetch across steps (two four-wavefront workgroups per CU overlap instead; one
+// eight-wavefront workgroup per CU was slower on every shape measured), row offsets
+// recomputed per load.  Partial tiles meet in LDS; each thread finishes four 4-channel pieces.
 // ---------------------------------------------------------------------------------
 template <typename T, int WAVES, int COH, typename AR>
 __device__ __forceinline__ void igemm_quad64_body(const AR &a, const Blk &b, unsigned char *lds) {
@@ -1459,7 +1460,6 @@ KDEF(igemm_f16_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<half_t
 KDEF(igemm_f16_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<half_t, 4, 0>(a, b, lds)))
 KDEF(igemm_f16_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<half_t, 8, 0>(a, b, lds)))
 KDEF2(igemm_f16_quad64x4, 256, 2, lds_quad64(4), IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
-KDEF(igemm_f16_quad64x8, 512, lds_quad64(8), IgemmArgs, (igemm_quad64_body<half_t, 8, 0>(a, b, lds)))
 KDEF(igemm_f16_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF2(igemm_f32_t128x64, 256, 2, lds_pipe(128, 64), IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
@@ -1468,7 +1468,6 @@ KDEF(igemm_f32_direct8, 512, lds_direct(8), IgemmArgs, (igemm_direct_body<float,
 KDEF(igemm_f32_quad4, 256, lds_direct(4), IgemmArgs, (igemm_quad_body<float, 4, 0>(a, b, lds)))
 KDEF(igemm_f32_quad8, 512, lds_direct(8), IgemmArgs, (igemm_quad_body<float, 8, 0>(a, b, lds)))
 KDEF2(igemm_f32_quad64x4, 256, 2, lds_quad64(4), IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
-KDEF(igemm_f32_quad64x8, 512, lds_quad64(8), IgemmArgs, (igemm_quad64_body<float, 8, 0>(a, b, lds)))
 KDEF(igemm_f32_t64x64_scalar, 256, lds_igemm(64, 64), IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
 KDEF(gemv_f16, 256, kLdsNone, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
 KDEF(gemv_f32, 256, kLdsNone, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
@@ -1883,7 +1882,7 @@ int persist_kernel_id(int id) {
     // latency-oriented contraction runs the four-wavefront fragment-loading body.
     case K_igemm_f16_direct8: case K_igemm_f16_quad4: case K_igemm_f16_quad8: return K_igemm_f16_direct4;
     case K_igemm_f32_direct8: case K_igemm_f32_quad4: case K_igemm_f32_quad8: return K_igemm_f32_direct4;
-    case K_igemm_f16_quad64x4: case K_igemm_f16_quad64x8: case K_igemm_f32_quad64x4: case K_igemm_f32_quad64x8:
+    case K_igemm_f16_quad64x4: case K_igemm_f32_quad64x4:
       return -1;                          // never in a persistent plan
     default: return (id >= 0 && id < K_COUNT) ? id : -1;
   }

@@ -142,9 +142,11 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, 
     if (quad64) {
       // GEMM-shaped and at least one 64 x 64 tile per compute unit: the quad-coalesced
       // kernel whose wavefronts each multiply a whole tile over their share of K.
-      const int waves = cdiv(a.K, 16 * ve) <= 16 ? 4 : 8;
-      out->kernel = f16 ? (waves == 4 ? K_igemm_f16_quad64x4 : K_igemm_f16_quad64x8)
-                        : (waves == 4 ? K_igemm_f32_quad64x4 : K_igemm_f32_quad64x8);
+      // Four wavefronts whatever K is: two such workgroups share a CU (70 KB of LDS each),
+      // which beat one eight-wavefront workgroup on every shape measured and leaves room
+      // for workgroups of co-running operators.
+      const int waves = 4;
+      out->kernel = f16 ? K_igemm_f16_quad64x4 : K_igemm_f32_quad64x4;
       out->gx = cdiv(a.M, 64);
       out->gy = cdiv(a.N, 64);
       out->gz = (uint32_t)batch;
