@@ -144,6 +144,7 @@ constexpr IgemmTile kTile64{64, 64, 256};
 constexpr int64_t kQuadMinRowBytes = 1024;   // rows of K at least this long take the quad-coalesced variant
 constexpr int kQuad64MinTiles = 128;             // GEMM-shaped operands with at least this many 64 x 64 tiles take them
 constexpr double kQuad64MaxFlops = 4.0e10;       // ... up to this weight (measured up to 1.7e10)
+constexpr int kQuadFourWaveTiles = 128;          // from this many 32 x 32 tiles on, four wavefronts per tile whatever K is
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)

@@ -16,12 +16,20 @@ const KernelResource kKernelResources[K_COUNT] = {
 
 namespace {
 
-// Tuning knobs (read once): OPARA_QUAD_MIN_ROW_BYTES, OPARA_QUAD64_MIN_TILES; OPARA_TILED_MIN_FLOPS moves the hand-over point between the
+// Tuning knobs (read once): OPARA_QUAD_MIN_ROW_BYTES, OPARA_QUAD_FOUR_WAVE_TILES, OPARA_QUAD64_MIN_TILES; OPARA_TILED_MIN_FLOPS moves the hand-over point between the
 // latency-oriented and the tiled contraction kernel.
 int64_t quad_min_row_bytes() {
   static const int64_t v = [] {
     const char *e = std::getenv("OPARA_QUAD_MIN_ROW_BYTES");
     return e ? (int64_t)std::atoll(e) : kQuadMinRowBytes;
+  }();
+  return v;
+}
+
+int64_t quad_four_wave_tiles() {
+  static const int64_t v = [] {
+    const char *e = std::getenv("OPARA_QUAD_FOUR_WAVE_TILES");
+    return e ? (int64_t)std::atoll(e) : (int64_t)kQuadFourWaveTiles;
   }();
   return v;
 }
@@ -175,7 +183,10 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, 
                                     {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_quad4, K_igemm_f16_quad8}};
       const bool quad = !persistent && (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
       int waves;
-      if (quad) waves = cdiv(a.K, 16 * ve) <= 8 ? 4 : 8;       // 256-byte steps, at most four per wavefront up to K = 8192 B
+      // Deep K on few tiles: eight wavefronts share it (latency).  With a tile or more per
+      // compute unit, four: more workgroups per CU overlap better than longer ones.
+      const int64_t tiles32 = (int64_t)cdiv(a.M, kDirectTile) * cdiv(a.N, kDirectTile) * batch;
+      if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= quad_four_wave_tiles()) ? 4 : 8;   // 256-byte steps
       else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
       out->kernel = ids[f16][(quad ? 2 : 0) + (waves == 8 ? 1 : 0)];
       out->gx = cdiv(a.M, kDirectTile);
