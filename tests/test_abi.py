@@ -10,7 +10,7 @@ from oracle import sched
 from paper_2312_10351_amd import binding as B
 from paper_2312_10351_amd.runtime import Session
 from workloads import (Builder, inception_block, googlenet_like, inception_v3_like, bert_base_like,
-                       random_small_dag, nasnet_like)
+                       random_small_dag, random_wide_dag, nasnet_like)
 from util import LIMITS
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -310,6 +310,36 @@ def test_random_small_workloads_schedule():
         dem = B.opara_get_demands(s.dag)
         preds, oso, ons, oq, osync, _ = oracle_schedule(wl, dem)
         assert (so, ns, q, syncs) == (oso, ons, oq, osync)
+        s.close()
+
+
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, bert_base_like, random_wide_dag])
+def test_planner_gives_each_executor_kind_its_kernels(builder):
+    """Host logic, no GPU: the graph executors' plan uses the quad-coalesced kernels for deep K and 64 x 64 tiles
+    for large GEMM-shaped operands; the persistent executor's plan never does (one workgroup size, the
+    fragment-loading bodies), keeps 32 x 32 tiles for them, and reports a positive tile count per operator."""
+    wl = builder()
+    s = Session(wl, device=None)
+    try:
+        dem = B.opara_get_demands(s.dag)
+        tiles, kernels = B.opara_persistent_plan(s.dag)
+        assert len(tiles) == len(kernels) == len(wl.ops)
+        graph_names = [B.opara_kernel_info(d.kernel_id)[0] for d in dem]
+        persist_names = [B.opara_kernel_info(k)[0] for k in kernels]
+        assert all(t > 0 for t in tiles)
+        assert not any("quad" in n for n in persist_names)
+        for op, d, gname, pname, t in zip(wl.ops, dem, graph_names, persist_names, tiles):
+            if not gname.startswith("igemm"):
+                assert pname == gname and t == d.grid_blocks         # same kernel, same grid
+            elif "quad64" in gname:                                  # 64 x 64 tiles against 32 x 32 or the tiled kernel
+                assert pname.split("_")[-1] in ("direct4", "direct8", "t128x64") and t != d.grid_blocks
+            elif "quad" in gname:                                    # same 32 x 32 tiles, fragment-loading body
+                assert pname.split("_")[-1] in ("direct4", "direct8", "t128x64")
+        if wl.name == "bert_base_like":
+            assert any("quad" in n for n in graph_names)
+        if wl.name == "random_wide_dag":
+            assert any("quad64x4" in n for n in graph_names) and any("t128x64" in n for n in persist_names)
+    finally:
         s.close()
 
 
