@@ -110,7 +110,8 @@ def oracle_schedule(wl, dem):
     return preds, so, ns, q, sched.sync_edges(preds, so), scal
 
 
-@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like, nasnet_like])
+@pytest.mark.parametrize("builder", [inception_block, googlenet_like, inception_v3_like, bert_base_like,
+                                     random_wide_dag, nasnet_like])
 def test_scheduler_matches_oracle_on_configs(builder):
     wl = builder()
     s = Session(wl, device=None)
@@ -123,6 +124,8 @@ def test_scheduler_matches_oracle_on_configs(builder):
         assert q == oq
         assert syncs == osync
         assert sched.check_schedule(preds, so, q, syncs)
+        if builder is random_wide_dag:       # the figures the design notes quote for the 400-operator DAG
+            assert (len(wl.ops), ns, len(syncs)) == (400, 182, 562)
         from oracle.executor import kahn_order
         assert B.opara_topo_order(s.dag) == kahn_order(len(wl.ops), wl.edges())
         # operator table: contractions are compute-intensive, the rest memory-intensive

@@ -267,3 +267,20 @@ def test_elementwise_on_images_and_nasnet_like_wiring():
     o2 = executor.run_dag(nasnet_like(cells=3, width=8, hw=9, dtype="f32", he_init=True, batch=2))
     sink = wl.sinks()[0]
     assert o2[sink].shape == (2, 100) and np.isfinite(o2[sink]).all() and np.abs(o1[sink]).max() > 1e-3
+
+
+def test_prefix_view_rule_on_a_hand_computed_dag():
+    """An operator reads the leading prefix of its producer's flat row-major buffer in its
+    own input shape.  Producer [2, 6] = relu of the external tensor, consumer views [3, 3]:
+    elements 0..8 of the row-major buffer, i.e. the whole first row and half of the second."""
+    from workloads.dag import Op, Workload
+    x = np.array([[1, -2, 3, -4, 5, -6], [7, -8, 9, -10, 11, -12]], dtype=np.float32)
+    ones = np.ones((3, 3), dtype=np.float32)
+    ops = [Op(0, "relu", [-1], [(2, 6)], (2, 6), {}, "producer"),
+           Op(1, "add", [0, -2], [(3, 3), (3, 3)], (3, 3), {}, "consumer")]
+    out = executor.run_dag(Workload("prefix", "f32", ops, [x, ones], {}))
+    assert np.array_equal(out[0], [[1, 0, 3, 0, 5, 0], [7, 0, 9, 0, 11, 0]])
+    assert np.array_equal(out[1], [[2, 1, 4], [1, 6, 1], [8, 1, 10]])
+    with pytest.raises(AssertionError):          # a consumer may not view more than the producer holds
+        bad = [ops[0], Op(1, "relu", [0], [(13,)], (13,), {}, "too_long")]
+        executor.run_dag(Workload("prefix", "f32", bad, [x], {}))

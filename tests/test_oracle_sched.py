@@ -263,3 +263,102 @@ def test_pruning_special_cases():
     preds = [[], [], [0, 1]]
     assert sched.prune_syncs(preds, [0, 0, 1], [0, 1, 2]) == [(1, 2)]
     assert sched.prune_syncs(preds, [0, 0, 1], [1, 0, 2]) == [(0, 2)]
+
+
+# ---------------------------------------------------------------- launch-order policies (Sec. 2.3 order comparison)
+# Hand-worked example.  Seven operators, Kahn order = id order:
+#   0 -> 2, 3     1 -> 4     2, 3 -> 5     4, 3 -> 6
+# classes (M memory-, C compute-intensive) and demands (ties on purpose: 0/1 and 2/4):
+#   id      0  1  2  3  4  5  6
+#   class   C  M  M  C  C  M  C
+#   demand  5  5  3  6  3  4  1
+HAND_PREDS = [[], [], [0], [0], [1], [2, 3], [4, 3]]
+HAND_CLS = [1, 0, 0, 1, 1, 0, 1]
+HAND_DEM = [5, 5, 3, 6, 3, 4, 1]
+# Each queue below was written out by hand from the policy's one-line definition:
+#  alg2            start at M: 1 | C{0:5,4:3} -> 4 | M empty -> 0 | M{2} -> 2 | C{3} -> 3 | M{5} -> 5 | 6
+#  alg2_comp_first start at C: 0 | M{1:5,2:3} -> 2 | C{3} -> 3 | M{1:5,5:4} -> 5 | C empty -> 1 | C{4} -> 4 | 6
+#  least_demand    {0,1} tie -> 0 | {1:5,2:3,3:6} -> 2 | {1:5,3:6} -> 1 | {3:6,4:3} -> 4 | 3 | {5:4,6:1} -> 6 | 5
+#  most_demand     {0,1} tie -> 0 | {1:5,2:3,3:6} -> 3 | {1:5,2:3} -> 1 | {2:3,4:3} tie -> 2 | {4:3,5:4} -> 5 | 4 | 6
+HAND_QUEUES = {
+    "alg2": [1, 4, 0, 2, 3, 5, 6],
+    "alg2_comp_first": [0, 2, 3, 5, 1, 4, 6],
+    "least_demand": [0, 2, 1, 4, 3, 6, 5],
+    "most_demand": [0, 3, 1, 2, 5, 4, 6],
+    "topo": [0, 1, 2, 3, 4, 5, 6],
+    "level": [0, 1, 2, 3, 4, 5, 6],
+}
+
+
+@pytest.mark.parametrize("policy", sched.POLICIES)
+def test_policy_queues_on_the_hand_worked_example(policy):
+    assert sched.order_launch_policy(HAND_PREDS, HAND_CLS, HAND_DEM, policy) == HAND_QUEUES[policy]
+    assert sched.order_launch(HAND_PREDS, HAND_CLS, HAND_DEM) == HAND_QUEUES["alg2"]
+
+
+def test_level_and_trace_order_differ_where_ids_do_not_follow_depth():
+    # 0 -> 3 -> 1 -> 5, 2 -> 4 -> 5.  Kahn smallest id: 0, 2, 3, 1, 4, 5 (1 becomes ready before 4 is taken);
+    # depths 0:0 2:0 3:1 4:1 1:2 5:3, so wave by wave 4 comes before 1.
+    preds = [[], [3], [], [0], [2], [1, 4]]
+    cls, dem = [0] * 6, [1] * 6
+    assert sched.order_launch_policy(preds, cls, dem, "topo") == [0, 2, 3, 1, 4, 5]
+    assert sched.order_launch_policy(preds, cls, dem, "level") == [0, 2, 3, 4, 1, 5]
+
+
+def replay_policy(preds, cls, dem, q, policy):
+    """Independent pick-by-pick check of a one-list policy or of the compute-first Alg. 2:
+    the ready set is recomputed from scratch before every pick."""
+    n = len(preds)
+    topo = kahn_order(n, [(u, v) for v, ps in enumerate(preds) for u in ps])
+    tidx = {v: i for i, v in enumerate(topo)}
+    done, prev_cls = set(), None
+    assert sorted(q) == list(range(n))
+    for v in q:
+        ready = [u for u in range(n) if u not in done and all(p in done for p in preds[u])]
+        assert v in ready
+        if policy == "alg2_comp_first":
+            want = sched.COMP if prev_cls is None else 1 - prev_cls
+            same = [u for u in ready if cls[u] == want]
+            pool = same if same else ready
+            best = min(pool, key=lambda u: (dem[u], tidx[u]))
+        elif policy == "least_demand":
+            best = min(ready, key=lambda u: (dem[u], tidx[u]))
+        else:
+            best = min(ready, key=lambda u: (-dem[u], tidx[u]))
+        assert v == best, (policy, v, best)
+        done.add(v)
+        prev_cls = cls[v]
+
+
+@pytest.mark.parametrize("policy", ["alg2_comp_first", "least_demand", "most_demand"])
+@pytest.mark.parametrize("seed", range(20))
+def test_policy_pick_by_pick(seed, policy):
+    rng = np.random.default_rng(3000 + seed)
+    n = int(rng.integers(2, 30))
+    preds = random_preds(rng, n, p_root=0.35)
+    cls = [int(rng.integers(0, 2)) for _ in range(n)]
+    dem = [int(rng.integers(1, 6)) for _ in range(n)]     # many ties
+    replay_policy(preds, cls, dem, sched.order_launch_policy(preds, cls, dem, policy), policy)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_level_order_is_depth_then_trace_order(seed):
+    rng = np.random.default_rng(4000 + seed)
+    n = int(rng.integers(2, 40))
+    preds = random_preds(rng, n, p_root=0.3)
+    q = sched.order_launch_policy(preds, [0] * n, [1] * n, "level")
+    topo = sched.order_launch_policy(preds, [0] * n, [1] * n, "topo")
+    assert topo == kahn_order(n, [(u, v) for v, ps in enumerate(preds) for u in ps])
+    # depth = length of the longest path from a root, from powers of the adjacency matrix
+    a = np.zeros((n, n), dtype=np.int64)
+    for v, ps in enumerate(preds):
+        for u in ps:
+            a[u, v] = 1
+    depth, p = np.zeros(n, dtype=int), np.eye(n, dtype=np.int64)
+    for k in range(1, n):
+        p = np.minimum(p @ a, 1)
+        depth[p.sum(0) > 0] = k
+    tidx = {v: i for i, v in enumerate(topo)}
+    assert sorted(q) == list(range(n))
+    keys = [(int(depth[v]), tidx[v]) for v in q]
+    assert keys == sorted(keys)
