@@ -50,7 +50,9 @@ enum opara_status {
   OPARA_ENOMEM = -3,
   OPARA_ESTATE = -4,       /* call made out of order (e.g. capture before assign + order)   */
   OPARA_EHIP = -5,         /* a HIP call failed; text via opara_last_error()                */
-  OPARA_EUNSUPPORTED = -6  /* operator / shape has no kernel                                */
+  OPARA_EUNSUPPORTED = -6, /* operator / shape has no kernel, or a mode does not serve this DAG */
+  OPARA_EGRAPH = -7        /* the graph runtime did not honour the dependencies of the graph it
+                              was given (found by the check inside opara_capture)             */
 };
 
 enum opara_op_type {
@@ -231,42 +233,72 @@ int32_t opara_num_ops(const opara_dag *g);
  * with exactly these dependencies: the previous operator of the same stream in
  * launch-queue order, plus every cross-stream predecessor (what recording one event
  * after each producer with a cross-stream consumer and waiting once per such producer
- * on the consumer's stream yields).  Nothing executes.
+ * on the consumer's stream yields).  No operator executes.
  *   OPARA_PARALLEL          assembles that graph node by node.  hip_streams[0..n_streams)
  *                           (hipStream_t handles supplied by the caller, at least as many
- *                           as opara_assign_streams reported, all distinct) are checked
- *                           but carry no work.  A DAG with several sinks gets one
- *                           trailing node without work that joins them.
+ *                           as opara_assign_streams reported, all distinct) carry no
+ *                           operator; hip_streams[0] runs the check described below and
+ *                           is synchronised.  A DAG with several sinks gets one trailing
+ *                           node without work that joins them.
+ *                           The executable graph is validated before it is returned (the
+ *                           graph runtime has been seen to start operators of irregular
+ *                           DAGs before a predecessor had finished, in some instances of a
+ *                           graph and not in others): it is instantiated with marker
+ *                           kernels as nodes, replayed twice on hip_streams[0] (each
+ *                           marker counts predecessors that have not finished; static
+ *                           device memory only), and only an instance without violations
+ *                           has its nodes switched to the operators' kernels, in place.
+ *                           After a violation a fresh instance of the SAME graph is
+ *                           tried, up to four; the streams and the launch queue are never
+ *                           replaced.  EGRAPH if no instance passes.
  *   OPARA_PARALLEL_CAPTURE  obtains the same graph the paper's way: the streams are put
  *                           into one stream capture, every operator is launched on its
  *                           stream in launch-queue order with event record / wait on
  *                           the cross-stream edges, all streams join hip_streams[0].
- *                           Only for DAGs with one root and one sink (EUNSUPPORTED
- *                           otherwise); with the ROCm 7.0 runtime, capturing DAGs whose
- *                           streams wait on each other in both directions crashed the
- *                           host process, which is why this is not the default.
+ *                           Only for DAGs with one root and one sink whose plan is a
+ *                           fork-join of streams: every stream but the first waits
+ *                           exactly once, for one event, at its first operator (which
+ *                           brings it into the capture); only the first stream waits
+ *                           repeatedly (EUNSUPPORTED otherwise, decided before any HIP
+ *                           call).  With the ROCm 7.0 runtime,
+ *                           captures in which streams waited on each other repeatedly
+ *                           (chains of blocks whose heads read several branch tails,
+ *                           random DAGs) ended in a crash of the host process; the cause
+ *                           inside the runtime is not known, which is why this route is
+ *                           limited to the shape it is tested on and is not the default.
+ *                           Not validated.
  *   OPARA_PARALLEL_PRUNED   as OPARA_PARALLEL, without the cross-stream edges that
- *                           opara_sync_edges_pruned drops.
+ *                           opara_sync_edges_pruned drops (the check still counts every
+ *                           predecessor).
  *   OPARA_SEQUENTIAL        captures the same kernels with the same launch shapes on
  *                           hip_streams[0] alone in default topological order (the
  *                           baseline: paper Sec. 5.1, default sequential graph).
  * Errors: ESTATE if assign/order were not called (parallel modes), EINVAL,
- * EUNSUPPORTED, EHIP (a running capture is ended and the partial graph destroyed).
+ * EUNSUPPORTED, EGRAPH, EHIP (a running capture is ended and the partial graph destroyed).
  */
 int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams,
                   int32_t mode, opara_exec **out);
 
 /*
- * Dependency self-check of the graph runtime (failure detection).  Builds a graph with
- * exactly the nodes order and dependency edges opara_capture gives the current parallel
- * plan, but with marker kernels instead of operators: each marks its operator done
- * after a few microseconds and counts predecessors that are not yet marked.  The graph
- * is launched twice on `hip_stream`, which is synchronised; n_violations receives the
- * total (0 = every dependency was honoured).  Uses static device memory only.  A
- * non-zero count means the graph runtime dropped a dependency of this topology and
- * node order.  The check runs on a graph of its own: it screens a plan, it does not
- * certify a particular opara_exec (compare a replay of the captured graph with the
- * sequential graph's result for that).  Needs assign + order first (ESTATE).
+ * How an executable graph was checked before opara_capture returned it (host int32 each,
+ * either may be NULL): kind is OPARA_VALIDATED_IN_PLACE (the returned instance itself ran
+ * the marker check), OPARA_SCREENED_ON_TWIN (the runtime refused to switch the kernels of
+ * an instantiated graph, so the operators' graph was instantiated beside a marker graph
+ * that passed) or OPARA_NOT_VALIDATED (sequential graph, stream capture, persistent
+ * executor: single chains and single kernels have not shown the defect); attempts is the
+ * number of instances built.
+ */
+enum opara_validation { OPARA_NOT_VALIDATED = 0, OPARA_SCREENED_ON_TWIN = 1, OPARA_VALIDATED_IN_PLACE = 2 };
+int opara_exec_validation(const opara_exec *e, int32_t *kind, int32_t *attempts);
+
+/*
+ * Dependency self-check of the graph runtime as a call of its own (diagnostics: how often
+ * does an instance of this plan's graph fail?).  Builds one instance of the marker graph
+ * opara_capture validates (same node order and dependency edges as OPARA_PARALLEL), launches
+ * it twice on `hip_stream`, which is synchronised; n_violations receives the number of
+ * operators that started before a predecessor had finished (0 = every dependency was
+ * honoured).  Uses static device memory only.  It says nothing about an opara_exec:
+ * opara_capture checks the instance it returns by itself.  Needs assign + order first (ESTATE).
  */
 int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violations);
 

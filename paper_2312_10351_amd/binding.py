@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libopara.so")
 MAX_INPUTS = 8
 
-OK, EINVAL, ECYCLE, ENOMEM, ESTATE, EHIP, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ECYCLE, ENOMEM, ESTATE, EHIP, EUNSUPPORTED, EGRAPH = 0, -1, -2, -3, -4, -5, -6, -7
+NOT_VALIDATED, SCREENED_ON_TWIN, VALIDATED_IN_PLACE = 0, 1, 2
 (CONV2D, GEMM, BGEMM, MAXPOOL, AVGPOOL, GAVGPOOL, CONCAT, LAYERNORM, SOFTMAX, GELU, RELU,
  ADD) = range(12)
 OP_TYPE_IDS = dict(conv2d=CONV2D, gemm=GEMM, bgemm=BGEMM, maxpool=MAXPOOL, avgpool=AVGPOOL,
@@ -68,7 +69,7 @@ EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_assign_streams_poli
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
            "opara_persistent_set_trace",
-           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_launch_op", "opara_run_eager",
+           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
 
@@ -109,6 +110,7 @@ def load():
     lib.opara_persistent_set_trace.argtypes = [vp, vp, vp, C.c_uint64]
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
+    lib.opara_exec_validation.argtypes = [vp, i32p, i32p]
     lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
     lib.opara_run_eager.argtypes = [vp, vp]
     lib.opara_kernel_count.argtypes = []
@@ -282,6 +284,13 @@ def opara_verify_dependencies(dag, stream_handle):
 def opara_exec_info(exe):
     a, b = C.c_int32(), C.c_int32()
     _check(load().opara_exec_info(exe, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def opara_exec_validation(exe):
+    """(kind, attempts): how opara_capture checked the executable graph it returned."""
+    a, b = C.c_int32(), C.c_int32()
+    _check(load().opara_exec_validation(exe, C.byref(a), C.byref(b)))
     return a.value, b.value
 
 

@@ -1,7 +1,9 @@
-// Graph capturer and replay (paper Sec. 3.4): every stream handed in by the caller is
-// pulled into one stream capture, operators are launched on their streams in launch-
-// queue order, cross-stream dependencies become event record / wait pairs, and the
-// result is instantiated as a single executable graph.
+// Graph capturer and replay (paper Sec. 3.4): one executable graph per DAG.  By default the
+// graph is assembled node by node with the dependencies a multi-stream capture would record
+// (previous operator of the stream in launch-queue order + every cross-stream predecessor)
+// and is validated in place before it is handed out; stream capture itself, the paper's
+// route, is kept for the DAG shapes it is known to serve.  Also here: the persistent
+// executor's capture and the entry point for callers that cannot allocate.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <new>
@@ -15,6 +17,7 @@ struct opara_exec {
   hipGraphExec_t exec = nullptr;
   std::vector<hipEvent_t> events;
   int32_t n_nodes = 0, n_edges = 0;
+  int32_t validation = 0, attempts = 0;   // see opara_exec_validation
   // persistent executor only: caller-owned workspace and the size of its counter block
   void *workspace = nullptr;
   int32_t persist_ops = 0, persist_items = 0, persist_workgroups = 0, persist_prefix = 0;
@@ -43,6 +46,74 @@ void destroy_exec(opara_exec *e) {
       goto fail;                                                                        \
     }                                                                                   \
   } while (0)
+
+constexpr int kCaptureAttempts = 4;      // instances of one graph tried before opara_capture gives up
+constexpr int kValidationReplays = 2;
+
+// Stream capture is used for fork-join plans only: every stream other than the origin
+// (the stream of the first queue entry) waits exactly once, at its first operator, on one
+// event (which brings it into the capture), and is itself waited for; only the origin
+// stream waits more than once.  Every DAG that captured cleanly has this shape (branch
+// heads with one input each, joins on the origin stream); every capture that ended in a
+// host-side crash of the runtime lacked it (streams that wait on each other again and again,
+// as in chains of blocks whose heads read several branch tails, or random DAGs).
+// On refusal *u -> *v is an offending dependency.
+bool stream_capture_supported(const opara_dag *g, int32_t *u_out, int32_t *v_out) {
+  const int32_t origin = g->stream_of[g->order[0]];
+  std::vector<int32_t> first_of((size_t)g->n_streams, -1);
+  for (int32_t i = 0; i < g->n; ++i) {
+    const int32_t v = g->order[i];
+    if (first_of[g->stream_of[v]] < 0) first_of[g->stream_of[v]] = v;
+  }
+  for (int32_t v = 0; v < g->n; ++v) {
+    const int32_t sv = g->stream_of[v];
+    const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+      const int32_t u = g->pred[j], su = g->stream_of[u];
+      if (su == sv || sv == origin) continue;                       // same stream, or a join on the origin
+      if (first_of[sv] == v && np == 1) continue;                   // the one wait that opens stream sv
+      *u_out = u; *v_out = v;
+      return false;
+    }
+  }
+  return true;
+}
+
+// Adds the nodes of the multi-stream plan to `graph` in launch-queue order: marker kernels
+// (tokens) or the operators' kernels.  Markers know every predecessor of their operator,
+// also those whose edge was pruned.
+hipError_t assemble_parallel(const opara_dag *g, const std::vector<uint8_t> &keep_edge, bool tokens, hipGraph_t graph,
+                             std::vector<hipGraphNode_t> *node_of) {
+  const int32_t n = g->n;
+  std::vector<hipGraphNode_t> last_on_stream((size_t)g->n_streams, nullptr), deps;
+  int32_t n_sinks = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t v = g->order[i], sv = g->stream_of[v];
+    deps.clear();
+    if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
+    TokenNodeArgs t = {};
+    t.real = g->plan[v].args;
+    t.tok.epoch = 1; t.tok.self = v; t.tok.delay = 4;
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
+      const int32_t u = g->pred[j];
+      if (t.tok.n_preds < kVerifyMaxPreds) t.tok.preds[t.tok.n_preds++] = u;
+      if (g->stream_of[u] != sv && keep_edge[j]) deps.push_back((*node_of)[u]);
+    }
+    hipError_t err = tokens ? add_token_node(graph, t, deps.empty() ? nullptr : deps.data(), deps.size(), &(*node_of)[v])
+                            : add_plan_node(graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &(*node_of)[v]);
+    if (err != hipSuccess) return err;
+    last_on_stream[sv] = (*node_of)[v];
+    n_sinks += (g->succ_off[v + 1] == g->succ_off[v]);
+  }
+  if (n_sinks > 1) {
+    hipGraphNode_t leaf = nullptr;
+    deps.clear();
+    for (int32_t v = 0; v < n; ++v)
+      if (g->succ_off[v + 1] == g->succ_off[v]) deps.push_back((*node_of)[v]);
+    return add_noop_node(graph, deps.data(), deps.size(), &leaf);
+  }
+  return hipSuccess;
+}
 
 }  // namespace
 
@@ -88,12 +159,29 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
     delete e;
     return OPARA_EUNSUPPORTED;
   }
+  if (mode == OPARA_PARALLEL_CAPTURE) {
+    int32_t u = -1, v = -1;
+    if (!stream_capture_supported(g, &u, &v)) {
+      set_error("opara_capture: stream capture serves fork-join plans only (every stream but the first waits once, at its "
+                "first operator); dependency %d -> %d makes stream %d wait for stream %d otherwise", u, v,
+                g->stream_of[v], g->stream_of[u]);
+      delete e;
+      return OPARA_EUNSUPPORTED;
+    }
+  }
   // Default: the graph is assembled node by node.  Each node depends on the previous
   // operator of its stream in launch-queue order and on every cross-stream predecessor;
   // one leaf node without work closes a DAG with several sinks.
+  //
+  // The graph runtime has been seen to start operators of irregular DAGs before a
+  // predecessor had finished, depending on the instance (which one fails changes from
+  // process to process).  So the graph is first instantiated with marker kernels as nodes
+  // (each marks its operator done after a few microseconds and counts predecessors not yet
+  // marked), that executable graph is replayed and must show no violation, and then every
+  // node of the SAME executable graph is switched to its operator's kernel: the instance
+  // that is handed out is the one that was checked.  A failed check is answered by a fresh
+  // instance of the same graph (same streams, same launch queue), never by another plan.
   if (mode == OPARA_PARALLEL || mode == OPARA_PARALLEL_PRUNED) {
-    std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(ns, nullptr), deps;
-    hipGraphNode_t leaf = nullptr;
     // pruned: keep_edge[pred slot j] says whether the cross-stream dependency still needs an edge
     std::vector<uint8_t> keep_edge(g->pred.size(), 1);
     if (mode == OPARA_PARALLEL_PRUNED) {
@@ -104,25 +192,51 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
         for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j)
           if (g->stream_of[g->pred[j]] != g->stream_of[v]) keep_edge[j] = keep[k++];
     }
-    HIP_TRY(hipGraphCreate(&e->graph, 0));
-    for (int32_t i = 0; i < n; ++i) {
-      const int32_t v = q[i], sv = g->stream_of[v];
-      deps.clear();
-      if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
-      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
-        const int32_t u = g->pred[j];
-        if (g->stream_of[u] != sv && keep_edge[j]) deps.push_back(node_of[u]);
+    if (n > kVerifyMaxOps) { set_error("opara_capture: more than %d operators", kVerifyMaxOps); delete e; return OPARA_EUNSUPPORTED; }
+    std::vector<hipGraphNode_t> node_of(n, nullptr);
+    bool swap_in_place = true;                     // false once the runtime has refused to switch a node's kernel
+    int violations = 0;
+    for (int attempt = 1; attempt <= kCaptureAttempts; ++attempt) {
+      e->attempts = attempt;
+      if (e->exec) { (void)hipGraphExecDestroy(e->exec); e->exec = nullptr; }
+      if (e->graph) { (void)hipGraphDestroy(e->graph); e->graph = nullptr; }
+      HIP_TRY(hipGraphCreate(&e->graph, 0));
+      HIP_TRY(assemble_parallel(g, keep_edge, /*tokens=*/true, e->graph, &node_of));
+      HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+      violations = 0;
+      for (int rep = 0; rep < kValidationReplays; ++rep) {
+        int viol = 0;
+        HIP_TRY(verify_reset(origin));
+        HIP_TRY(hipGraphLaunch(e->exec, origin));
+        HIP_TRY(verify_read(origin, &viol));
+        violations += viol;
       }
-      HIP_TRY(add_plan_node(e->graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
-      last_on_stream[sv] = node_of[v];
+      if (violations != 0) continue;               // this instance drops a dependency: build another
+      if (swap_in_place) {
+        hipError_t err = hipSuccess;
+        for (int32_t v = 0; v < n && err == hipSuccess; ++v) err = set_exec_node_plan(e->exec, node_of[v], g->plan[v]);
+        if (err == hipSuccess) {
+          e->validation = OPARA_VALIDATED_IN_PLACE;
+          break;
+        }
+        (void)hipGetLastError();
+        swap_in_place = false;                     // fall through: operators' graph beside the checked twin
+      }
+      (void)hipGraphExecDestroy(e->exec); e->exec = nullptr;
+      (void)hipGraphDestroy(e->graph); e->graph = nullptr;
+      HIP_TRY(hipGraphCreate(&e->graph, 0));
+      HIP_TRY(assemble_parallel(g, keep_edge, /*tokens=*/false, e->graph, &node_of));
+      HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+      e->validation = OPARA_SCREENED_ON_TWIN;
+      break;
     }
-    if (n_sinks > 1) {
-      deps.clear();
-      for (int32_t v = 0; v < n; ++v)
-        if (g->succ_off[v + 1] == g->succ_off[v]) deps.push_back(node_of[v]);
-      HIP_TRY(add_noop_node(e->graph, deps.data(), deps.size(), &leaf));
+    if (e->validation == OPARA_NOT_VALIDATED) {
+      set_error("opara_capture: the graph runtime started operators before their predecessors in %d of %d instances "
+                "of this graph (last one: %d violations); no graph is handed out", kCaptureAttempts, kCaptureAttempts,
+                violations);
+      destroy_exec(e);
+      return OPARA_EGRAPH;
     }
-    HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
     size_t nn = 0, ne = 0;
     HIP_TRY(hipGraphGetNodes(e->graph, nullptr, &nn));
     HIP_TRY(hipGraphGetEdges(e->graph, nullptr, nullptr, &ne));
@@ -212,33 +326,12 @@ extern "C" int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t
   hipGraphExec_t exec = nullptr;
   int total = 0;
   {
-    std::vector<hipGraphNode_t> node_of(n, nullptr), last_on_stream(g->n_streams, nullptr), deps;
+    std::vector<hipGraphNode_t> node_of(n, nullptr);
+    const std::vector<uint8_t> keep_edge(g->pred.size(), 1);
     HIP_TRY(hipGraphCreate(&graph, 0));
-    int32_t n_sinks = 0;
-    for (int32_t i = 0; i < n; ++i) {
-      const int32_t v = g->order[i], sv = g->stream_of[v];
-      TokenArgs t = {};
-      t.epoch = 1; t.self = v; t.delay = 4;
-      deps.clear();
-      if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
-      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
-        const int32_t u = g->pred[j];
-        if (t.n_preds < kVerifyMaxPreds) t.preds[t.n_preds++] = u;
-        if (g->stream_of[u] != sv) deps.push_back(node_of[u]);
-      }
-      HIP_TRY(add_token_node(graph, t, deps.empty() ? nullptr : deps.data(), deps.size(), &node_of[v]));
-      last_on_stream[sv] = node_of[v];
-      n_sinks += (g->succ_off[v + 1] == g->succ_off[v]);
-    }
-    if (n_sinks > 1) {
-      hipGraphNode_t leaf = nullptr;
-      deps.clear();
-      for (int32_t v = 0; v < n; ++v)
-        if (g->succ_off[v + 1] == g->succ_off[v]) deps.push_back(node_of[v]);
-      HIP_TRY(add_noop_node(graph, deps.data(), deps.size(), &leaf));
-    }
+    HIP_TRY(assemble_parallel(g, keep_edge, /*tokens=*/true, graph, &node_of));
     HIP_TRY(hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
-    for (int rep = 0; rep < 2; ++rep) {
+    for (int rep = 0; rep < kValidationReplays; ++rep) {
       int viol = 0;
       HIP_TRY(verify_reset(st));
       HIP_TRY(hipGraphLaunch(exec, st));
@@ -313,6 +406,107 @@ extern "C" int opara_persistent_workspace_bytes(const opara_dag *g, uint64_t *by
   return OPARA_OK;
 }
 
+namespace {
+
+// Builds the workspace image of the persistent executor for the current launch queue:
+// records in launch-queue order, work items, predecessor lists.  Asks the runtime how many
+// workgroups of the kernel the device holds at once (no allocation).  Returns an opara_status.
+int build_persist_image(const opara_dag *g, int32_t n_workgroups, const char *who, PersistImage *img) {
+  const int32_t n = g->n;
+  const PersistLayout lay = persist_layout(n);
+  const int32_t prefix = serial_prefix(g);                      // run as ordinary kernel nodes
+  const int32_t np_ops = n - prefix;                            // operators inside the persistent kernel
+  const uint32_t lds_bytes = persist_lds_bytes((uint32_t)np_ops);
+  if (lds_bytes > kPersistMaxLds || n > 65535) {
+    set_error("%s: %d operators exceed the ticket table held in workgroup memory", who, n);
+    return OPARA_EUNSUPPORTED;
+  }
+  // Workgroups the device holds at once: the launch size, and the tiles per work item of
+  // operators that have more tiles than that.
+  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan_persist[g->order[prefix]].kernel));
+  uint32_t wgs = 0;
+  {
+    hipError_t err = persist_max_workgroups(f16, lds_bytes, &wgs);
+    if (err != hipSuccess) {
+      set_error("%s: occupancy query failed: %s", who, hipGetErrorString(err));
+      (void)hipGetLastError();
+      return OPARA_EHIP;
+    }
+  }
+  if (wgs == 0) { set_error("%s: the kernel does not fit a compute unit", who); return OPARA_EHIP; }
+  if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
+  // Records in launch-queue order.
+  std::vector<unsigned char> &host = img->host;
+  host.assign(lay.bytes, 0);
+  PersistHeader *hdr = (PersistHeader *)host.data();
+  hdr->spin_limit = kPersistDefaultSpinLimit;
+  hdr->epoch = 1;
+  int32_t *begin = (int32_t *)(host.data() + lay.begin);
+  PersistPredsLds *preds = (PersistPredsLds *)(host.data() + lay.preds);
+  PersistOp *rec = (PersistOp *)(host.data() + lay.rec);
+  std::vector<int32_t> pos_of(n, -1);
+  int64_t total = 0;
+  std::vector<char> in_prefix((size_t)n, 0);                    // complete before the kernel starts
+  for (int32_t q = 0; q < prefix; ++q) in_prefix[g->order[q]] = 1;
+  for (int32_t i = 0; i < np_ops; ++i) {
+    const int32_t v = g->order[prefix + i];
+    const KernelPlan &p = g->plan_persist[v];
+    const int kid = persist_kernel_id(p.kernel);
+    if (kid < 0) { set_error("%s: operator %d has no persistent kernel", who, v); return OPARA_EUNSUPPORTED; }
+    if (kernel_is_f16(kid) != f16) { set_error("%s: mixed element types", who); return OPARA_EUNSUPPORTED; }
+    pos_of[v] = i;
+    const int64_t t = (int64_t)p.gx * p.gy * p.gz;
+    if (t < 1 || t > 65535 || total + t > INT32_MAX) { set_error("%s: work-item count out of range", who); return OPARA_EUNSUPPORTED; }
+    begin[i] = (int32_t)total;
+    const int64_t chunk = (t + wgs - 1) / wgs;                  // 1 unless the operator has more tiles than workgroups
+    const int64_t items = (t + chunk - 1) / chunk;
+    total += (items + kPersistItemAlign - 1) / kPersistItemAlign * kPersistItemAlign;
+    rec[i].kernel = kid + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
+    rec[i].gx = (int32_t)p.gx; rec[i].gy = (int32_t)p.gy; rec[i].gz = (int32_t)p.gz;
+    rec[i].args = p.args;
+    const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
+    if (np > kPersistMaxPreds) { set_error("%s: operator %d has %d predecessors (limit %d)", who, v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
+    int32_t kept = 0;
+    for (int32_t j = 0; j < np; ++j) {
+      const int32_t pu = g->pred[g->pred_off[v] + j];
+      const int32_t u = pos_of[pu];
+      if (u >= 0) { preds[i].pos[kept++] = (uint16_t)u; continue; }
+      if (!in_prefix[pu]) { set_error("%s: launch queue is not topological", who); return OPARA_ESTATE; }
+    }
+    preds[i].n = (uint16_t)kept;
+    preds[i].tiles = (uint16_t)t;
+    preds[i].chunk = (uint16_t)chunk;
+  }
+  begin[np_ops] = (int32_t)total;
+  if ((int64_t)wgs > total) wgs = (uint32_t)total;
+  if (wgs > (uint32_t)kPersistItemAlign) wgs -= wgs % kPersistItemAlign;
+  img->prefix = prefix;
+  img->np_ops = np_ops;
+  img->total = (int32_t)total;
+  img->wgs = wgs;
+  img->lds_bytes = lds_bytes;
+  img->f16 = f16;
+  return OPARA_OK;
+}
+
+// Kernel arguments of an image that lives at device address `workspace`.
+PersistArgs persist_args_at(const PersistImage &img, int32_t n_ops, void *workspace) {
+  const PersistLayout lay = persist_layout(n_ops);
+  PersistArgs pa;
+  unsigned char *ws = (unsigned char *)workspace;
+  pa.hdr = (PersistHeader *)ws;
+  pa.done = (uint32_t *)(ws + lay.done);
+  pa.flags = (uint32_t *)(ws + lay.flags);
+  pa.item_begin = (const int32_t *)(ws + lay.begin);
+  pa.preds = (const PersistPredsLds *)(ws + lay.preds);
+  pa.rec = (const PersistOp *)(ws + lay.rec);
+  pa.n = img.np_ops;
+  pa.total = img.total;
+  return pa;
+}
+
+}  // namespace
+
 extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t workspace_bytes,
                                         int32_t n_workgroups, opara_exec **out) {
   if (!g || !workspace || !out || n_workgroups < 0) { set_error("opara_capture_persistent: bad argument"); return OPARA_EINVAL; }
@@ -325,105 +519,34 @@ extern "C" int opara_capture_persistent(opara_dag *g, void *workspace, uint64_t 
               (unsigned long long)workspace_bytes, (unsigned long long)lay.bytes);
     return OPARA_EINVAL;
   }
-  const int32_t prefix = serial_prefix(g);                      // run as ordinary kernel nodes
-  const int32_t np_ops = n - prefix;                            // operators inside the persistent kernel
-  const uint32_t lds_bytes = persist_lds_bytes((uint32_t)np_ops);
-  if (lds_bytes > kPersistMaxLds || n > 65535) {
-    set_error("opara_capture_persistent: %d operators exceed the ticket table held in workgroup memory", n);
-    return OPARA_EUNSUPPORTED;
-  }
-  // Workgroups the device holds at once: the launch size, and the tiles per work item of
-  // operators that have more tiles than that.
-  const bool f16 = kernel_is_f16(persist_kernel_id(g->plan_persist[g->order[prefix]].kernel));
-  uint32_t wgs = 0;
+  PersistImage img;
   {
-    hipError_t err = persist_max_workgroups(f16, lds_bytes, &wgs);
-    if (err != hipSuccess) {
-      set_error("opara_capture_persistent: occupancy query failed: %s", hipGetErrorString(err));
-      (void)hipGetLastError();
-      return OPARA_EHIP;
-    }
+    const int rc = build_persist_image(g, n_workgroups, "opara_capture_persistent", &img);
+    if (rc != OPARA_OK) return rc;
   }
-  if (wgs == 0) { set_error("opara_capture_persistent: the kernel does not fit a compute unit"); return OPARA_EHIP; }
-  if (n_workgroups > 0 && (uint32_t)n_workgroups < wgs) wgs = (uint32_t)n_workgroups;
-  // Records in launch-queue order.
-  std::vector<unsigned char> host(lay.bytes, 0);
-  PersistHeader *hdr = (PersistHeader *)host.data();
-  hdr->spin_limit = kPersistDefaultSpinLimit;
-  hdr->epoch = 1;
-  int32_t *begin = (int32_t *)(host.data() + lay.begin);
-  PersistPredsLds *preds = (PersistPredsLds *)(host.data() + lay.preds);
-  PersistOp *rec = (PersistOp *)(host.data() + lay.rec);
-  std::vector<int32_t> pos_of(n, -1);
-  std::vector<uint32_t> tiles(n, 0);
-  int64_t total = 0;
-  std::vector<char> in_prefix((size_t)n, 0);                    // complete before the kernel starts
-  for (int32_t q = 0; q < prefix; ++q) in_prefix[g->order[q]] = 1;
-  for (int32_t i = 0; i < np_ops; ++i) {
-    const int32_t v = g->order[prefix + i];
-    const KernelPlan &p = g->plan_persist[v];
-    const int kid = persist_kernel_id(p.kernel);
-    if (kid < 0) { set_error("opara_capture_persistent: operator %d has no persistent kernel", v); return OPARA_EUNSUPPORTED; }
-    if (kernel_is_f16(kid) != f16) { set_error("opara_capture_persistent: mixed element types"); return OPARA_EUNSUPPORTED; }
-    pos_of[v] = i;
-    const int64_t t = (int64_t)p.gx * p.gy * p.gz;
-    if (t < 1 || t > 65535 || total + t > INT32_MAX) { set_error("opara_capture_persistent: work-item count out of range"); return OPARA_EUNSUPPORTED; }
-    tiles[i] = (uint32_t)t;
-    begin[i] = (int32_t)total;
-    const int64_t chunk = (t + wgs - 1) / wgs;                  // 1 unless the operator has more tiles than workgroups
-    const int64_t items = (t + chunk - 1) / chunk;
-    total += (items + kPersistItemAlign - 1) / kPersistItemAlign * kPersistItemAlign;
-    rec[i].kernel = kid + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
-    rec[i].gx = (int32_t)p.gx; rec[i].gy = (int32_t)p.gy; rec[i].gz = (int32_t)p.gz;
-    rec[i].args = p.args;
-    const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
-    if (np > kPersistMaxPreds) { set_error("opara_capture_persistent: operator %d has %d predecessors (limit %d)", v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
-    int32_t kept = 0;
-    for (int32_t j = 0; j < np; ++j) {
-      const int32_t pu = g->pred[g->pred_off[v] + j];
-      const int32_t u = pos_of[pu];
-      if (u >= 0) { preds[i].pos[kept++] = (uint16_t)u; continue; }
-      if (!in_prefix[pu]) { set_error("opara_capture_persistent: launch queue is not topological"); return OPARA_ESTATE; }
-    }
-    preds[i].n = (uint16_t)kept;
-    preds[i].tiles = (uint16_t)t;
-    preds[i].chunk = (uint16_t)chunk;
-  }
-  begin[np_ops] = (int32_t)total;
   opara_exec *e = new (std::nothrow) opara_exec();
   if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
   {
-    if ((int64_t)wgs > total) wgs = (uint32_t)total;
-    if (wgs > (uint32_t)kPersistItemAlign) wgs -= wgs % kPersistItemAlign;
-    HIP_TRY(hipMemcpy(workspace, host.data(), lay.bytes, hipMemcpyHostToDevice));
-    PersistArgs pa;
-    unsigned char *ws = (unsigned char *)workspace;
-    pa.hdr = (PersistHeader *)ws;
-    pa.done = (uint32_t *)(ws + lay.done);
-    pa.flags = (uint32_t *)(ws + lay.flags);
-    pa.item_begin = (const int32_t *)(ws + lay.begin);
-    pa.preds = (const PersistPredsLds *)(ws + lay.preds);
-    pa.rec = (const PersistOp *)(ws + lay.rec);
-    pa.n = np_ops;
-    pa.total = (int32_t)total;
+    HIP_TRY(hipMemcpy(workspace, img.host.data(), lay.bytes, hipMemcpyHostToDevice));
+    const PersistArgs pa = persist_args_at(img, n, workspace);
     hipGraphNode_t node = nullptr, last = nullptr;
     HIP_TRY(hipGraphCreate(&e->graph, 0));
-    for (int32_t q = 0; q < prefix; ++q) {                      // the serial prefix: a chain of ordinary launches
+    for (int32_t q = 0; q < img.prefix; ++q) {                  // the serial prefix: a chain of ordinary launches
       HIP_TRY(add_plan_node(e->graph, g->plan[g->order[q]], last ? &last : nullptr, last ? 1 : 0, &node));
       last = node;
     }
-    HIP_TRY(add_persist_node(e->graph, f16, pa, wgs, lds_bytes, last ? &last : nullptr, last ? 1 : 0, &node));
+    HIP_TRY(add_persist_node(e->graph, img.f16, pa, img.wgs, img.lds_bytes, last ? &last : nullptr, last ? 1 : 0, &node));
     HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
-    e->n_nodes = prefix + 1;
-    e->n_edges = prefix;
+    e->n_nodes = img.prefix + 1;
+    e->n_edges = img.prefix;
     e->workspace = workspace;
-    e->persist_prefix = prefix;
+    e->persist_prefix = img.prefix;
     e->persist_args = pa;
-    e->persist_f16 = f16;
-    e->persist_lds = lds_bytes;
+    e->persist_f16 = img.f16;
+    e->persist_lds = img.lds_bytes;
     e->persist_ops = n;
-    e->persist_items = (int32_t)total;
-    e->persist_workgroups = (int32_t)wgs;
+    e->persist_items = img.total;
+    e->persist_workgroups = (int32_t)img.wgs;
   }
   *out = e;
   return OPARA_OK;
@@ -528,6 +651,13 @@ extern "C" int opara_replay(opara_exec *e, void *hip_stream) {
   if (!e || !e->exec) { set_error("opara_replay: null handle"); return OPARA_EINVAL; }
   hipError_t err = hipGraphLaunch(e->exec, (hipStream_t)hip_stream);
   if (err != hipSuccess) { set_error("hipGraphLaunch failed: %s", hipGetErrorString(err)); return OPARA_EHIP; }
+  return OPARA_OK;
+}
+
+extern "C" int opara_exec_validation(const opara_exec *e, int32_t *kind, int32_t *attempts) {
+  if (!e) { set_error("opara_exec_validation: null handle"); return OPARA_EINVAL; }
+  if (kind) *kind = e->validation;
+  if (attempts) *attempts = e->attempts;
   return OPARA_OK;
 }
 

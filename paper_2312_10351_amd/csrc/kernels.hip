@@ -1793,7 +1793,8 @@ extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f32(Persist
 static __device__ int g_verify_tok[opara::kVerifyMaxOps];
 static __device__ int g_verify_viol;
 
-extern "C" __global__ void opara_k_token(opara::TokenArgs a) {
+extern "C" __global__ void opara_k_token(opara::TokenNodeArgs node) {
+  const opara::TokenArgs &a = node.tok;
   if (threadIdx.x != 0) return;
   for (int i = 0; i < a.n_preds; ++i)
     if (__hip_atomic_load(&g_verify_tok[a.preds[i]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
@@ -1853,6 +1854,21 @@ hipError_t add_plan_node(hipGraph_t graph, const KernelPlan &p, const hipGraphNo
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
 }
 
+hipError_t set_exec_node_plan(hipGraphExec_t exec, hipGraphNode_t node, const KernelPlan &p) {
+  void *func = const_cast<void *>(kernel_symbol(p.kernel));
+  if (!func) return hipErrorInvalidValue;
+  KernelArgs args = p.args;
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = func;
+  np.gridDim = dim3(p.gx, p.gy, p.gz);
+  np.blockDim = dim3(p.block);
+  np.sharedMemBytes = 0;
+  np.kernelParams = kparams;
+  np.extra = nullptr;
+  return hipGraphExecKernelNodeSetParams(exec, node, &np);
+}
+
 hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
   int zero = 0;
   void *kparams[1] = {&zero};
@@ -1864,9 +1880,9 @@ hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
 }
 
-hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNode_t *deps, size_t n_deps,
+hipError_t add_token_node(hipGraph_t graph, const TokenNodeArgs &t, const hipGraphNode_t *deps, size_t n_deps,
                           hipGraphNode_t *node) {
-  TokenArgs args = t;
+  TokenNodeArgs args = t;
   void *kparams[1] = {&args};
   hipKernelNodeParams np = {};
   np.func = (void *)opara_k_token;

@@ -16,10 +16,18 @@ hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_
 // Dependency self-check (see opara_verify_dependencies): a token node marks its
 // operator as done after a short delay and counts predecessors not yet marked.
 constexpr int kVerifyMaxOps = 1 << 16;
-constexpr int kVerifyMaxPreds = 8;
+constexpr int kVerifyMaxPreds = 16;
 struct TokenArgs { int32_t epoch, self, n_preds, delay; int32_t preds[kVerifyMaxPreds]; };
-hipError_t add_token_node(hipGraph_t graph, const TokenArgs &t, const hipGraphNode_t *deps, size_t n_deps,
+// What a token node is given.  The operator's own argument record sits at offset 0 and the
+// record is as large as any kernel's: when the node of an instantiated graph is later
+// switched to the operator's kernel, the argument block the runtime holds for the node is
+// large enough and already valid for that kernel.
+struct TokenNodeArgs { KernelArgs real; TokenArgs tok; };
+hipError_t add_token_node(hipGraph_t graph, const TokenNodeArgs &t, const hipGraphNode_t *deps, size_t n_deps,
                           hipGraphNode_t *node);
+// Switches a kernel node of an instantiated graph to the planned launch `p` (kernel, grid,
+// workgroup size, arguments).  The node keeps its place and dependencies.
+hipError_t set_exec_node_plan(hipGraphExec_t exec, hipGraphNode_t node, const KernelPlan &p);
 
 // ---- Persistent executor: the whole DAG as one kernel -------------------------------
 // Workgroups of one launch draw (operator, tile) work items from a ticket counter in
@@ -82,4 +90,5 @@ hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups,
 
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter
+
 }  // namespace opara

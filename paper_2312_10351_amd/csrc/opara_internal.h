@@ -6,6 +6,18 @@
 #include "../../include/opara.h"
 #include "kernel_args.h"
 
+namespace opara {
+// Host copy of a persistent executor's workspace (header, counters, flags, item table,
+// predecessor lists, operator records in launch-queue order) and what the launch needs.
+struct PersistImage {
+  std::vector<unsigned char> host;
+  int32_t prefix = 0;               // leading queue operators launched as ordinary kernels
+  int32_t np_ops = 0, total = 0;    // operators inside the kernel, work items
+  uint32_t wgs = 0, lds_bytes = 0;  // workgroups of the launch, dynamic LDS per workgroup
+  bool f16 = false;
+};
+}  // namespace opara
+
 struct opara_dag {
   int32_t n = 0;
   std::vector<opara_op_desc> ops;

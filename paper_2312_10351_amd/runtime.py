@@ -71,7 +71,6 @@ class Session:
         self._workspaces = []
         self.streams = None
         self.capture_log = []
-        self._seq_reference = None
         self._fake = 0x10000
         self._keep = []
         self.dtype_id = B.F32 if wl.dtype == "f32" else B.F16
@@ -251,31 +250,21 @@ class Session:
             self.streams = StreamSet(n, self.device)
         return self.streams
 
-    def capture(self, mode, policy=B.ORDER_ALG2, validate=True, max_attempts=6, stream_policy=B.STREAMS_ALG1):
-        """Capture a graph.  Parallel graphs are validated before they are handed out: the
-        graph runtime has been seen to drop single dependencies of irregular DAGs
-        (depending on node order and allocation addresses), so the captured graph is
-        replayed once over poisoned outputs and must reproduce the sequential graph's
-        result bit for bit; otherwise it is rebuilt, then rebuilt with other node orders.
-        `self.capture_log` records what happened."""
+    def capture(self, mode, policy=B.ORDER_ALG2, stream_policy=B.STREAMS_ALG1):
+        """Schedule (parallel modes) and capture a graph.  The library validates a multi-stream
+        graph before it returns it; `self.capture_log` records how (kind, instances built)."""
         if mode == B.SEQUENTIAL:
             st = self.make_streams(1)
             exe = B.opara_capture(self.dag, st.handles[:1], mode)
             self.execs.append(exe)
             return exe
-        attempts = [policy, policy, policy] + [p for p in (B.ORDER_TOPO, B.ORDER_LEVEL, B.ORDER_LEAST_DEMAND)
-                                               if p != policy]
-        for i, pol in enumerate(attempts[:max_attempts]):
-            _, ns, _, _ = self.schedule(pol, stream_policy)
-            st = self.make_streams(max(ns, 1))
-            exe = B.opara_capture(self.dag, st.handles[:ns], mode)
-            if not validate or self.device is None or self._matches_sequential(exe):
-                self.execs.append(exe)
-                self.capture_log.append(dict(mode=mode, requested_policy=policy, used_policy=pol, attempts=i + 1))
-                return exe
-            B.opara_exec_destroy(exe)
-        raise RuntimeError("no captured parallel graph reproduced the sequential result: "
-                           "the graph runtime keeps dropping dependencies of this DAG")
+        _, ns, _, _ = self.schedule(policy, stream_policy)
+        st = self.make_streams(max(ns, 1))
+        exe = B.opara_capture(self.dag, st.handles[:ns], mode)
+        kind, attempts = B.opara_exec_validation(exe)
+        self.capture_log.append(dict(mode=mode, policy=policy, validation=kind, attempts=attempts))
+        self.execs.append(exe)
+        return exe
 
     def capture_persistent(self, policy=B.ORDER_ALG2, n_workgroups=0):
         """Capture the whole DAG as one persistent kernel (work items in launch-queue order,
@@ -291,38 +280,6 @@ class Session:
         self._workspaces.append(ws)
         self.execs.append(exe)
         return exe
-
-    def capture_best(self, probe_replays=30):
-        """Capture the sequential graph, the multi-stream graph and the persistent executor
-        (under the Alg. 2 and the wave-by-wave work-item order), time `probe_replays` replays of
-        each and return (executor, name, {name: median microseconds}).  Which one wins depends
-        on the DAG: operator parallelism pays only where branch work exceeds what a
-        synchronisation costs on this runtime (paper Eq. 3), so chains of large operators are
-        best left to the sequential graph."""
-        import time
-        h = self.make_streams(1)
-        handle, ts = h.handles[0], h.torch_streams[0]
-        cands = {"sequential_graph": lambda: self.capture(B.SEQUENTIAL),
-                 "multi_stream_graph": lambda: self.capture(B.PARALLEL),
-                 "persistent_alg2": lambda: self.capture_persistent(policy=B.ORDER_ALG2),
-                 "persistent_level": lambda: self.capture_persistent(policy=B.ORDER_LEVEL)}
-        exes, med = {}, {}
-        for name, make in cands.items():
-            exe = exes[name] = make()
-            for _ in range(5):
-                B.opara_replay(exe, handle)
-            ts.synchronize()
-            lat = []
-            for _ in range(probe_replays):
-                t0 = time.perf_counter()
-                B.opara_replay(exe, handle)
-                ts.synchronize()
-                lat.append((time.perf_counter() - t0) * 1e6)
-            med[name] = float(np.median(lat))
-            if name.startswith("persistent") and self.persistent_status(exe) != 0:
-                med[name] = float("inf")           # a wait ran out: not a candidate
-        best = min(med, key=med.get)
-        return exes[best], best, med
 
     def persistent_trace(self, exe):
         """Replay once with the in-kernel timeline on.  Returns an int64 array [tiles, 5]:
@@ -350,20 +307,6 @@ class Session:
 
     def persistent_reset(self, exe, spin_limit=0):
         B.opara_persistent_reset(exe, self.make_streams(1).handles[0], spin_limit)
-
-    def _matches_sequential(self, exe):
-        import torch
-        if self._seq_reference is None:
-            seq = B.opara_capture(self.dag, self.make_streams(1).handles[:1], B.SEQUENTIAL)
-            self.replay(seq)
-            self._seq_reference = [t.contiguous().clone() for t in self.out_dev]
-            B.opara_exec_destroy(seq)
-        bits = torch.int32 if self.wl.dtype == "f32" else torch.int16
-        for t in self.out_dev:
-            t.fill_(float("nan"))
-        torch.cuda.synchronize()
-        self.replay(exe)
-        return all(torch.equal(t.contiguous().view(bits), r.view(bits)) for t, r in zip(self.out_dev, self._seq_reference))
 
     def replay(self, exe, sync=True):
         import torch

@@ -167,6 +167,29 @@ def test_zero_copy_concat_dag_matches_oracle_scheduler(builder, kw):
         s.close()
 
 
+def _capture_status(session, mode):
+    """opara_capture with made-up stream handles: only what is decided before the first HIP call."""
+    _, ns, _, _ = session.schedule()
+    handles = (C.c_void_p * ns)(*[0x1000 + 16 * i for i in range(ns)])
+    out = C.c_void_p()
+    return B.load().opara_capture(session.dag, handles, ns, mode, C.byref(out)), B.opara_last_error()
+
+
+@pytest.mark.parametrize("builder,zero_copy", [(googlenet_like, True), (inception_v3_like, True), (nasnet_like, False),
+                                               (bert_base_like, False), (random_wide_dag, False)])
+def test_stream_capture_is_refused_outside_fork_join_plans(builder, zero_copy):
+    """Stream capture crashed the host process for plans whose streams wait on each other
+    repeatedly (the zero-copy GoogLeNet-like chain of blocks among them); the library refuses
+    those before it touches the runtime.  No GPU is needed to see the refusal."""
+    s = Session(builder(), device=None, zero_copy_concat=zero_copy)
+    try:
+        rc, msg = _capture_status(s, B.PARALLEL_CAPTURE)
+        assert rc == B.EUNSUPPORTED, (rc, msg)
+        assert "fork-join" in msg or "one root and one sink" in msg
+    finally:
+        s.close()
+
+
 def test_dependency_only_predecessors_are_validated():
     descs = chain_descs(3, [[-1], [0], [-1]])
     descs[2].n_deps = 2

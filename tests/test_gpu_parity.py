@@ -29,7 +29,8 @@ def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlie
                 s.replay(exe)
                 assert s.persistent_status(exe) == 0, f"{wl.name} [{mode}]: a wait inside the kernel ran out"
             else:
-                exe = s.capture({"seq": B.SEQUENTIAL, "par": B.PARALLEL, "capture": B.PARALLEL_CAPTURE}[mode])
+                exe = s.capture({"seq": B.SEQUENTIAL, "par": B.PARALLEL, "capture": B.PARALLEL_CAPTURE,
+                                 "pruned": B.PARALLEL_PRUNED}[mode])
                 s.replay(exe)
             problems = compare_all(s, ref, outlier_frac=outlier_frac)
             assert not problems, f"{wl.name} [{mode}]: " + "; ".join(problems[:4])
@@ -162,22 +163,6 @@ def test_deep_contractions_take_the_quad_coalesced_kernels():
                          f"igemm_{dtype}_quad64x4"], names        # 128 tiles of 64 x 64
 
 
-def test_capture_best_picks_a_working_executor():
-    """The autotuned capture returns one of the executors, with its timings, and that executor reproduces the oracle."""
-    from paper_2312_10351_amd.runtime import Session
-    for wl in (inception_block(), bert_base_like(layers=2)):
-        ref = executor.run_dag(wl)
-        s = Session(wl)
-        try:
-            exe, name, med = s.capture_best(probe_replays=10)
-            assert name in med and len(med) == 4 and med[name] == min(med.values())
-            s.clear_outputs()
-            s.replay(exe)
-            assert not compare_all(s, ref, outlier_frac=1e-3), name
-        finally:
-            s.close()
-
-
 def test_inception_block_fp32_all_modes():
     wl = inception_block()
     sinks = run_modes(wl, modes=("eager", "seq", "par"))
@@ -269,14 +254,14 @@ def test_random_wide_dag_full_size():
     wl = random_wide_dag()
     ref = executor.run_dag(wl)
     assert max(float(np.abs(a.astype(np.float64)).max()) for a in ref.values()) < 1e4
-    sinks = run_modes(wl, modes=("seq", "par"), ref=ref, literal=True, outlier_frac=1e-3)
-    assert sinks["seq"] == sinks["par"]
+    sinks = run_modes(wl, modes=("seq", "par", "pruned"), ref=ref, literal=True, outlier_frac=1e-3)
+    assert sinks["seq"] == sinks["par"] == sinks["pruned"]
 
 
 def test_parallel_graph_honours_every_dependency_under_all_orders():
     """Irregular DAG, every launch-order policy: a replay over NaN-poisoned outputs must
-    reproduce the sequential graph bit for bit (Session.capture rebuilds a graph whose
-    replay does not; the log says how often that was needed)."""
+    reproduce the sequential graph bit for bit.  opara_capture has validated the instance
+    it returned (marker kernels in place); the log says how many instances it built."""
     import torch
     wl = random_small_dag(7, n_ops=150, max_width=10)
     s = Session(wl)
@@ -294,6 +279,8 @@ def test_parallel_graph_honours_every_dependency_under_all_orders():
                 s.replay(exe)
                 assert all(torch.equal(t.view(torch.int16), r.view(torch.int16)) for t, r in zip(s.out_dev, ref))
         assert len(s.capture_log) == len(B.ORDER_POLICY_NAMES)
+        assert all(c["validation"] in (B.VALIDATED_IN_PLACE, B.SCREENED_ON_TWIN) and 1 <= c["attempts"] <= 4
+                   for c in s.capture_log), s.capture_log
     finally:
         s.close()
 
@@ -318,7 +305,8 @@ def test_graph_structure_and_replay_determinism():
         same_stream_pairs = n - ns
         assert nodes == n and edges == same_stream_pairs + len(syncs)
         assert B.opara_verify_dependencies(s.dag, s.streams.handles[0]) == 0    # marker-kernel self-check
-        assert s.capture_log and s.capture_log[0]["attempts"] == 1          # validated against the sequential graph
+        assert s.capture_log[0]["validation"] in (B.VALIDATED_IN_PLACE, B.SCREENED_ON_TWIN)   # checked inside the library
+        assert B.opara_exec_validation(seq) == (B.NOT_VALIDATED, 0)
         s.replay(par)
         first = [s.output(v).tobytes() for v in range(n)]
         for _ in range(3):
