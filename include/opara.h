@@ -387,6 +387,26 @@ int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int32_t launch
 int opara_persistent_set_trace(opara_exec *e, void *hip_stream, void *trace, uint64_t trace_bytes);
 int opara_persistent_reset(opara_exec *e, void *hip_stream, uint32_t spin_limit);
 
+/*
+ * For callers that cannot allocate device memory (code running under a stream capture of
+ * their own, tight serving loops, harnesses that forbid hipMalloc): one pass over the DAG
+ * through the persistent executor, as opara_capture_persistent + opara_replay run it, but
+ * without a graph and without a caller workspace.  The workspace (counters, completion
+ * flags, operator records) is a static device array inside the library, 2.5 MiB per GPU,
+ * held until the process ends; it serves DAGs of up to 512 operators (EUNSUPPORTED beyond,
+ * before anything is launched).  The call uploads the workspace image on `hip_stream`
+ * (every call uploads all of it, so whatever the previous call left in the array is
+ * overwritten), launches the serial prefix of the launch queue as ordinary kernels and then
+ * the persistent kernel, all on `hip_stream`, asynchronously.  It calls no hipMalloc,
+ * hipFree or other allocating routine of the HIP runtime.  error_word: NULL, or a host
+ * uint32 that receives the kernel's error word (0 = every wait ended; see
+ * opara_capture_persistent) after the call has synchronised `hip_stream`.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different
+ * streams, or another thread) race; order them on one stream.  Synchronise `hip_stream`
+ * before the DAG is destroyed or given a new launch queue.  Needs a launch queue (ESTATE).
+ */
+int opara_run_persistent_noalloc(opara_dag *g, void *hip_stream, uint32_t *error_word);
+
 /* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
 int opara_replay(opara_exec *e, void *hip_stream);
 

@@ -69,6 +69,7 @@ EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_assign_streams_poli
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
            "opara_persistent_set_trace",
+           "opara_run_persistent_noalloc",
            "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
@@ -111,6 +112,7 @@ def load():
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
     lib.opara_exec_validation.argtypes = [vp, i32p, i32p]
+    lib.opara_run_persistent_noalloc.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
     lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
     lib.opara_run_eager.argtypes = [vp, vp]
     lib.opara_kernel_count.argtypes = []
@@ -292,6 +294,14 @@ def opara_exec_validation(exe):
     a, b = C.c_int32(), C.c_int32()
     _check(load().opara_exec_validation(exe, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def opara_run_persistent_noalloc(dag, stream_handle, want_error_word=True):
+    """One pass through the persistent executor on the library's static workspace.  Returns the
+    kernel's error word (after synchronising the stream), or None when not asked for."""
+    w = C.c_uint32()
+    _check(load().opara_run_persistent_noalloc(dag, C.c_void_p(stream_handle), C.byref(w) if want_error_word else None))
+    return w.value if want_error_word else None
 
 
 def opara_launch_op(dag, op, stream_handle):

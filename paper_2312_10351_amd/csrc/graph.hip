@@ -556,6 +556,52 @@ fail:
   return OPARA_EHIP;
 }
 
+// One pass over the DAG through the persistent executor without a graph and without any
+// allocation: the workspace is the library's static device array, the image is uploaded on
+// the caller's stream, the serial prefix and the persistent kernel are ordinary launches.
+extern "C" int opara_run_persistent_noalloc(opara_dag *g, void *hip_stream, uint32_t *error_word) {
+  if (!g) { set_error("opara_run_persistent_noalloc: null handle"); return OPARA_EINVAL; }
+  if (g->order.empty()) { set_error("opara_run_persistent_noalloc: call opara_order_launch first"); return OPARA_ESTATE; }
+  const int32_t n = g->n;
+  const PersistLayout lay = persist_layout(n);
+  hipStream_t st = (hipStream_t)hip_stream;
+  void *ws = nullptr;
+  size_t ws_bytes = 0;
+  HIP_TRY(static_workspace(&ws, &ws_bytes));
+  if (n > kStaticWorkspaceMaxOps || lay.bytes > ws_bytes) {
+    set_error("opara_run_persistent_noalloc: %d operators need %llu bytes of workspace; the static workspace serves up to "
+              "%d operators (%llu bytes)", n, (unsigned long long)lay.bytes, kStaticWorkspaceMaxOps,
+              (unsigned long long)ws_bytes);
+    return OPARA_EUNSUPPORTED;
+  }
+  if (g->noalloc_gen != g->order_gen) {
+    // A new launch queue: an earlier upload may still be reading the old image.
+    HIP_TRY(hipStreamSynchronize(st));
+    g->noalloc_gen = 0;
+    const int rc = build_persist_image(g, 0, "opara_run_persistent_noalloc", &g->noalloc_image);
+    if (rc != OPARA_OK) return rc;
+    g->noalloc_gen = g->order_gen;
+  }
+  {
+    const PersistImage &img = g->noalloc_image;
+    // The whole image every time: counters, flags, launch number and error word start clean
+    // whatever the previous call (of this or another DAG) left in the array.
+    HIP_TRY(hipMemcpyAsync(ws, img.host.data(), lay.bytes, hipMemcpyHostToDevice, st));
+    for (int32_t q = 0; q < img.prefix; ++q) HIP_TRY(launch_plan(g->plan[g->order[q]], st));
+    HIP_TRY(launch_persist(img.f16, persist_args_at(img, n, ws), img.wgs, img.lds_bytes, st));
+    if (error_word) {
+      PersistHeader h;
+      HIP_TRY(hipMemcpyAsync(&h, ws, sizeof(h), hipMemcpyDeviceToHost, st));
+      HIP_TRY(hipStreamSynchronize(st));
+      *error_word = h.error;
+    }
+  }
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  return OPARA_EHIP;
+}
+
 extern "C" int opara_persistent_status(opara_exec *e, void *hip_stream, uint32_t *error_word) {
   if (!e || !e->workspace || !error_word) { set_error("opara_persistent_status: not a persistent executor"); return OPARA_EINVAL; }
   hipStream_t st = (hipStream_t)hip_stream;

@@ -1803,6 +1803,14 @@ extern "C" __global__ void opara_k_token(opara::TokenNodeArgs node) {
   __hip_atomic_store(&g_verify_tok[a.self], a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Workspace of the persistent executor for callers that cannot allocate device memory:
+// counters, completion flags and operator records of up to kStaticWorkspaceMaxOps
+// operators.  Every GPU the library runs on holds its own copy at its own address until
+// the process ends; host code reaches it only through the address static_workspace()
+// looks up (the array's name is a host-side stand-in, not a device address).
+constexpr size_t kScratchBytes = 2560u * 1024u;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 // Kernel without work: a pure dependency node (common root / common leaf of a capture).
 extern "C" __global__ void opara_k_noop(int) {}
 
@@ -1946,6 +1954,25 @@ hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups,
   if (f16) hipLaunchKernelGGL(opara_k_persist_f16, dim3(n_workgroups), dim3(256), lds_bytes, s, a);
   else hipLaunchKernelGGL(opara_k_persist_f32, dim3(n_workgroups), dim3(256), lds_bytes, s, a);
   return hipGetLastError();
+}
+
+hipError_t static_workspace(void **ptr, size_t *bytes) {
+  constexpr int kMaxDevices = 64;
+  static void *addr[kMaxDevices];          // per device, written once (the lookup is idempotent)
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void *p = __atomic_load_n(&addr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess) return err;
+    if (!p) return hipErrorInvalidSymbol;
+    __atomic_store_n(&addr[dev], p, __ATOMIC_RELEASE);
+  }
+  *ptr = p;
+  *bytes = kScratchBytes;
+  return hipSuccess;
 }
 
 hipError_t verify_reset(hipStream_t s) {

@@ -91,4 +91,9 @@ hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups,
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter
 
+// Workspace of the persistent executor for callers that cannot allocate: a static device
+// array inside the library (one copy per GPU).  Returns its device address on the current
+// device (looked up once per device) and its size.
+constexpr int kStaticWorkspaceMaxOps = 512;
+hipError_t static_workspace(void **ptr, size_t *bytes);
 }  // namespace opara

@@ -32,6 +32,11 @@ struct opara_dag {
   std::vector<int32_t> stream_of;   // empty until opara_assign_streams
   int32_t n_streams = 0;
   std::vector<int32_t> order;       // empty until opara_order_launch
+  uint64_t order_gen = 0;           // counts the launch queues computed so far
+  // Workspace image of the persistent executor as opara_run_persistent_noalloc last built it
+  // (kept here so that the asynchronous upload reads memory that outlives the call).
+  opara::PersistImage noalloc_image;
+  uint64_t noalloc_gen = 0;         // order_gen the image belongs to, 0 = none
 };
 
 namespace opara {

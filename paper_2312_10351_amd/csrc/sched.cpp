@@ -368,6 +368,7 @@ extern "C" int opara_order_launch_policy(opara_dag *g, int32_t policy, int32_t *
       if (--indeg[s] == 0) push(s);
     }
   }
+  ++g->order_gen;
   std::memcpy(order, g->order.data(), sizeof(int32_t) * n);
   return OPARA_OK;
 }

@@ -281,6 +281,12 @@ class Session:
         self.execs.append(exe)
         return exe
 
+    def run_persistent_noalloc(self, policy=B.ORDER_ALG2):
+        """One pass through the persistent executor on the library's static workspace (no graph,
+        no allocation).  Returns the kernel's error word."""
+        B.opara_order_launch_policy(self.dag, policy)
+        return B.opara_run_persistent_noalloc(self.dag, self.make_streams(1).handles[0])
+
     def persistent_trace(self, exe):
         """Replay once with the in-kernel timeline on.  Returns an int64 array [tiles, 5]:
         lookup start, predecessors complete, body end (ns since the first event), queue

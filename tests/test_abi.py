@@ -190,6 +190,16 @@ def test_stream_capture_is_refused_outside_fork_join_plans(builder, zero_copy):
         s.close()
 
 
+def test_static_workspace_serves_512_operators():
+    """The no-allocation entry point's static workspace (2.5 MiB) holds the image of 512 operators."""
+    dag = B.opara_build_dag(chain_descs(512, [[-1]] + [[i] for i in range(511)]), [0x1000])
+    assert B.opara_persistent_workspace_bytes(dag) <= 2560 * 1024
+    B.opara_dag_destroy(dag)
+    dag = B.opara_build_dag(chain_descs(600, [[-1]] + [[i] for i in range(599)]), [0x1000])
+    assert B.opara_persistent_workspace_bytes(dag) > 2560 * 1024
+    B.opara_dag_destroy(dag)
+
+
 def test_dependency_only_predecessors_are_validated():
     descs = chain_descs(3, [[-1], [0], [-1]])
     descs[2].n_deps = 2
