@@ -128,10 +128,9 @@ def bench_config(index, steps, warmup, with_kernels, zero_copy_concat=False):
     from paper_2312_10351_amd.roofline import dag_roofline, MFMA_FLOPS, HBM_BYTES_PER_S
     from workloads import build_config
     wl = build_config(index)
-    if zero_copy_concat == "auto":            # wherever a concatenation can be elided
-        from workloads import concat_elision_plan
-        zero_copy_concat = len(concat_elision_plan(wl)) > 0
-    s = Session(wl, zero_copy_concat=zero_copy_concat)
+    s = Session(wl, zero_copy_concat=bool(zero_copy_concat))
+    if zero_copy_concat == "auto":            # wherever the library finds a concatenation to remove
+        zero_copy_concat = len(s.elided) > 0
     try:
         t0 = time.perf_counter()
         so, ns = B.opara_assign_streams(s.dag)

@@ -161,6 +161,32 @@ int opara_build_dag(const opara_op_desc *ops, int32_t n_ops,
                     const opara_limits *lim, opara_dag **out);
 
 /*
+ * Zero-copy concatenation, a rewrite of the operator list applied before opara_build_dag
+ * (the paper's cost model, Sec. 3.1 Eq. 1-3, charges every operator a launch and every
+ * cross-stream dependency a synchronisation: a concatenation that only copies costs both).
+ * A CONCAT operator is removed when every one of its inputs is the whole output of a
+ * distinct CONV2D operator of the same dtype that nothing else reads (c_out == in_cols[i],
+ * batch*h_out*w_out == m, c_row_stride 0) and its readers have room for the branches in
+ * their deps lists; otherwise it stays.  In the reduced list
+ *   - each such branch writes its channel slice of the concatenation's buffer: out =
+ *     the CONCAT's out + (first channel) elements, params.c_row_stride = the CONCAT's n;
+ *     the branch's own out buffer is no longer written;
+ *   - every reader of the concatenation names a new external slot (whose pointer is the
+ *     CONCAT's out) as that input and lists the branches in deps, after the dependencies
+ *     it already had, in argument order, without repeats;
+ *   - operator ids are renumbered densely in the old order.
+ * ops[n_ops], ext_inputs[n_ext]: the full DAG as opara_build_dag would take it (host).
+ * out_ops: host array [n_ops], receives *n_out records.  new_id: host int32[n_ops], the
+ * reduced id of every operator, -1 for a removed concatenation.  ext_out: host array
+ * [n_ext + n_ops], receives the *n_ext_out external pointers of the reduced list (the
+ * first n_ext unchanged).  The buffers of removed concatenations still hold the
+ * concatenated tensors after a run.  No HIP call.  Errors: EINVAL, ENOMEM.
+ */
+int opara_elide_concats(const opara_op_desc *ops, int32_t n_ops, void *const *ext_inputs, int32_t n_ext,
+                        opara_op_desc *out_ops, int32_t *n_out, int32_t *new_id, void **ext_out,
+                        int32_t *n_ext_out);
+
+/*
  * Stream allocation, paper Algorithm 1: operators are visited in topological
  * order; an operator joins the stream of its first predecessor (argument order)
  * that no successor has joined yet, otherwise it opens a new stream.  Stream ids are

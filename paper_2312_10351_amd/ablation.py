@@ -83,13 +83,14 @@ def concat_ablation(index, replays):
     operators disappear) against explicit concatenation kernels, in all three executors."""
     from . import binding as B
     from .runtime import Session
-    from workloads import build_config, concat_elision_plan
+    from workloads import build_config
     wl = build_config(index)
-    out = {"ablation": "zero_copy_concat", "workload": wl.name, "concats": sum(o.type == "concat" for o in wl.ops),
-           "elided": len(concat_elision_plan(wl))}
+    out = {"ablation": "zero_copy_concat", "workload": wl.name, "concats": sum(o.type == "concat" for o in wl.ops)}
     for tag, zc in (("explicit", False), ("zero_copy", True)):
         s = Session(wl, zero_copy_concat=zc)
         try:
+            if zc:
+                out["elided"] = len(s.elided)
             out[tag] = {"sequential_us": replay_latency(s, s.capture(B.SEQUENTIAL), replays),
                         "multi_stream_graph_us": replay_latency(s, s.capture(B.PARALLEL), replays),
                         "persistent_us": replay_latency(s, s.capture_persistent(), replays)}

@@ -63,7 +63,7 @@ class Demand(C.Structure):
                 ("op_class", C.c_int32), ("kernel_id", C.c_int32), ("demand", C.c_uint64)]
 
 
-EXPORTS = ["opara_build_dag", "opara_assign_streams", "opara_assign_streams_policy", "opara_order_launch",
+EXPORTS = ["opara_build_dag", "opara_elide_concats", "opara_assign_streams", "opara_assign_streams_policy", "opara_order_launch",
            "opara_order_launch_policy", "opara_sync_edges", "opara_sync_edges_pruned",
            "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
@@ -89,6 +89,8 @@ def load():
     vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
     lib.opara_build_dag.argtypes = [C.POINTER(OpDesc), C.c_int32, C.POINTER(C.c_void_p), C.c_int32,
                                     C.POINTER(Limits), C.POINTER(vp)]
+    lib.opara_elide_concats.argtypes = [C.POINTER(OpDesc), C.c_int32, C.POINTER(C.c_void_p), C.c_int32,
+                                        C.POINTER(OpDesc), i32p, i32p, C.POINTER(C.c_void_p), i32p]
     lib.opara_assign_streams.argtypes = [vp, i32p, i32p]
     lib.opara_assign_streams_policy.argtypes = [vp, C.c_int32, i32p, i32p]
     lib.opara_sync_edges_pruned.argtypes = [vp, i32p, C.c_int32, i32p]
@@ -145,6 +147,26 @@ def opara_build_dag(descs, ext_ptrs, limits=None):
     lim = C.byref(limits) if limits is not None else None
     _check(load().opara_build_dag(arr, len(descs), ext, len(ext_ptrs), lim, C.byref(out)))
     return out
+
+
+def opara_elide_concats(descs, ext_ptrs):
+    """Zero-copy concatenation rewrite.  Returns (reduced descs, new_id per operator (-1 = removed),
+    external pointers of the reduced list)."""
+    n = len(descs)
+    arr = (OpDesc * max(n, 1))(*descs)
+    ext = (C.c_void_p * max(len(ext_ptrs), 1))(*ext_ptrs)
+    out = (OpDesc * max(n, 1))()
+    new_id = (C.c_int32 * max(n, 1))()
+    ext_out = (C.c_void_p * (len(ext_ptrs) + max(n, 1)))()
+    n_out, n_ext_out = C.c_int32(), C.c_int32()
+    _check(load().opara_elide_concats(arr, n, ext, len(ext_ptrs), out, C.byref(n_out), new_id, ext_out,
+                                      C.byref(n_ext_out)))
+    reduced = []
+    for i in range(n_out.value):
+        d = OpDesc()
+        C.memmove(C.byref(d), C.byref(out[i]), C.sizeof(OpDesc))
+        reduced.append(d)
+    return reduced, list(new_id)[:n], [ext_out[i] or 0 for i in range(n_ext_out.value)]
 
 
 def opara_num_ops(dag):

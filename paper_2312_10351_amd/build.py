@@ -74,7 +74,7 @@ def build(verbose=False):
     if not os.path.exists(inc) or open(inc).read() != new:
         open(inc, "w").write(new)
     objs = [k_obj, g_obj]
-    for src in ("sched.cpp", "plan.cpp"):
+    for src in ("sched.cpp", "plan.cpp", "rewrite.cpp"):
         o = os.path.join(BUILD, src.replace(".cpp", ".o"))
         _run([HIPCC, "-x", "c++", *COMMON, "-Wall", "-c", os.path.join(CSRC, src), "-o", o])
         objs.append(o)

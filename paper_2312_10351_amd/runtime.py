@@ -57,13 +57,12 @@ class Session:
         16-byte vector width and that feeds convolutions only is stored with zero
         channels appended (and the weights with matching zero taps) - a storage layout,
         the results are unchanged.
-        zero_copy_concat: a channel concatenation whose inputs are convolutions with no other
-        consumer is not executed: each branch writes its channel slice of the concatenated
-        buffer (output pixel stride = total channels) and the readers of the concatenation
-        depend on the branches directly.  The library then sees a DAG without those
-        operators: `self.lib_ops[i]` is the workload id of library operator i and
-        `self.lib_id[v]` the library id of workload operator v (None if elided).  Outputs are
-        still addressed by workload id."""
+        zero_copy_concat: the operator list goes through opara_elide_concats before the DAG is
+        built: concatenations of convolution branches are removed, each branch writes its
+        channel slice of the concatenated buffer and the readers depend on the branches.
+        `self.lib_ops[i]` is the workload id of library operator i, `self.lib_id[v]` the
+        library id of workload operator v (absent if removed), `self.elided` the removed
+        concatenations.  Outputs are still addressed by workload id."""
         self.wl = wl
         self.device = device
         self.dag = None
@@ -89,44 +88,15 @@ class Session:
         self.ext_dev = [self._upload(self._to_physical_input(a, self.ext_pad.get(i))) for i, a in enumerate(wl.ext_inputs)]
         self.out_dev = [None] * len(wl.ops)
         self.w_dev, self.b_dev = {}, {}
-        # zero-copy concatenation: shared buffers become extra external slots
-        from workloads import concat_elision_plan
-        plan = concat_elision_plan(wl) if zero_copy_concat else {}
-        self.elided = plan
-        slice_of = {}                       # producer id -> (concat id, first channel, total channels)
-        concat_slot = {}
-        for c, parts in plan.items():
-            cop = wl.ops[c]
-            total = cop.out_shape[0]
-            rows = cop.out_shape[1] * cop.out_shape[2] * wl.batch
-            buf = self._alloc(rows * total)
-            self.out_dev[c] = buf
-            concat_slot[c] = len(self.ext_dev)
-            self.ext_dev.append(buf)
-            for u, off, ch in parts:
-                slice_of[u] = (c, off, total)
-                self.out_dev[u] = buf + off * self._elsize() if isinstance(buf, int) else buf.view(rows, total)[:, off:off + ch]
-        self.lib_ops = [op.id for op in wl.ops if op.id not in plan]
-        self.lib_id = {v: i for i, v in enumerate(self.lib_ops)}
         descs = []
         for op in wl.ops:
-            if op.id in plan:
-                continue
             d = B.OpDesc()
             d.op_type = B.OP_TYPE_IDS[op.type]
             d.op_class = B.CLASS_DEFAULT if class_override is None else class_override[op.id]
             d.dtype = self.dtype_id
             d.n_inputs = len(op.inputs)
-            deps = []
             for i, u in enumerate(op.inputs):
-                if u in plan:
-                    d.inputs[i] = -(concat_slot[u] + 1)
-                    deps += [self.lib_id[p] for p, _, _ in plan[u] if self.lib_id[p] not in deps]
-                else:
-                    d.inputs[i] = self.lib_id[u] if u >= 0 else u
-            d.n_deps = len(deps)
-            for i, u in enumerate(deps):
-                d.deps[i] = u
+                d.inputs[i] = u
             if demand_override is not None:
                 d.grid_blocks, d.block_threads, d.lds_bytes, d.vgprs = demand_override[op.id]
             self._fill_params(op, d.params)
@@ -146,16 +116,39 @@ class Session:
                 self.b_dev[op.id] = self._upload(b.astype(np.float32))
                 d.weight = self._ptr(self.w_dev[op.id])
                 d.bias = self._ptr(self.b_dev[op.id])
-            if op.id in slice_of:
-                d.params.c_row_stride = slice_of[op.id][2]
-                out = self.out_dev[op.id]
-            else:
-                out = self._alloc(int(np.prod(op.out_shape)) * (wl.batch if _is_image(op) else 1))
-                self.out_dev[op.id] = out
-            d.out = self._ptr(out)
+            self.out_dev[op.id] = self._alloc(int(np.prod(op.out_shape)) * (wl.batch if _is_image(op) else 1))
+            d.out = self._ptr(self.out_dev[op.id])
             descs.append(d)
+        ext_ptrs = [self._ptr(t) for t in self.ext_dev]
+        self.elided = []                    # workload ids of the concatenations the library removed
+        self.lib_ops = list(range(len(wl.ops)))
+        if zero_copy_concat:
+            # The library decides which concatenations go and where their branches write; here
+            # only the buffers follow: a branch's output becomes a view into the concatenation's.
+            full = descs
+            descs, new_id, ext_ptrs = B.opara_elide_concats(full, ext_ptrs)
+            self.lib_ops = [v for v in range(len(wl.ops)) if new_id[v] >= 0]
+            self.elided = [v for v in range(len(wl.ops)) if new_id[v] < 0]
+            owner = {self._ptr(self.out_dev[c]): c for c in self.elided}
+            es = self._elsize()
+            for v in self.lib_ops:
+                d, before = descs[new_id[v]], full[v]
+                if d.out == before.out:
+                    continue
+                total = d.params.c_row_stride
+                c = next(c for base, c in owner.items() if base <= d.out < base + self._numel(c) * es)
+                off = (d.out - self._ptr(self.out_dev[c])) // es
+                if self.device is None:
+                    self.out_dev[v] = d.out
+                else:
+                    self.out_dev[v] = self.out_dev[c].view(-1, total)[:, off:off + d.params.c_out]
+        self.lib_id = {v: i for i, v in enumerate(self.lib_ops)}
         self.descs = descs
-        self.dag = B.opara_build_dag(descs, [self._ptr(t) for t in self.ext_dev])
+        self.dag = B.opara_build_dag(descs, ext_ptrs)
+
+    def _numel(self, op_id):
+        op = self.wl.ops[op_id]
+        return int(np.prod(op.out_shape)) * (self.wl.batch if _is_image(op) else 1)
 
     # ---- device memory (PyTorch) or fake addresses when there is no device
     def _upload(self, arr):

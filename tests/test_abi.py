@@ -140,17 +140,17 @@ def test_scheduler_matches_oracle_on_configs(builder):
 @pytest.mark.parametrize("builder,kw", [(inception_block, {}), (googlenet_like, {}), (inception_v3_like, {}),
                                         (googlenet_like, dict(batch=2))])
 def test_zero_copy_concat_dag_matches_oracle_scheduler(builder, kw):
-    """Zero-copy concatenation: the library sees the DAG without the elided concatenations,
-    readers depend on the branches through dependency-only predecessors.  Streams, launch
-    queue and synchronisation edges must be the oracle's on that reduced DAG."""
-    from workloads import concat_elision_plan, reduced_dag
+    """Zero-copy concatenation: opara_elide_concats removes the concatenations of convolution
+    branches; readers depend on the branches through dependency-only predecessors.  Which
+    operators go, and the streams, launch queue and synchronisation edges of what is left,
+    must be what the checker's own reading of the rewrite and the oracle scheduler give."""
+    from util import expected_elision
     wl = builder(**kw)
-    plan = concat_elision_plan(wl)
-    assert len(plan) >= 1 and all(wl.ops[c].type == "concat" for c in plan)
+    removed, kept, preds = expected_elision(wl)
+    assert len(removed) >= 1
     s = Session(wl, device=None, zero_copy_concat=True)
     try:
-        kept, preds = reduced_dag(wl, plan)
-        assert s.lib_ops == kept and B.opara_num_ops(s.dag) == len(kept)
+        assert s.elided == removed and s.lib_ops == kept and B.opara_num_ops(s.dag) == len(kept)
         so, ns, q, syncs = s.schedule()
         dem = B.opara_get_demands(s.dag)
         oso, ons = sched.assign_streams(preds)
@@ -158,11 +158,45 @@ def test_zero_copy_concat_dag_matches_oracle_scheduler(builder, kw):
         oq = sched.order_launch(preds, [d.op_class for d in dem], scal)
         assert (so, ns) == (oso, ons) and q == oq and syncs == sched.sync_edges(preds, so)
         assert sched.check_schedule(preds, so, q, syncs)
-        # every branch that fills a slice is a predecessor of every reader of the concatenation
-        for c, parts in plan.items():
-            readers = [op.id for op in wl.ops if c in op.inputs]
-            for r in readers:
-                assert set(s.lib_id[p] for p, _, _ in parts) <= set(preds[s.lib_id[r]])
+        # every branch that fills a slice is a predecessor of every reader of the concatenation,
+        # and writes at its channel offset with the concatenation's pixel stride
+        es = 2 if wl.dtype == "f16" else 4
+        for c in removed:
+            base, off = s._ptr(s.out_dev[c]), 0
+            for r in [op.id for op in wl.ops if c in op.inputs]:
+                assert set(s.lib_id[b] for b in wl.ops[c].inputs) <= set(preds[s.lib_id[r]])
+            for b_, shp in zip(wl.ops[c].inputs, wl.ops[c].in_shapes):
+                d = s.descs[s.lib_id[b_]]
+                assert d.out == base + off * es and d.params.c_row_stride == wl.ops[c].out_shape[0]
+                off += shp[0]
+    finally:
+        s.close()
+
+
+def test_elide_concats_leaves_other_concatenations_alone():
+    """A concatenation with a pooled branch, or whose branch has a second reader, stays; a
+    DAG without candidates comes back unchanged."""
+    b = Builder("mixed", "f16")
+    x = b.ext((16, 8, 8))
+    c1, c2 = b.conv(x, 8, 1), b.conv(x, 24, 3, pad=1)
+    p = b.pool("maxpool", x, 3, 1, 1)
+    cat_pool = b.concat_c([c1, p])               # a pooling branch: stays
+    c3, c4 = b.conv(cat_pool, 8, 1), b.conv(cat_pool, 8, 1)
+    cat_ok = b.concat_c([c3, c4])                # goes
+    c5 = b.conv(cat_ok, 16, 1)
+    cat_shared = b.concat_c([c5, c2])            # c5 is also read by the pooling below: stays
+    b.pool("avgpool", c5, 3, 1, 1)
+    b.gavgpool(cat_shared)
+    s = Session(b.build(3), device=None, zero_copy_concat=True)
+    try:
+        assert s.elided == [cat_ok]
+        d = s.descs[s.lib_id[c5]]
+        assert d.n_deps == 2 and [d.deps[0], d.deps[1]] == [s.lib_id[c3], s.lib_id[c4]] and d.inputs[0] < 0
+    finally:
+        s.close()
+    s = Session(bert_base_like(layers=1), device=None, zero_copy_concat=True)
+    try:
+        assert s.elided == [] and s.lib_ops == list(range(14))
     finally:
         s.close()
 

@@ -60,3 +60,40 @@ def compare_all(session, ref, ops=None, outlier_frac=0.0):
         if m:
             problems.append(f"op {op.id} {op.name} ({op.type}): {m}")
     return problems
+
+
+def expected_elision(wl, max_deps=8):
+    """The checker's own reading of the zero-copy rewrite, written from its definition in
+    opara.h: a channel concatenation goes when each input is the whole output of a distinct
+    convolution that nothing else reads.  Returns (removed, kept, preds): the removed
+    concatenation ids, the surviving workload ids in order, and for every survivor its
+    predecessors in reduced numbering (operator arguments, then the branches standing in for
+    each removed concatenation in argument order, no repeats)."""
+    readers = {}
+    for op in wl.ops:
+        for u in op.inputs:
+            if u >= 0:
+                readers[u] = readers.get(u, 0) + 1
+    removed = set()
+    for op in wl.ops:
+        if op.type != "concat" or op.params.get("axis") != 0:
+            continue
+        if all(u >= 0 and wl.ops[u].type == "conv2d" and readers[u] == 1 and tuple(wl.ops[u].out_shape) == tuple(s)
+               for u, s in zip(op.inputs, op.in_shapes)):
+            removed.add(op.id)
+    for op in wl.ops:       # a reader must have room for the branches in its dependency list
+        extra = sum(len(wl.ops[u].inputs) for u in op.inputs if u in removed)
+        assert extra <= max_deps, "the test DAGs stay within the dependency list"
+    kept = [op.id for op in wl.ops if op.id not in removed]
+    number = {v: i for i, v in enumerate(kept)}
+    preds = []
+    for v in kept:
+        row = []
+        for u in wl.ops[v].inputs:
+            if u >= 0 and u not in removed and number[u] not in row:
+                row.append(number[u])
+        for u in wl.ops[v].inputs:
+            if u in removed:
+                row += [number[b] for b in wl.ops[u].inputs if number[b] not in row]
+        preds.append(row)
+    return sorted(removed), kept, preds

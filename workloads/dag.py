@@ -58,53 +58,3 @@ class Workload:
     def sinks(self):
         has_succ = set(u for u, _ in self.edges())
         return [op.id for op in self.ops if op.id not in has_succ]
-
-
-def concat_elision_plan(wl):
-    """Channel concatenations whose branches can write their slices in place (zero-copy
-    concatenation): every input is the whole output of a distinct convolution that has no
-    other consumer.  Returns {concat id: [(producer id, first channel, channels), ...]}.
-    Pure graph bookkeeping; what is done with the plan is each executor's business."""
-    consumers = {}
-    for op in wl.ops:
-        for u in op.inputs:
-            if u >= 0:
-                consumers.setdefault(u, []).append(op.id)
-    plan = {}
-    for op in wl.ops:
-        if op.type != "concat" or op.params.get("axis") != 0:
-            continue
-        ok = len(set(op.inputs)) == len(op.inputs)
-        parts, off = [], 0
-        for u, shp in zip(op.inputs, op.in_shapes):
-            ok = ok and u >= 0 and wl.ops[u].type == "conv2d" and consumers.get(u) == [op.id] \
-                and tuple(wl.ops[u].out_shape) == tuple(shp)
-            parts.append((u, off, shp[0]))
-            off += shp[0]
-        ok = ok and all(tuple(wl.ops[v].in_shapes[i]) == tuple(op.out_shape)
-                        for v in consumers.get(op.id, []) for i, u in enumerate(wl.ops[v].inputs) if u == op.id)
-        if ok:
-            plan[op.id] = parts
-    return plan
-
-
-def reduced_dag(wl, plan):
-    """The DAG without the concatenations in `plan`: an operator that read such a
-    concatenation depends on its producers instead.  Returns (kept, preds): `kept[i]` is the
-    workload id of reduced operator i; `preds[i]` its predecessors in reduced numbering,
-    ordered as arguments that are operators first, then the producers standing in for each
-    elided concatenation (argument order), without repeats."""
-    kept = [op.id for op in wl.ops if op.id not in plan]
-    new_id = {v: i for i, v in enumerate(kept)}
-    preds = []
-    for v in kept:
-        op = wl.ops[v]
-        direct = [u for u in op.inputs if u >= 0 and u not in plan]
-        via = [p for u in op.inputs if u in plan for p, _, _ in plan[u]]
-        seen, row = set(), []
-        for u in direct + via:
-            if u not in seen:
-                seen.add(u)
-                row.append(new_id[u])
-        preds.append(row)
-    return kept, preds
