@@ -64,7 +64,8 @@ enum opara_op_type {
 /* Operator table of paper Sec. 3.3 (memory- vs compute-intensive operators). */
 enum opara_class { OPARA_CLASS_DEFAULT = -1, OPARA_MEM = 0, OPARA_COMP = 1 };
 enum opara_dtype { OPARA_F32 = 0, OPARA_F16 = 1 };
-enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_CAPTURE = 2, OPARA_PARALLEL_PRUNED = 3 };
+enum opara_mode  { OPARA_PARALLEL = 0, OPARA_SEQUENTIAL = 1, OPARA_PARALLEL_CAPTURE = 2, OPARA_PARALLEL_PRUNED = 3,
+                   OPARA_FUSED = 4 };
 
 enum opara_flags {
   OPARA_FLAG_RELU     = 1u,  /* CONV2D / GEMM: clamp the result at zero                    */
@@ -249,6 +250,13 @@ int opara_sync_edges(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_ed
  */
 int opara_sync_edges_pruned(const opara_dag *g, int32_t *uv, int32_t cap, int32_t *n_edges);
 
+/*
+ * Wave of every operator (host int32[n_ops]; n_waves may be NULL): 0 for an operator
+ * without predecessors, else one more than the largest wave of its predecessors.  The
+ * waves are what OPARA_FUSED launches together.  No HIP call.
+ */
+int opara_wave_of(const opara_dag *g, int32_t *wave_of, int32_t *n_waves);
+
 /* Demand records (paper Sec. 3.2) and default topological order; host arrays [n_ops]. */
 int opara_get_demands(const opara_dag *g, opara_demand *out);
 int opara_topo_order(const opara_dag *g, int32_t *order);
@@ -299,6 +307,25 @@ int32_t opara_num_ops(const opara_dag *g);
  *   OPARA_SEQUENTIAL        captures the same kernels with the same launch shapes on
  *                           hip_streams[0] alone in default topological order (the
  *                           baseline: paper Sec. 5.1, default sequential graph).
+ *   OPARA_FUSED             operator parallelism inside kernel nodes instead of between
+ *                           streams: on this runtime a dependency between streams of a
+ *                           graph costs more than a batch-1 operator (the t_overhead of
+ *                           paper Eq. 3), a dependency inside a single chain of nodes
+ *                           much less.  The launch queue is cut into waves - every
+ *                           operator whose predecessors all lie in earlier waves, in
+ *                           launch-queue order, so Alg. 2 still decides which operators
+ *                           meet on the chip and in which order their workgroups are
+ *                           dispatched.  A wave of one operator becomes an ordinary
+ *                           kernel node (the same kernel as in the other modes); a wave of
+ *                           several becomes a group node: ONE kernel whose grid is the sum
+ *                           of the members' grids, each workgroup running its operator's
+ *                           own body (at most 16 operators per node, a larger wave is
+ *                           split).  All nodes form one chain.  Needs a launch queue only
+ *                           (ESTATE); streams play no part, hip_streams is not read beyond
+ *                           the argument check.  Operators inside a group run the
+ *                           four-wavefront form of their kernel, so results can differ
+ *                           from the other modes in the last bits; they are identical from
+ *                           replay to replay.  The opara_dag must outlive the opara_exec.
  * Errors: ESTATE if assign/order were not called (parallel modes), EINVAL,
  * EUNSUPPORTED, EGRAPH, EHIP (a running capture is ended and the partial graph destroyed).
  */
@@ -432,6 +459,25 @@ int opara_persistent_reset(opara_exec *e, void *hip_stream, uint32_t spin_limit)
  * before the DAG is destroyed or given a new launch queue.  Needs a launch queue (ESTATE).
  */
 int opara_run_persistent_noalloc(opara_dag *g, void *hip_stream, uint32_t *error_word);
+
+/*
+ * Fused executor (OPARA_FUSED): the node of the chain every operator runs in (host
+ * int32[n_ops], nodes numbered in execution order), the number of nodes, and the kernel of
+ * every node (host int32[n_nodes]: a kernel id of the kernel table for a single operator,
+ * OPARA_GROUP_KERNEL_LIGHT / _HEAVY for a group node: the group kernel that holds the bodies
+ * with at most 128 vector registers, or all bodies); each may be NULL.  Operators that
+ * share a node run concurrently inside one kernel.
+ */
+enum { OPARA_GROUP_KERNEL_LIGHT = -1, OPARA_GROUP_KERNEL_HEAVY = -2 };
+int opara_fused_plan(const opara_exec *e, int32_t *node_of, int32_t *n_nodes, int32_t *node_kernel);
+/*
+ * Measurement aid: launches every node of a fused executor by itself (an ordinary launch
+ * of the node's kernel with the node's arguments) `launches` times back to back on
+ * `hip_stream`, after two untimed launches, between two HIP events on that stream, and
+ * returns the time per launch in microseconds, us[n_nodes] (host float).  Outputs are
+ * rewritten with the same values.  Synchronises the stream.
+ */
+int opara_fused_time_nodes(opara_exec *e, void *hip_stream, int32_t launches, float *us);
 
 /* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
 int opara_replay(opara_exec *e, void *hip_stream);

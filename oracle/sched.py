@@ -10,6 +10,9 @@ the product path).
   * min_streams    : the fewest streams any allocation can use - the comparison system's
     policy the paper sets Alg. 1 against (Sec. 5.2: 28 streams against 4 on GoogLeNet;
     Sec. 5.4: cubic matching against the linear greedy pass).
+  * waves          : the groups of operators that can run together once all earlier groups
+    have run (the level-synchronous schedule the paper's comparison systems use, Sec. 5.1;
+    this build launches each group as one kernel).
   * prune_syncs    : the synchronisations that remain once those implied by other
     dependencies are dropped (Sec. 3.1: every synchronisation costs t_overhead, Eq. 3).
 
@@ -162,6 +165,25 @@ def order_launch_policy(preds, op_class, demand, policy):
             if indeg[s] == 0:
                 ready.append(s)
     return q
+
+
+def waves(preds):
+    """Wave of every operator: 0 without predecessors, else 1 + the largest wave among its
+    predecessors, i.e. the length of the longest dependency chain that ends in it.  Taking,
+    again and again, every operator whose predecessors have all run yields these groups."""
+    n = len(preds)
+    wave = [None] * n
+    left = set(range(n))
+    k = 0
+    while left:
+        ready = [v for v in left if all(wave[u] is not None and wave[u] < k for u in preds[v])]
+        if not ready:
+            raise ValueError("graph has a cycle")
+        for v in ready:
+            wave[v] = k
+        left -= set(ready)
+        k += 1
+    return wave
 
 
 def sync_edges(preds, stream_of):

@@ -15,7 +15,7 @@ OP_TYPE_IDS = dict(conv2d=CONV2D, gemm=GEMM, bgemm=BGEMM, maxpool=MAXPOOL, avgpo
                    gelu=GELU, relu=RELU, add=ADD)
 CLASS_DEFAULT, MEM, COMP = -1, 0, 1
 F32, F16 = 0, 1
-PARALLEL, SEQUENTIAL, PARALLEL_CAPTURE, PARALLEL_PRUNED = 0, 1, 2, 3
+PARALLEL, SEQUENTIAL, PARALLEL_CAPTURE, PARALLEL_PRUNED, FUSED = 0, 1, 2, 3, 4
 STREAMS_ALG1, STREAMS_MIN = 0, 1
 FLAG_RELU, FLAG_B_KMAJOR = 1, 2
 (ORDER_ALG2, ORDER_ALG2_COMP_FIRST, ORDER_LEAST_DEMAND, ORDER_MOST_DEMAND, ORDER_TOPO,
@@ -65,12 +65,12 @@ class Demand(C.Structure):
 
 EXPORTS = ["opara_build_dag", "opara_elide_concats", "opara_assign_streams", "opara_assign_streams_policy", "opara_order_launch",
            "opara_order_launch_policy", "opara_sync_edges", "opara_sync_edges_pruned",
-           "opara_get_demands", "opara_topo_order", "opara_num_ops", "opara_capture",
+           "opara_get_demands", "opara_wave_of", "opara_topo_order", "opara_num_ops", "opara_capture",
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
            "opara_persistent_set_trace",
            "opara_run_persistent_noalloc",
-           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_launch_op", "opara_run_eager",
+           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_fused_plan", "opara_fused_time_nodes", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
 
@@ -98,6 +98,7 @@ def load():
     lib.opara_order_launch_policy.argtypes = [vp, C.c_int32, i32p]
     lib.opara_sync_edges.argtypes = [vp, i32p, C.c_int32, i32p]
     lib.opara_get_demands.argtypes = [vp, C.POINTER(Demand)]
+    lib.opara_wave_of.argtypes = [vp, i32p, i32p]
     lib.opara_topo_order.argtypes = [vp, i32p]
     lib.opara_num_ops.argtypes = [vp]
     lib.opara_capture.argtypes = [vp, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(vp)]
@@ -114,6 +115,8 @@ def load():
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
     lib.opara_exec_validation.argtypes = [vp, i32p, i32p]
+    lib.opara_fused_plan.argtypes = [vp, i32p, i32p, i32p]
+    lib.opara_fused_time_nodes.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_float)]
     lib.opara_run_persistent_noalloc.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
     lib.opara_launch_op.argtypes = [vp, C.c_int32, vp]
     lib.opara_run_eager.argtypes = [vp, vp]
@@ -226,6 +229,14 @@ def opara_get_demands(dag):
     return list(d)
 
 
+def opara_wave_of(dag):
+    """(wave of every operator, number of waves)."""
+    n = opara_num_ops(dag)
+    w, nw = (C.c_int32 * n)(), C.c_int32()
+    _check(load().opara_wave_of(dag, w, C.byref(nw)))
+    return list(w), nw.value
+
+
 def opara_topo_order(dag):
     n = opara_num_ops(dag)
     q = (C.c_int32 * n)()
@@ -309,6 +320,35 @@ def opara_exec_info(exe):
     a, b = C.c_int32(), C.c_int32()
     _check(load().opara_exec_info(exe, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+GROUP_KERNEL_LIGHT, GROUP_KERNEL_HEAVY = -1, -2
+
+
+def opara_fused_plan(exe, n_ops):
+    """(node of every operator, number of nodes) of a fused executor."""
+    node_of, n = (C.c_int32 * n_ops)(), C.c_int32()
+    _check(load().opara_fused_plan(exe, node_of, C.byref(n), None))
+    return list(node_of), n.value
+
+
+def opara_fused_node_kernels(exe, dtype):
+    """Kernel name of every node of a fused executor ("group_<dtype>_light/heavy" for group nodes)."""
+    n = C.c_int32()
+    _check(load().opara_fused_plan(exe, None, C.byref(n), None))
+    k = (C.c_int32 * n.value)()
+    _check(load().opara_fused_plan(exe, None, None, k))
+    return [f"group_{dtype}_light" if i == GROUP_KERNEL_LIGHT else f"group_{dtype}_heavy" if i == GROUP_KERNEL_HEAVY
+            else opara_kernel_info(i)[0] for i in k]
+
+
+def opara_fused_time_nodes(exe, stream_handle, launches):
+    """Microseconds per launch of every node of a fused executor, launched by itself."""
+    n = C.c_int32()
+    _check(load().opara_fused_plan(exe, None, C.byref(n), None))
+    us = (C.c_float * n.value)()
+    _check(load().opara_fused_time_nodes(exe, C.c_void_p(stream_handle), launches, us))
+    return list(us)
 
 
 def opara_exec_validation(exe):

@@ -7,7 +7,9 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <new>
+#include <algorithm>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 #include "launch.h"
 #include "opara_internal.h"
@@ -24,6 +26,16 @@ struct opara_exec {
   opara::PersistArgs persist_args{};   // the persistent kernel's launch: arguments, element type, LDS
   bool persist_f16 = false;
   uint32_t persist_lds = 0;
+  // fused executor only: the chain of nodes (single operators and groups) and where each operator went
+  struct FusedNode {
+    bool is_group = false, f16 = false, light = false;
+    int32_t op = -1;                     // single operator (ordinary kernel of the graph executors' plan)
+    uint32_t blocks = 0, lds = 0;
+    opara::GroupArgs ga;                 // group: the launch record
+  };
+  std::vector<FusedNode> fused;
+  std::vector<int32_t> fused_node_of;
+  const opara_dag *dag = nullptr;        // for launching single nodes again (timing aid); the DAG must outlive the exec
 };
 
 using namespace opara;
@@ -115,15 +127,127 @@ hipError_t assemble_parallel(const opara_dag *g, const std::vector<uint8_t> &kee
   return hipSuccess;
 }
 
+// Fused executor: the launch queue is cut into waves (every operator whose predecessors lie
+// in earlier waves, in queue order); a wave of one operator is an ordinary kernel node with
+// the graph executors' kernel, a wave of several becomes group nodes (one kernel whose grid
+// is the sum of the members' grids); all nodes form one chain.
+int capture_fused(opara_dag *g, opara_exec **out) {
+  if (g->order.empty()) { set_error("opara_capture: call opara_order_launch first"); return OPARA_ESTATE; }
+  const int32_t n = g->n;
+  opara_exec *e = new (std::nothrow) opara_exec();
+  if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
+  e->dag = g;
+  e->fused_node_of.assign(n, -1);
+  std::vector<int32_t> indeg(n), wave;
+  std::vector<char> done(n, 0);
+  for (int32_t v = 0; v < n; ++v) indeg[v] = g->pred_off[v + 1] - g->pred_off[v];
+  uint32_t max_lds = 0;
+  int32_t placed = 0;
+  while (placed < n) {
+    wave.clear();
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = g->order[i];
+      if (!done[v] && indeg[v] == 0) wave.push_back(v);
+    }
+    if (wave.empty()) { set_error("opara_capture: launch queue is not topological"); delete e; return OPARA_ESTATE; }
+    for (int32_t v : wave) {
+      done[v] = 1;
+      ++placed;
+      for (int32_t j = g->succ_off[v]; j < g->succ_off[v + 1]; ++j) --indeg[g->succ[j]];
+    }
+    // Operators that can share a group kernel: a 256-thread body, one element type.  The rest
+    // (none with the present kernel set) and waves of one run as ordinary kernel nodes.
+    std::vector<int32_t> members;
+    auto flush = [&]() {
+      if (members.empty()) return;
+      opara_exec::FusedNode node;
+      if (members.size() == 1) {
+        node.op = members[0];
+      } else {
+        node.is_group = true;
+        node.light = true;
+        std::memset(&node.ga, 0, sizeof node.ga);
+        node.ga.n = (int32_t)members.size();
+        int64_t end = 0;
+        for (size_t i = 0; i < members.size(); ++i) {
+          const KernelPlan &p = g->plan_group[members[i]];
+          bool light = true;
+          group_kernel_ok(p.kernel, &light);
+          node.light = node.light && light;
+          node.f16 = kernel_is_f16(p.kernel);
+          const int64_t tiles = (int64_t)p.gx * p.gy * p.gz;
+          end += (tiles + kGroupAlign - 1) / kGroupAlign * kGroupAlign;
+          node.ga.block_end[i] = (int32_t)end;
+          node.ga.kernel[i] = p.kernel;
+          node.ga.gx[i] = (int32_t)p.gx; node.ga.gy[i] = (int32_t)p.gy;
+          node.ga.tiles[i] = (int32_t)tiles;
+          node.ga.args[i] = p.args;
+          node.lds = std::max(node.lds, kKernelResources[p.kernel].lds_bytes);
+        }
+        node.lds = std::max(node.lds, 16u);
+        node.blocks = (uint32_t)end;
+        max_lds = std::max(max_lds, node.lds);
+      }
+      for (int32_t v : members) e->fused_node_of[v] = (int32_t)e->fused.size();
+      e->fused.push_back(node);
+      members.clear();
+    };
+    int64_t blocks = 0;
+    for (int32_t v : wave) {
+      const KernelPlan &p = g->plan_group[v];
+      bool light = true;
+      const int64_t tiles = (int64_t)p.gx * p.gy * p.gz;
+      const bool fits = group_kernel_ok(p.kernel, &light) && wave.size() > 1 && tiles < (1 << 24);
+      if (!fits) {                                    // on its own, before what follows it in the queue
+        flush();
+        members.push_back(v);
+        flush();
+        blocks = 0;
+        continue;
+      }
+      if (!members.empty() && (members.size() == (size_t)kGroupMaxOps || blocks + tiles > (1 << 24) ||
+                               kernel_is_f16(p.kernel) != kernel_is_f16(g->plan_group[members[0]].kernel))) {
+        flush();
+        blocks = 0;
+      }
+      members.push_back(v);
+      blocks += tiles + kGroupAlign;
+    }
+    flush();
+  }
+  {
+    hipGraphNode_t node = nullptr, last = nullptr;
+    HIP_TRY(group_prepare(std::max(max_lds, 16u)));
+    HIP_TRY(hipGraphCreate(&e->graph, 0));
+    for (const opara_exec::FusedNode &fn : e->fused) {
+      if (fn.is_group)
+        HIP_TRY(add_group_node(e->graph, fn.f16, fn.light, fn.ga, fn.blocks, fn.lds, last ? &last : nullptr, last ? 1 : 0, &node));
+      else
+        HIP_TRY(add_plan_node(e->graph, g->plan[fn.op], last ? &last : nullptr, last ? 1 : 0, &node));
+      last = node;
+    }
+    HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+    e->n_nodes = (int32_t)e->fused.size();
+    e->n_edges = e->n_nodes - 1;
+  }
+  *out = e;
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  destroy_exec(e);
+  return OPARA_EHIP;
+}
+
 }  // namespace
 
 extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_streams, int32_t mode,
                              opara_exec **out) {
-  if (!g || !hip_streams || !out || n_streams < 1 || (mode != OPARA_PARALLEL && mode != OPARA_SEQUENTIAL && mode != OPARA_PARALLEL_CAPTURE && mode != OPARA_PARALLEL_PRUNED)) {
+  if (!g || !hip_streams || !out || n_streams < 1 || mode < OPARA_PARALLEL || mode > OPARA_FUSED) {
     set_error("opara_capture: bad argument");
     return OPARA_EINVAL;
   }
   *out = nullptr;
+  if (mode == OPARA_FUSED) return capture_fused(g, out);
   const int32_t n = g->n;
   const bool parallel = mode != OPARA_SEQUENTIAL;
   if (parallel) {
@@ -698,6 +822,47 @@ extern "C" int opara_replay(opara_exec *e, void *hip_stream) {
   hipError_t err = hipGraphLaunch(e->exec, (hipStream_t)hip_stream);
   if (err != hipSuccess) { set_error("hipGraphLaunch failed: %s", hipGetErrorString(err)); return OPARA_EHIP; }
   return OPARA_OK;
+}
+
+extern "C" int opara_fused_plan(const opara_exec *e, int32_t *node_of, int32_t *n_nodes, int32_t *node_kernel) {
+  if (!e || e->fused.empty()) { set_error("opara_fused_plan: not a fused executor"); return OPARA_EINVAL; }
+  if (node_of) std::memcpy(node_of, e->fused_node_of.data(), sizeof(int32_t) * e->fused_node_of.size());
+  if (n_nodes) *n_nodes = (int32_t)e->fused.size();
+  if (node_kernel)
+    for (size_t i = 0; i < e->fused.size(); ++i) {
+      const opara_exec::FusedNode &fn = e->fused[i];
+      node_kernel[i] = fn.is_group ? (fn.light ? OPARA_GROUP_KERNEL_LIGHT : OPARA_GROUP_KERNEL_HEAVY) : e->dag->plan[fn.op].kernel;
+    }
+  return OPARA_OK;
+}
+
+extern "C" int opara_fused_time_nodes(opara_exec *e, void *hip_stream, int32_t launches, float *us) {
+  if (!e || e->fused.empty() || !us || launches < 1) { set_error("opara_fused_time_nodes: bad argument"); return OPARA_EINVAL; }
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  HIP_TRY(hipEventCreate(&t0));
+  HIP_TRY(hipEventCreate(&t1));
+  for (size_t i = 0; i < e->fused.size(); ++i) {
+    const opara_exec::FusedNode &fn = e->fused[i];
+    float ms = 0.f;
+    for (int32_t k = -2; k < launches; ++k) {       // two untimed launches first
+      if (k == 0) HIP_TRY(hipEventRecord(t0, st));
+      if (fn.is_group) HIP_TRY(launch_group(fn.f16, fn.light, fn.ga, fn.blocks, fn.lds, st));
+      else HIP_TRY(launch_plan(e->dag->plan[fn.op], st));
+    }
+    HIP_TRY(hipEventRecord(t1, st));
+    HIP_TRY(hipEventSynchronize(t1));
+    HIP_TRY(hipEventElapsedTime(&ms, t0, t1));
+    us[i] = ms * 1e3f / (float)launches;
+  }
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  if (t0) (void)hipEventDestroy(t0);
+  if (t1) (void)hipEventDestroy(t1);
+  return OPARA_EHIP;
 }
 
 extern "C" int opara_exec_validation(const opara_exec *e, int32_t *kind, int32_t *attempts) {

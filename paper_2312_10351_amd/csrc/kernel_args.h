@@ -134,6 +134,23 @@ struct KernelPlan {
   KernelArgs args;
 };
 
+// A group node: up to kGroupMaxOps mutually independent operators launched as ONE kernel
+// whose grid is the sum of their grids.  Workgroup w serves the operator i with
+// block_end[i-1] <= w < block_end[i]; each operator's range is padded to a multiple of the
+// XCD count (padding workgroups leave at once), so that tile t of an operator runs on XCD
+// t % 8 as in a launch of its own.  The record travels by value as the kernel argument.
+constexpr int kGroupMaxOps = 16;
+constexpr int kGroupAlign = 8;
+struct GroupArgs {
+  int32_t n;
+  int32_t reserved[3];
+  int32_t block_end[kGroupMaxOps];
+  int32_t kernel[kGroupMaxOps];                    // KernelId of the operator's body
+  int32_t gx[kGroupMaxOps], gy[kGroupMaxOps];     // the operator's own grid (x, y; z follows)
+  int32_t tiles[kGroupMaxOps];                     // gx * gy * gz
+  KernelArgs args[kGroupMaxOps];
+};
+
 // Tile geometry of the implicit-GEMM kernels (output columns x rows per workgroup).
 struct IgemmTile { int bn, bm, threads; };
 constexpr IgemmTile kTile128x64{128, 64, 256};   // 128 output columns x 64 rows

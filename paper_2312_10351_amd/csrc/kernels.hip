@@ -1788,6 +1788,114 @@ __device__ __forceinline__ void persist_body(const PersistArgs &pa) {
 extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f16(PersistArgs pa) { persist_body<true>(pa); }
 extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f32(PersistArgs pa) { persist_body<false>(pa); }
 
+// ---------------------------------------------------------------------------------
+// Group kernel (fused executor): one launch runs several mutually independent operators.
+// A workgroup finds its operator from the block ranges in the argument record, rebuilds
+// its position in that operator's own grid and runs the operator's ordinary body on the
+// operator's arguments, which it reads from the kernel-argument segment like any kernel
+// does.  No flags, no coherent accesses: kernel boundaries order the groups.  Two flavours
+// per element type: "light" holds the bodies that need at most 128 vector registers
+// (four wavefronts per SIMD stay resident, which the streaming bodies want), "heavy" all
+// 256-thread bodies.
+// ---------------------------------------------------------------------------------
+template <bool F16, bool LIGHT>
+__device__ __forceinline__ void group_body() {
+  // The record is the kernel's only argument and therefore starts the kernel-argument
+  // segment.  It is read in place through the segment pointer: indexing the by-value
+  // parameter with a run-time operator number would make the compiler copy all of it into
+  // private memory first.
+  typedef const GroupArgs __attribute__((address_space(4))) CGA;
+  CGA &ga = *(CGA *)__builtin_amdgcn_kernarg_segment_ptr();
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+  const int blk = (int)blockIdx.x;
+  int i = 0;
+  while (i + 1 < ga.n && blk >= ga.block_end[i]) ++i;            // uniform: a handful of scalar compares
+  i = __builtin_amdgcn_readfirstlane(i);
+  const int tile = blk - (i ? ga.block_end[i - 1] : 0);
+  if (tile >= ga.tiles[i]) return;                                 // padding of the operator's range
+  Blk b;
+  b.gx = ga.gx[i]; b.gy = ga.gy[i];
+  b.remap = true;
+  b.x = tile % b.gx;
+  const int rest = tile / b.gx;
+  b.y = rest % b.gy;
+  b.z = rest / b.gy;
+  unsigned char *lds = dyn_lds;
+#define GCASE(name, Args, call)                               \
+  case K_##name: {                                            \
+    typedef const Args __attribute__((address_space(4))) CA;  \
+    CA &a = *(CA *)&ga.args[i];                               \
+    call;                                                     \
+  } break;
+  if constexpr (F16) {
+    switch (ga.kernel[i]) {
+      GCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
+      GCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0>(a, b, lds)))
+      GCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
+      GCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
+      GCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, 0>(a, b, lds)))
+      GCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, 0>(a, b, lds)))
+      GCASE(gap_f16, GapArgs, (gap_body<half_t, 0>(a, b, lds)))
+      GCASE(layernorm_f16_wave, RowArgs, (row_cached_body<half_t, true, 64, 2, 0>(a, b, lds)))
+      GCASE(layernorm_f16_block, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, 0>(a, b, lds)))
+      GCASE(layernorm_f16_generic, RowArgs, (row_generic_body<half_t, true, 0>(a, b, lds)))
+      GCASE(softmax_f16_wave, RowArgs, (row_cached_body<half_t, false, 64, 2, 0>(a, b, lds)))
+      GCASE(softmax_f16_block, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, 0>(a, b, lds)))
+      GCASE(softmax_f16_generic, RowArgs, (row_generic_body<half_t, false, 0>(a, b, lds)))
+      GCASE(elt_f16_vec, EltArgs, (elt_body<half_t, 8, 0>(a, b, lds)))
+      GCASE(elt_f16_scalar, EltArgs, (elt_body<half_t, 1, 0>(a, b, lds)))
+      GCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, 0>(a, b, lds)))
+      GCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, 0>(a, b, lds)))
+      default:
+        if constexpr (!LIGHT) {
+          switch (ga.kernel[i]) {
+            GCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+            GCASE(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, 0>(a, b, lds)))
+            GCASE(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
+            default: break;
+          }
+        }
+        break;
+    }
+  } else {
+    switch (ga.kernel[i]) {
+      GCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
+      GCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, 0>(a, b, lds)))
+      GCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
+      GCASE(gemv_f32, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
+      GCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, 0>(a, b, lds)))
+      GCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, 0>(a, b, lds)))
+      GCASE(gap_f32, GapArgs, (gap_body<float, 0>(a, b, lds)))
+      GCASE(layernorm_f32_wave, RowArgs, (row_cached_body<float, true, 64, 2, 0>(a, b, lds)))
+      GCASE(layernorm_f32_block, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, 0>(a, b, lds)))
+      GCASE(layernorm_f32_generic, RowArgs, (row_generic_body<float, true, 0>(a, b, lds)))
+      GCASE(softmax_f32_wave, RowArgs, (row_cached_body<float, false, 64, 2, 0>(a, b, lds)))
+      GCASE(softmax_f32_block, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, 0>(a, b, lds)))
+      GCASE(softmax_f32_generic, RowArgs, (row_generic_body<float, false, 0>(a, b, lds)))
+      GCASE(elt_f32_vec, EltArgs, (elt_body<float, 4, 0>(a, b, lds)))
+      GCASE(elt_f32_scalar, EltArgs, (elt_body<float, 1, 0>(a, b, lds)))
+      GCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, 0>(a, b, lds)))
+      GCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, 0>(a, b, lds)))
+      default:
+        if constexpr (!LIGHT) {
+          switch (ga.kernel[i]) {
+            GCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+            GCASE(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, 0>(a, b, lds)))
+            GCASE(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
+            default: break;
+          }
+        }
+        break;
+    }
+  }
+#undef GCASE
+}
+
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f16_light(GroupArgs) { group_body<true, true>(); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f16_heavy(GroupArgs) { group_body<true, false>(); }
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f32_light(GroupArgs) { group_body<false, true>(); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f32_heavy(GroupArgs) { group_body<false, false>(); }
+
 // Dependency self-check: done-tokens per operator and a violation counter, in static
 // device memory (nothing is allocated).
 static __device__ int g_verify_tok[opara::kVerifyMaxOps];
@@ -1898,6 +2006,61 @@ hipError_t add_token_node(hipGraph_t graph, const TokenNodeArgs &t, const hipGra
   np.blockDim = dim3(64);
   np.kernelParams = kparams;
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+namespace {
+void *group_func(bool f16, bool light) {
+  return f16 ? (light ? (void *)opara_k_group_f16_light : (void *)opara_k_group_f16_heavy)
+             : (light ? (void *)opara_k_group_f32_light : (void *)opara_k_group_f32_heavy);
+}
+}  // namespace
+
+bool group_kernel_ok(int id, bool *light) {
+  switch (id) {
+    case K_igemm_f16_t128x64: case K_igemm_f32_t128x64: case K_igemm_f16_quad4: case K_igemm_f32_quad4:
+    case K_igemm_f16_quad64x4: case K_igemm_f32_quad64x4:
+      *light = false;
+      return true;
+    case K_igemm_f16_direct8: case K_igemm_f32_direct8: case K_igemm_f16_quad8: case K_igemm_f32_quad8:
+      return false;                       // 512-thread bodies
+    default:
+      *light = true;
+      return id >= 0 && id < K_COUNT;
+  }
+}
+
+hipError_t group_prepare(uint32_t max_lds_bytes) {
+  for (int f16 = 0; f16 < 2; ++f16)
+    for (int light = 0; light < 2; ++light) {
+      hipError_t err = hipFuncSetAttribute(group_func(f16, light), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)max_lds_bytes);
+      if (err != hipSuccess) return err;
+    }
+  return hipSuccess;
+}
+
+hipError_t add_group_node(hipGraph_t graph, bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks,
+                          uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
+  GroupArgs args = ga;
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = group_func(f16, light);
+  np.gridDim = dim3(n_blocks);
+  np.blockDim = dim3(256);
+  np.sharedMemBytes = lds_bytes;
+  np.kernelParams = kparams;
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t launch_group(bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s) {
+  if (f16) {
+    if (light) hipLaunchKernelGGL(opara_k_group_f16_light, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
+    else hipLaunchKernelGGL(opara_k_group_f16_heavy, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
+  } else {
+    if (light) hipLaunchKernelGGL(opara_k_group_f32_light, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
+    else hipLaunchKernelGGL(opara_k_group_f32_heavy, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
+  }
+  return hipGetLastError();
 }
 
 int persist_kernel_id(int id) {

@@ -13,6 +13,14 @@ hipError_t add_plan_node(hipGraph_t graph, const KernelPlan &p, const hipGraphNo
                          hipGraphNode_t *node);
 hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
 
+// Group nodes (fused executor): whether a kernel's body can run inside a group kernel at
+// all (256-thread bodies) and inside the light flavour (at most 128 vector registers).
+bool group_kernel_ok(int kernel_id, bool *light);
+hipError_t add_group_node(hipGraph_t graph, bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks,
+                          uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
+hipError_t launch_group(bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s);
+hipError_t group_prepare(uint32_t max_lds_bytes);   // raises the dynamic LDS limit of the group kernels once
+
 // Dependency self-check (see opara_verify_dependencies): a token node marks its
 // operator as done after a short delay and counts predecessors not yet marked.
 constexpr int kVerifyMaxOps = 1 << 16;

@@ -28,6 +28,7 @@ struct opara_dag {
   std::vector<int32_t> topo, tindex;
   std::vector<opara::KernelPlan> plan;          // graph executors (and the demand table)
   std::vector<opara::KernelPlan> plan_persist;  // persistent executor
+  std::vector<opara::KernelPlan> plan_group;    // inside a group node of the fused executor (256-thread bodies)
   std::vector<opara_demand> dem;
   std::vector<int32_t> stream_of;   // empty until opara_assign_streams
   int32_t n_streams = 0;
@@ -51,10 +52,12 @@ void set_error(const char *fmt, ...);
 int sync_keep_mask(const opara_dag *g, std::vector<uint8_t> *keep);
 
 // Chooses the kernel, grid and arguments for operator `v`; `in[i]` are the resolved
-// device pointers of its inputs.  `persistent` asks for the plan the persistent executor
-// runs (one workgroup size, its own hand-over point to the tiled contraction kernel); the
-// other plan is the one the graph executors launch and the demand table describes.
-// Returns an opara_status.
-int plan_op(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out);
+// device pointers of its inputs.  kPlanGraph is the plan the graph executors launch and the
+// demand table describes; kPlanPersistent the one the persistent executor runs (one
+// workgroup size, fragment-loading contractions, its own hand-over point to the tiled
+// kernel); kPlanGroup the one for operators inside a group kernel (one workgroup size,
+// quad-coalesced contractions allowed).  Returns an opara_status.
+enum { kPlanGraph = 0, kPlanPersistent = 1, kPlanGroup = 2 };
+int plan_op(const opara_op_desc &op, const void *const *in, int kind, KernelPlan *out);
 
 }  // namespace opara

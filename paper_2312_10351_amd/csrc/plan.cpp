@@ -58,7 +58,8 @@ int fail(const char *what, const opara_op_desc &op) {
   return OPARA_EINVAL;
 }
 
-int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out) {
+int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelPlan *out) {
+  const bool persistent = kind == kPlanPersistent, group = kind == kPlanGroup;
   const opara_op_params &p = op.params;
   const bool f16 = op.dtype == OPARA_F16;
   const int ve = f16 ? 8 : 4;
@@ -186,7 +187,8 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, bool persistent, 
       // Deep K on few tiles: eight wavefronts share it (latency).  With a tile or more per
       // compute unit, four: more workgroups per CU overlap better than longer ones.
       const int64_t tiles32 = (int64_t)cdiv(a.M, kDirectTile) * cdiv(a.N, kDirectTile) * batch;
-      if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= quad_four_wave_tiles()) ? 4 : 8;   // 256-byte steps
+      if (group) waves = 4;                                    // one workgroup size inside a group kernel
+      else if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= quad_four_wave_tiles()) ? 4 : 8;   // 256-byte steps
       else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
       out->kernel = ids[f16][(quad ? 2 : 0) + (waves == 8 ? 1 : 0)];
       out->gx = cdiv(a.M, kDirectTile);
@@ -319,11 +321,11 @@ int plan_concat(const opara_op_desc &op, const void *const *in, KernelPlan *out)
 
 }  // namespace
 
-int plan_op(const opara_op_desc &op, const void *const *in, bool persistent, KernelPlan *out) {
+int plan_op(const opara_op_desc &op, const void *const *in, int kind, KernelPlan *out) {
   std::memset(out, 0, sizeof *out);
   int rc;
   switch (op.op_type) {
-    case OPARA_CONV2D: case OPARA_GEMM: case OPARA_BGEMM: rc = plan_igemm(op, in, persistent, out); break;
+    case OPARA_CONV2D: case OPARA_GEMM: case OPARA_BGEMM: rc = plan_igemm(op, in, kind, out); break;
     case OPARA_MAXPOOL: case OPARA_AVGPOOL: rc = plan_pool(op, in, out); break;
     case OPARA_GAVGPOOL: rc = plan_gap(op, in, out); break;
     case OPARA_LAYERNORM: case OPARA_SOFTMAX: rc = plan_row(op, in, out); break;

@@ -139,6 +139,7 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
     // ---- kernel plan + demand record per operator
     g->plan.resize(n_ops);
     g->plan_persist.resize(n_ops);
+    g->plan_group.resize(n_ops);
     g->dem.resize(n_ops);
     for (int v = 0; v < n_ops; ++v) {
       const opara_op_desc &op = g->ops[v];
@@ -148,8 +149,9 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
         in[i] = u < 0 ? g->ext[-(int64_t)u - 1] : g->ops[u].out;
         if (!in[i]) { set_error("operator %d: input %d resolves to a null pointer", v, i); delete g; return OPARA_EINVAL; }
       }
-      rc = plan_op(op, in, false, &g->plan[v]);
-      if (rc == OPARA_OK) rc = plan_op(op, in, true, &g->plan_persist[v]);
+      rc = plan_op(op, in, kPlanGraph, &g->plan[v]);
+      if (rc == OPARA_OK) rc = plan_op(op, in, kPlanPersistent, &g->plan_persist[v]);
+      if (rc == OPARA_OK) rc = plan_op(op, in, kPlanGroup, &g->plan_group[v]);
       if (rc != OPARA_OK) { delete g; return rc; }
       const KernelPlan &p = g->plan[v];
       const KernelResource &r = kKernelResources[p.kernel];
@@ -389,6 +391,23 @@ extern "C" int opara_sync_edges(const opara_dag *g, int32_t *uv, int32_t cap, in
       ++k;
     }
   *n_edges = k;
+  return OPARA_OK;
+}
+
+// Wave of every operator: 0 for operators without predecessors, else one more than the
+// largest wave among its predecessors.  These are the groups the fused executor launches
+// together (it takes, again and again, every operator whose predecessors have all run).
+extern "C" int opara_wave_of(const opara_dag *g, int32_t *wave_of, int32_t *n_waves) {
+  if (!g || !wave_of) { set_error("opara_wave_of: null pointer"); return OPARA_EINVAL; }
+  int32_t deepest = -1;
+  for (int32_t i = 0; i < g->n; ++i) {
+    const int32_t v = g->topo[i];
+    int32_t w = 0;
+    for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) w = std::max(w, wave_of[g->pred[j]] + 1);
+    wave_of[v] = w;
+    deepest = std::max(deepest, w);
+  }
+  if (n_waves) *n_waves = deepest + 1;
   return OPARA_OK;
 }
 

@@ -246,7 +246,9 @@ class Session:
     def capture(self, mode, policy=B.ORDER_ALG2, stream_policy=B.STREAMS_ALG1):
         """Schedule (parallel modes) and capture a graph.  The library validates a multi-stream
         graph before it returns it; `self.capture_log` records how (kind, instances built)."""
-        if mode == B.SEQUENTIAL:
+        if mode in (B.SEQUENTIAL, B.FUSED):
+            if mode == B.FUSED:
+                B.opara_order_launch_policy(self.dag, policy)
             st = self.make_streams(1)
             exe = B.opara_capture(self.dag, st.handles[:1], mode)
             self.execs.append(exe)

@@ -37,11 +37,43 @@ def operator_timeline(session, exe, order):
     return rows
 
 
+def timeline_summary(session, exe):
+    """Overlap evidence from the persistent executor's own timeline (a profiler sees one
+    kernel): busy fraction of the workgroups and how many operators are in flight."""
+    from . import binding as B
+    tr = session.persistent_trace(exe)
+    _, wgs = B.opara_persistent_info(exe)
+    span = float(tr[:, 2].max() - tr[:, 0].min())
+    run = (tr[:, 2] - tr[:, 1]).astype(np.float64)
+    n_pos = int(tr[:, 3].max()) + 1
+    prefix = B.opara_persistent_prefix(exe)    # operators ahead of the kernel (ordinary kernel nodes) carry no stamps
+    ev = []
+    for p in range(prefix, n_pos):
+        m = tr[:, 3] == p
+        ev.append((float(tr[m, 1].min()), 1))
+        ev.append((float(tr[m, 2].max()), -1))
+    ev.sort()
+    cur, peak, area, last = 0, 0, 0.0, ev[0][0]
+    hist = {}
+    for t, d in ev:
+        area += cur * (t - last)
+        hist[cur] = hist.get(cur, 0.0) + (t - last)
+        last = t
+        cur += d
+        peak = max(peak, cur)
+    total = sum(hist.values()) or 1.0
+    return dict(span_us=span / 1e3, serial_prefix_operators=prefix, workgroups=wgs, work_items=int(len(tr)),
+                workgroup_busy_fraction=float(run.sum() / (span * wgs)),
+                operators_in_flight_peak=peak, operators_in_flight_mean=area / total,
+                time_share_by_operators_in_flight={str(k): round(v / total, 4) for k, v in sorted(hist.items())},
+                median_tile_us=float(np.median(run)) / 1e3,
+                median_wait_for_predecessors_us=float(np.median(tr[:, 1] - tr[:, 0])) / 1e3)
+
+
 def main():
     from . import binding as B
     from .runtime import Session
     from workloads import build_config
-    import bench
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--policy", default="alg2", choices=list(B.ORDER_POLICY_NAMES))
@@ -65,7 +97,7 @@ def main():
             print(f"| {r['pos']} | {r['op']} | {r['name']} | {r['kernel']} | {r['tiles']} | {r['first_ready_us']:.1f} | "
                   f"{r['last_published_us']:.1f} | {r['median_tile_us']:.2f} | {r['median_wait_us']:.2f} |")
         print()
-        print(json.dumps(bench.timeline_summary(s, exe)))
+        print(json.dumps(timeline_summary(s, exe)))
         if s.persistent_status(exe) != 0:
             raise SystemExit("a wait inside the kernel ran out")
     finally:

@@ -124,6 +124,7 @@ def test_scheduler_matches_oracle_on_configs(builder):
         assert q == oq
         assert syncs == osync
         assert sched.check_schedule(preds, so, q, syncs)
+        assert B.opara_wave_of(s.dag) == (sched.waves(preds), max(sched.waves(preds)) + 1)
         if builder is random_wide_dag:       # the figures the design notes quote for the 400-operator DAG
             assert (len(wl.ops), ns, len(syncs)) == (400, 182, 562)
         from oracle.executor import kahn_order
@@ -366,6 +367,7 @@ def test_order_policies_match_oracle():
             assert q == sched.order_launch_policy(preds, cls, dem, name), (trial, name, inputs)
             assert sched.check_schedule(preds, so, q, sched.sync_edges(preds, so))
         assert B.opara_order_launch_policy(dag, B.ORDER_ALG2) == B.opara_order_launch(dag)
+        assert B.opara_wave_of(dag)[0] == sched.waves(preds)
         with pytest.raises(B.OparaError):
             B.opara_order_launch_policy(dag, 17)
         B.opara_dag_destroy(dag)

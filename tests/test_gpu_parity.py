@@ -30,8 +30,13 @@ def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlie
                 assert s.persistent_status(exe) == 0, f"{wl.name} [{mode}]: a wait inside the kernel ran out"
             else:
                 exe = s.capture({"seq": B.SEQUENTIAL, "par": B.PARALLEL, "capture": B.PARALLEL_CAPTURE,
-                                 "pruned": B.PARALLEL_PRUNED}[mode])
+                                 "pruned": B.PARALLEL_PRUNED, "fused": B.FUSED}[mode])
                 s.replay(exe)
+                if mode == "fused":      # every wave is one node; operators of a wave share it
+                    node_of, n_nodes = B.opara_fused_plan(exe, len(s.lib_ops))
+                    wave_of, n_waves = B.opara_wave_of(s.dag)
+                    assert n_nodes >= n_waves and all(node_of[u] < node_of[v] for u in range(len(node_of))
+                                                      for v in range(len(node_of)) if wave_of[u] < wave_of[v])
             problems = compare_all(s, ref, outlier_frac=outlier_frac)
             assert not problems, f"{wl.name} [{mode}]: " + "; ".join(problems[:4])
             if literal and wl.dtype == "f16":   # the plain 2e-2 / 1e-2 bound, on every operator
@@ -165,9 +170,9 @@ def test_deep_contractions_take_the_quad_coalesced_kernels():
 
 def test_inception_block_fp32_all_modes():
     wl = inception_block()
-    sinks = run_modes(wl, modes=("eager", "seq", "par"))
+    sinks = run_modes(wl, modes=("eager", "seq", "par", "fused"))
     assert sinks["seq"] == sinks["par"] == sinks["eager"]   # same kernels, same bits
-    run_modes(inception_block(random_bias=True))
+    run_modes(inception_block(random_bias=True), modes=("eager", "seq", "par", "fused"))
 
 
 @pytest.mark.parametrize("builder,kw", [
@@ -175,9 +180,9 @@ def test_inception_block_fp32_all_modes():
     (inception_v3_like, {}), (inception_v3_like, {"he_init": True}), (bert_base_like, {})])
 def test_model_configs(builder, kw):
     wl = builder(**kw)
-    modes = ("seq", "par") if builder is bert_base_like else ("seq", "par", "capture")   # capture: one root only
+    modes = ("seq", "par", "fused") if builder is bert_base_like else ("seq", "par", "capture", "fused")   # capture: one root only
     sinks = run_modes(wl, modes=modes, literal=not kw.get("he_init"))
-    assert sinks["seq"] == sinks["par"] == sinks[modes[-1]]
+    assert sinks["seq"] == sinks["par"] == sinks[modes[-2]]
     if kw.get("he_init"):
         out = np.frombuffer(sinks["par"][wl.sinks()[0]], dtype=np.float16).astype(np.float64)
         assert np.abs(out).max() > 1e-2          # the scaled variant really exercises the numerics
@@ -187,7 +192,7 @@ def test_model_configs(builder, kw):
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_random_small_dags(seed, dtype):
     wl = random_small_dag(100 + seed, dtype=dtype, n_ops=50)
-    run_modes(wl, modes=("par",), outlier_frac=1e-3)
+    run_modes(wl, modes=("par", "fused"), outlier_frac=1e-3)
 
 
 @pytest.mark.parametrize("builder,kw", [
@@ -196,13 +201,14 @@ def test_random_small_dags(seed, dtype):
 def test_image_batches(builder, kw):
     """Batch > 1 (batch sweep of the paper's Sec. 5.2): [B][H][W][C] activations, M = B*H*W rows."""
     wl = builder(**kw)
-    sinks = run_modes(wl, modes=("seq", "par"))
+    sinks = run_modes(wl, modes=("seq", "par", "fused"))
     assert sinks["seq"] == sinks["par"]
 
 
 @pytest.mark.parametrize("builder,kw", [
     (inception_block, dict(random_bias=True)), (inception_block, dict(dtype="f16", batch=3, random_bias=True)),
-    (googlenet_like, dict(he_init=True)), (inception_v3_like, dict(he_init=True)), (googlenet_like, dict(batch=2))])
+    (googlenet_like, dict(he_init=True)), (inception_v3_like, dict(he_init=True)), (googlenet_like, dict(batch=2)),
+    (googlenet_like, {})])       # the last one is the benchmark's headline combination
 def test_zero_copy_concat(builder, kw):
     """Branches write their channel slices of the concatenated tensor in place; the
     concatenation operators are not executed.  Every operator output, the elided
@@ -211,8 +217,9 @@ def test_zero_copy_concat(builder, kw):
     wl = builder(**kw)
     ref = executor.run_dag(wl)
     plain = run_modes(wl, modes=("seq",), ref=ref, outlier_frac=1e-3)
-    fused = run_modes(wl, modes=("eager", "seq", "par", "persist"), ref=ref, outlier_frac=1e-3, zero_copy_concat=True)
-    assert fused["seq"] == fused["par"] == fused["eager"] == plain["seq"]
+    inplace = run_modes(wl, modes=("eager", "seq", "par", "persist", "fused"), ref=ref, outlier_frac=1e-3,
+                        zero_copy_concat=True, literal=not kw)
+    assert inplace["seq"] == inplace["par"] == inplace["eager"] == plain["seq"]
 
 
 @pytest.mark.parametrize("make", [lambda: googlenet_like(he_init=True), lambda: bert_base_like(),
@@ -246,7 +253,7 @@ def test_nasnet_cell_like_dag(kw):
     """A second irregular workload (skip connections across cells, element-wise sums of
     image tensors), in every executor."""
     wl = nasnet_like(**kw)
-    sinks = run_modes(wl, modes=("eager", "seq", "par", "persist"), outlier_frac=1e-3)
+    sinks = run_modes(wl, modes=("eager", "seq", "par", "persist", "fused"), outlier_frac=1e-3)
     assert sinks["seq"] == sinks["par"] == sinks["eager"]
 
 
@@ -254,7 +261,7 @@ def test_random_wide_dag_full_size():
     wl = random_wide_dag()
     ref = executor.run_dag(wl)
     assert max(float(np.abs(a.astype(np.float64)).max()) for a in ref.values()) < 1e4
-    sinks = run_modes(wl, modes=("seq", "par", "pruned"), ref=ref, literal=True, outlier_frac=1e-3)
+    sinks = run_modes(wl, modes=("seq", "par", "pruned", "fused"), ref=ref, literal=True, outlier_frac=1e-3)
     assert sinks["seq"] == sinks["par"] == sinks["pruned"]
 
 
@@ -281,6 +288,47 @@ def test_parallel_graph_honours_every_dependency_under_all_orders():
         assert len(s.capture_log) == len(B.ORDER_POLICY_NAMES)
         assert all(c["validation"] in (B.VALIDATED_IN_PLACE, B.SCREENED_ON_TWIN) and 1 <= c["attempts"] <= 4
                    for c in s.capture_log), s.capture_log
+    finally:
+        s.close()
+
+
+def test_fused_executor_splits_wide_waves_and_keeps_single_operators_as_kernel_nodes():
+    """A wave of 40 independent operators (contractions, pooling, row-wise and element-wise
+    ones, heavy and light bodies mixed) becomes three group nodes of at most 16; the chain of
+    single operators after it stays ordinary kernel nodes; replays are deterministic."""
+    b = Builder("wide_wave", "f16")
+    x = b.ext((24, 19, 17))
+    m = b.ext((70, 1096))
+    outs = []
+    for i in range(10):
+        outs.append(b.conv(x, 16 + 8 * i, 3 if i % 2 else 1, pad=1 if i % 2 else 0))      # quad (K = 216 * 2 B < 1 KiB: direct) and direct bodies
+        outs.append(b.gemm(m, 70, 1096, 40 + 8 * i))                                         # deep K: quad-coalesced body
+        outs.append(b.pool("maxpool" if i % 2 else "avgpool", x, 3, 1, 1))
+        outs.append(b.rowwise(("gelu", "layernorm", "softmax", "relu", "add")[i % 5], [m], 70, 1096, {"eps": 1e-5}))
+    tail = b.concat_c([outs[0], outs[4]])
+    tail = b.conv(tail, 32, 1)
+    b.gavgpool(tail)
+    wl = b.build(21, random_bias=True, w_std=0.1)
+    ref = executor.run_dag(wl)
+    s = Session(wl)
+    try:
+        exe = s.capture(B.FUSED)
+        node_of, n_nodes = B.opara_fused_plan(exe, len(wl.ops))
+        assert n_nodes == 3 + 3 and sorted(set(node_of[:40])) == [0, 1, 2] and node_of[40:] == [3, 4, 5]
+        assert max(node_of[:40].count(k) for k in range(3)) == 16
+        assert B.opara_exec_info(exe) == (6, 5)
+        first = None
+        for _ in range(3):
+            for t in s.out_dev:
+                t.fill_(float("nan"))
+            s.replay(exe)
+            assert not compare_all(s, ref)
+            bits = [s.output(v).tobytes() for v in range(len(wl.ops))]
+            assert first is None or bits == first
+            first = bits
+        us = B.opara_fused_time_nodes(exe, s.make_streams(1).handles[0], 5)
+        assert len(us) == 6 and all(0 < u < 1e4 for u in us)
+        assert not compare_all(s, ref)
     finally:
         s.close()
 

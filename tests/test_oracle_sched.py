@@ -362,3 +362,31 @@ def test_level_order_is_depth_then_trace_order(seed):
     assert sorted(q) == list(range(n))
     keys = [(int(depth[v]), tidx[v]) for v in q]
     assert keys == sorted(keys)
+
+
+# ---------------------------------------------------------------- waves
+def test_waves_hand_worked_and_longest_chain():
+    # the hand-worked DAG above: 0, 1 | 2, 3, 4 | 5, 6
+    assert sched.waves(HAND_PREDS) == [0, 0, 1, 1, 1, 2, 2]
+    # ids that do not follow depth: 0 -> 3 -> 1 -> 5, 2 -> 4 -> 5
+    assert sched.waves([[], [3], [], [0], [2], [1, 4]]) == [0, 2, 0, 1, 1, 3]
+    assert sched.waves([[]] + [[i] for i in range(6)]) == list(range(7))        # a chain
+    assert sched.waves([[], [], []]) == [0, 0, 0]
+    with pytest.raises(ValueError):
+        sched.waves([[1], [0]])
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_waves_are_longest_path_lengths(seed):
+    rng = np.random.default_rng(5000 + seed)
+    n = int(rng.integers(2, 40))
+    preds = random_preds(rng, n, p_root=0.3)
+    a = np.zeros((n, n), dtype=np.int64)
+    for v, ps in enumerate(preds):
+        for u in ps:
+            a[u, v] = 1
+    depth, p = np.zeros(n, dtype=int), np.eye(n, dtype=np.int64)
+    for k in range(1, n):
+        p = np.minimum(p @ a, 1)
+        depth[p.sum(0) > 0] = k
+    assert sched.waves(preds) == [int(d) for d in depth]
