@@ -207,7 +207,7 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
             e["launches"] += 1; e["time_us"] += t; e["flops"] += work[v][0]; e["bytes"] += work[v][1]
         dom = max(by, key=lambda k: by[k]["time_us"])
         res["dominant_graph_kernel"] = kernel_block(dom, by[dom]["flops"], by[dom]["bytes"], by[dom]["launches"],
-                                                    by[dom]["time_us"], wl.dtype, traffic.get((wl.name, dom)))
+                                                    by[dom]["time_us"], wl.dtype, traffic.get((wl.name, dom + tag)))
         res["sum_isolated_us"] = float(sum(t_iso))
         finish = [0.0] * len(wl.ops)
         for op in wl.ops:                     # a removed concatenation takes no time of its own

@@ -390,6 +390,18 @@ int opara_verify_dependencies(opara_dag *g, void *hip_stream, int32_t *n_violati
  * beside other kernels, may run at the same time: they share the device's workgroup slots,
  * and a launch whose workgroups are not all resident yet makes progress as the others
  * finish (its waits are long, not unbounded).
+ * Assumptions the hand-off rests on (hardware behaviour of gfx950, not the language memory
+ * model): results are written with device-coherent write-through stores (sc1), a wavefront
+ * waits for its own stores with s_waitcnt vmcnt(0) before the workgroup's thread 0 adds to
+ * the operator's counter with a RELAXED device-scope atomic, and a consumer invalidates its
+ * caches after it has seen the flag.  The stores of the other wavefronts are ordered before
+ * the counter update by the workgroup barrier and their own vmcnt wait, not by a release
+ * fence (a release at device scope writes back the whole L2 of the XCD, about 200 ns per
+ * workgroup, serialised).  Under the HIP memory model this is a data race; on gfx950 a
+ * store that vmcnt has retired has reached the memory side all XCDs share.  The second
+ * assumption is residency: work items are dealt to workgroups statically, so the launch
+ * makes progress only while all its workgroups are resident; co-running kernels that hold
+ * compute units for long can make a wait run out (reported, see below).
  * Errors: ESTATE without a launch queue, EINVAL (workspace), EUNSUPPORTED (more than 8
  * predecessors or 65535 tiles per operator, more than about 2,600 operators, mixed
  * element types), EHIP.
@@ -479,7 +491,13 @@ int opara_fused_plan(const opara_exec *e, int32_t *node_of, int32_t *n_nodes, in
  */
 int opara_fused_time_nodes(opara_exec *e, void *hip_stream, int32_t launches, float *us);
 
-/* One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises. */
+/*
+ * One hipGraphLaunch on `hip_stream`; asynchronous, the caller synchronises.  The status
+ * covers the launch only.  A persistent executor reports a wait that ran out inside its
+ * kernel through its sticky error word, not here: a caller that must know reads
+ * opara_persistent_status after the replays it cares about (once the word is set, every
+ * later replay leaves its outputs unwritten until opara_persistent_reset).
+ */
 int opara_replay(opara_exec *e, void *hip_stream);
 
 /* Nodes and dependency edges of the captured graph (host int32 each). */

@@ -2,7 +2,6 @@
 // The demand record of an operator (paper Sec. 3.2: threads, shared memory and
 // registers of one block; Sec. 2.3: number of blocks) follows from the plan made
 // here plus the static resources of the chosen kernel.
-#include <cstdlib>
 #include <cstring>
 #include "opara_internal.h"
 
@@ -15,40 +14,6 @@ const KernelResource kKernelResources[K_COUNT] = {
 };
 
 namespace {
-
-// Tuning knobs (read once): OPARA_QUAD_MIN_ROW_BYTES, OPARA_QUAD_FOUR_WAVE_TILES, OPARA_QUAD64_MIN_TILES; OPARA_TILED_MIN_FLOPS moves the hand-over point between the
-// latency-oriented and the tiled contraction kernel.
-int64_t quad_min_row_bytes() {
-  static const int64_t v = [] {
-    const char *e = std::getenv("OPARA_QUAD_MIN_ROW_BYTES");
-    return e ? (int64_t)std::atoll(e) : kQuadMinRowBytes;
-  }();
-  return v;
-}
-
-int64_t quad_four_wave_tiles() {
-  static const int64_t v = [] {
-    const char *e = std::getenv("OPARA_QUAD_FOUR_WAVE_TILES");
-    return e ? (int64_t)std::atoll(e) : (int64_t)kQuadFourWaveTiles;
-  }();
-  return v;
-}
-
-int quad64_min_tiles() {
-  static const int v = [] {
-    const char *e = std::getenv("OPARA_QUAD64_MIN_TILES");
-    return e ? std::atoi(e) : kQuad64MinTiles;
-  }();
-  return v;
-}
-
-double tiled_min_flops() {
-  static const double v = [] {
-    const char *e = std::getenv("OPARA_TILED_MIN_FLOPS");
-    return e ? std::atof(e) : kTiledMinFlops;
-  }();
-  return v;
-}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline uint32_t cdiv(int64_t a, int64_t b) { return (uint32_t)((a + b - 1) / b); }
@@ -146,8 +111,8 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelP
     const bool fits32 = (int64_t)a.M * a.lda < lim32 && (int64_t)a.N * a.ldb < lim32 &&
                         (!a.gather || (int64_t)(a.M / a.HoWo) * a.img_stride < lim32);
     const bool quad64 = !persistent && !a.b_kmajor && !a.gather && fits32 && flops < kQuad64MaxFlops &&
-                        (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * batch >= quad64_min_tiles() &&
-                        (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
+                        (int64_t)cdiv(a.M, 64) * cdiv(a.N, 64) * batch >= kQuad64MinTiles &&
+                        (int64_t)a.K * (f16 ? 2 : 4) >= kQuadMinRowBytes;
     if (quad64) {
       // GEMM-shaped and at least one 64 x 64 tile per compute unit: the quad-coalesced
       // kernel whose wavefronts each multiply a whole tile over their share of K.
@@ -163,7 +128,7 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelP
       out->args.igemm = a;
       return OPARA_OK;
     }
-    if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= (persistent ? kTiledMinFlopsPersistent : tiled_min_flops())) {
+    if (!a.b_kmajor && tiles >= kTiledMinTiles && flops >= (persistent ? kTiledMinFlopsPersistent : kTiledMinFlops)) {
       // Throughput-oriented tiled kernel (128 output columns x 64 rows per workgroup):
       // pays once the contraction is heavy and has enough tiles to occupy the device.
       t = kTile128x64;
@@ -182,13 +147,13 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelP
       // variant that loads MFMA fragments as they are.
       static const int ids[2][4] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_quad4, K_igemm_f32_quad8},
                                     {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_quad4, K_igemm_f16_quad8}};
-      const bool quad = !persistent && (int64_t)a.K * (f16 ? 2 : 4) >= quad_min_row_bytes();
+      const bool quad = !persistent && (int64_t)a.K * (f16 ? 2 : 4) >= kQuadMinRowBytes;
       int waves;
       // Deep K on few tiles: eight wavefronts share it (latency).  With a tile or more per
       // compute unit, four: more workgroups per CU overlap better than longer ones.
       const int64_t tiles32 = (int64_t)cdiv(a.M, kDirectTile) * cdiv(a.N, kDirectTile) * batch;
       if (group) waves = 4;                                    // one workgroup size inside a group kernel
-      else if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= quad_four_wave_tiles()) ? 4 : 8;   // 256-byte steps
+      else if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= (int64_t)kQuadFourWaveTiles) ? 4 : 8;   // 256-byte steps
       else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
       out->kernel = ids[f16][(quad ? 2 : 0) + (waves == 8 ? 1 : 0)];
       out->gx = cdiv(a.M, kDirectTile);

@@ -7,7 +7,7 @@ from paper_2312_10351_amd import binding as B
 from paper_2312_10351_amd.runtime import Session
 from workloads import (Builder, inception_block, googlenet_like, inception_v3_like, bert_base_like,
                        random_wide_dag, random_small_dag, nasnet_like)
-from util import compare_all, literal_fp16_bound_ok
+from util import compare_all, literal_fp16_bound_ok, literal_fp16_miss_fraction
 
 pytestmark = pytest.mark.gpu
 
@@ -39,9 +39,15 @@ def run_modes(wl, modes=("eager", "seq", "par"), ref=None, literal=False, outlie
                                                       for v in range(len(node_of)) if wave_of[u] < wave_of[v])
             problems = compare_all(s, ref, outlier_frac=outlier_frac)
             assert not problems, f"{wl.name} [{mode}]: " + "; ".join(problems[:4])
-            if literal and wl.dtype == "f16":   # the plain 2e-2 / 1e-2 bound, on every operator
+            if literal is True and wl.dtype == "f16":   # the plain 2e-2 / 1e-2 bound, on every operator
                 bad = [op.name for op in wl.ops if not literal_fp16_bound_ok(s.output(op.id), ref[op.id])]
                 assert not bad, f"{wl.name} [{mode}]: plain fp16 bound violated at {bad[:5]}"
+            elif literal and wl.dtype == "f16":
+                # Tensors of RMS 2-13 (He-initialised networks): the plain bound on all but the stated
+                # share of every operator's elements (the scale-aware bound above holds on all of them).
+                bad = [(op.name, f) for op in wl.ops
+                       for f in [literal_fp16_miss_fraction(s.output(op.id), ref[op.id])] if f > literal]
+                assert not bad, f"{wl.name} [{mode}]: plain fp16 bound missed by more than {literal:g} of the elements at {bad[:5]}"
             sinks[mode] = {v: s.output(v).tobytes() for v in wl.sinks()}
     finally:
         s.close()
@@ -181,7 +187,7 @@ def test_inception_block_fp32_all_modes():
 def test_model_configs(builder, kw):
     wl = builder(**kw)
     modes = ("seq", "par", "fused") if builder is bert_base_like else ("seq", "par", "capture", "fused")   # capture: one root only
-    sinks = run_modes(wl, modes=modes, literal=not kw.get("he_init"))
+    sinks = run_modes(wl, modes=modes, literal=2e-3 if kw.get("he_init") else True)
     assert sinks["seq"] == sinks["par"] == sinks[modes[-2]]
     if kw.get("he_init"):
         out = np.frombuffer(sinks["par"][wl.sinks()[0]], dtype=np.float16).astype(np.float64)
@@ -218,7 +224,7 @@ def test_zero_copy_concat(builder, kw):
     ref = executor.run_dag(wl)
     plain = run_modes(wl, modes=("seq",), ref=ref, outlier_frac=1e-3)
     inplace = run_modes(wl, modes=("eager", "seq", "par", "persist", "fused"), ref=ref, outlier_frac=1e-3,
-                        zero_copy_concat=True, literal=not kw)
+                        zero_copy_concat=True, literal=True if not kw else 2e-3 if kw.get("he_init") else False)
     assert inplace["seq"] == inplace["par"] == inplace["eager"] == plain["seq"]
 
 
@@ -253,7 +259,8 @@ def test_nasnet_cell_like_dag(kw):
     """A second irregular workload (skip connections across cells, element-wise sums of
     image tensors), in every executor."""
     wl = nasnet_like(**kw)
-    sinks = run_modes(wl, modes=("eager", "seq", "par", "persist", "fused"), outlier_frac=1e-3)
+    sinks = run_modes(wl, modes=("eager", "seq", "par", "persist", "fused"), outlier_frac=1e-3,
+                      literal=2e-3 if kw.get("dtype", "f16") == "f16" else False)
     assert sinks["seq"] == sinks["par"] == sinks["eager"]
 
 

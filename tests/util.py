@@ -26,6 +26,13 @@ def literal_fp16_bound_ok(got, ref):
     return bool((np.abs(g - o) <= 1e-2 + 2e-2 * np.abs(o)).all())
 
 
+def literal_fp16_miss_fraction(got, ref):
+    """Share of elements outside the plain bound |g - o| <= 1e-2 + 2e-2 |o|."""
+    g = np.asarray(got, dtype=np.float64)
+    o = np.asarray(ref, dtype=np.float64)
+    return float((np.abs(g - o) > 1e-2 + 2e-2 * np.abs(o)).mean()) if o.size else 0.0
+
+
 def mismatch(got, ref, dtype, outlier_frac=0.0):
     """None if `got` matches the oracle `ref` within tolerance, else a description.
     outlier_frac: share of elements that may miss the scale-aware bound as long as they
