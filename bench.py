@@ -2,11 +2,12 @@
 """Benchmark: batch-1 DAG latency of operator-parallel graph replay on one MI355X.
 
 A step is one replay of the whole captured DAG (launch order + single hipGraph) with inputs
-and weights resident in HBM.  Four executors replay the same kernel bodies on the same
+and weights resident in HBM.  Five executors replay the same kernel bodies on the same
 buffers, each as ONE hipGraph:
   sequential graph     one stream, default topological order (the baseline, paper Sec. 5.1)
   multi-stream graph   Alg. 1 streams, Alg. 2 order, dependencies as graph edges (the paper's design)
   persistent executor  one kernel, Alg. 2 order, dependencies as completion flags
+  chained executor     the same without a work-item loop: one tile per workgroup, blocks in queue order
   fused executor       the launch queue cut into waves, a wave of several operators is one kernel
 The headline value is the fastest operator-parallel executor (named in config.mode) on the
 GoogLeNet-like fp16 DAG; the other configs are reported beside it, each with its own
@@ -170,12 +171,14 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
             probe[pol] = time_replays(s, s.capture_persistent(policy=pol), 40, 10)["median_us"]
         per_policy = min(probe, key=probe.get)
         per = s.capture_persistent(policy=per_policy)
+        chn = s.capture_chained()
         runs = {"sequential": time_replays(s, seq, steps, warmup), "multi_stream_graph": time_replays(s, par, steps, warmup),
-                "persistent": time_replays(s, per, steps, warmup), "fused": time_replays(s, fus, steps, warmup)}
-        if s.persistent_status(per) != 0:
-            raise RuntimeError("persistent executor: a wait ran out")
+                "persistent": time_replays(s, per, steps, warmup), "chained": time_replays(s, chn, steps, warmup),
+                "fused": time_replays(s, fus, steps, warmup)}
+        if s.persistent_status(per) != 0 or s.persistent_status(chn) != 0:
+            raise RuntimeError("persistent / chained executor: a wait ran out")
         r_seq = runs["sequential"]
-        best = min(("multi_stream_graph", "persistent", "fused"), key=lambda k: runs[k]["median_us"])
+        best = min(("multi_stream_graph", "persistent", "chained", "fused"), key=lambda k: runs[k]["median_us"])
         r_best = runs[best]
         roof = dag_roofline(wl)
         node_of, n_nodes = B.opara_fused_plan(fus, len(s.lib_ops))
@@ -186,11 +189,13 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
                    assign_streams_ms=(t1 - t0) * 1e3, order_launch_ms=(t2 - t1) * 1e3, capture_ms=(t4 - t3) * 1e3,
                    sequential_and_fused_capture_ms=(t5 - t4) * 1e3, persistent_queue=B.ORDER_POLICY_NAMES[per_policy],
                    persistent_queue_probe_us={B.ORDER_POLICY_NAMES[k]: v for k, v in probe.items()},
-                   sequential=r_seq, parallel=runs["multi_stream_graph"], persistent=runs["persistent"], fused=runs["fused"],
+                   sequential=r_seq, parallel=runs["multi_stream_graph"], persistent=runs["persistent"], chained=runs["chained"],
+                   fused=runs["fused"], chained_blocks=B.opara_persistent_info(chn)[0],
                    persistent_timeline=timeline_summary(s, per), best_mode=best, best=r_best,
                    speedup_vs_sequential=r_seq["median_us"] / r_best["median_us"],
                    speedup_multi_stream_graph=r_seq["median_us"] / runs["multi_stream_graph"]["median_us"],
                    speedup_persistent=r_seq["median_us"] / runs["persistent"]["median_us"],
+                   speedup_chained=r_seq["median_us"] / runs["chained"]["median_us"],
                    speedup_fused=r_seq["median_us"] / runs["fused"]["median_us"],
                    dag_flops=roof["flops"], dag_bytes=roof["bytes"],
                    roofline_us=dict(flops=roof["t_flops_us"], bytes=roof["t_bytes_us"], critical_path=roof["t_cp_us"],
@@ -232,16 +237,17 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
             res["fused_node_kernels"] = {k: dict(launches=v["launches"], avg_us=v["time_us"] / v["launches"], operators=v["ops"])
                                          for k, v in fk.items()}
             res["fused_sum_of_node_times_us"] = float(sum(us))
-        elif best == "persistent":
+        elif best in ("persistent", "chained"):
             # one kernel runs the DAG behind its serial prefix: launched alone between HIP events on the
             # launch stream; its work is the operators inside it
-            t_us = B.opara_persistent_time_kernel(per, st.handles[0], steps)
-            if s.persistent_status(per) != 0:
-                raise RuntimeError("persistent executor: a wait ran out")
-            queue = B.opara_order_launch_policy(s.dag, per_policy)
-            inside = queue[B.opara_persistent_prefix(per):]
-            kern = kernel_block("persist_" + wl.dtype, sum(work[v][0] for v in inside), sum(work[v][1] for v in inside), 1,
-                                t_us, wl.dtype, traffic.get((wl.name, "persist_" + wl.dtype + tag)),
+            one = per if best == "persistent" else chn
+            t_us = B.opara_persistent_time_kernel(one, st.handles[0], steps)
+            if s.persistent_status(one) != 0:
+                raise RuntimeError(best + " executor: a wait ran out")
+            queue = B.opara_order_launch_policy(s.dag, per_policy if best == "persistent" else B.ORDER_ALG2)
+            inside = queue[B.opara_persistent_prefix(one):]
+            kern = kernel_block(("persist_" if best == "persistent" else "chain_") + wl.dtype, sum(work[v][0] for v in inside), sum(work[v][1] for v in inside), 1,
+                                t_us, wl.dtype, traffic.get((wl.name, ("persist_" if best == "persistent" else "chain_") + wl.dtype + tag)),
                                 operators_in_kernel=len(inside))
         else:
             kern = res["dominant_graph_kernel"]
@@ -250,7 +256,7 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
         if cpu_budget_s > 0:
             block, ref = oracle_pass(wl, cpu_budget_s, one_thread=index == 1)
             s.clear_outputs()
-            s.replay({"multi_stream_graph": par, "persistent": per, "fused": fus}[best])
+            s.replay({"multi_stream_graph": par, "persistent": per, "chained": chn, "fused": fus}[best])
             worst, ok = 0.0, True
             for v in wl.sinks():
                 g, o = s.output(v).astype(np.float64), ref[v].astype(np.float64)
@@ -289,6 +295,8 @@ def calibration_copy(reps=10, mib=64):
 MODE_TEXT = {
     "persistent": "persistent executor: one hipGraph replay = the serial stem as kernel nodes, then one kernel for the rest "
                   "(work items in launch-queue order, dependencies as completion flags)",
+    "chained": "chained executor: one hipGraph replay = the serial stem as kernel nodes, then one launch whose workgroups each run "
+               "one tile behind a wait for their operator's predecessors (blocks in launch-queue order)",
     "multi_stream_graph": "multi-stream hipGraph replay (Alg. 1 streams, Alg. 2 launch order)",
     "fused": "fused executor: one hipGraph replay = a chain of kernel nodes, one per wave of the Alg. 2 launch queue; a wave of "
              "several operators is ONE kernel whose grid is the sum of their grids"}
@@ -335,10 +343,11 @@ def main():
                    "mode": MODE_TEXT[head["best_mode"]]},
         "throughput_inferences_per_s": 1e6 / head["best"]["back_to_back_us"],
         "speedup_vs_sequential_hipgraph": head["speedup_vs_sequential"],
-        "speedup_by_executor": {k: head["speedup_" + k] for k in ("multi_stream_graph", "persistent", "fused")},
+        "speedup_by_executor": {k: head["speedup_" + k] for k in ("multi_stream_graph", "persistent", "chained", "fused")},
         "speedup_vs_sequential_hipgraph_all_configs": {r["workload"]: dict(best=r["best_mode"], speedup=r["speedup_vs_sequential"],
                                                                             multi_stream_graph=r["speedup_multi_stream_graph"],
-                                                                            persistent=r["speedup_persistent"], fused=r["speedup_fused"])
+                                                                            persistent=r["speedup_persistent"], chained=r["speedup_chained"],
+                                                                            fused=r["speedup_fused"])
                                                        for r in [head] + others},
         "dag_roofline_fraction": head["roofline_fraction"],
         "roofline": head["roofline"],

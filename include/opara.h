@@ -453,6 +453,29 @@ int opara_persistent_set_trace(opara_exec *e, void *hip_stream, void *trace, uin
 int opara_persistent_reset(opara_exec *e, void *hip_stream, uint32_t spin_limit);
 
 /*
+ * Chained executor: the persistent executor without its work-item loop.  ONE launch whose
+ * grid is the sum of the operators' grids in launch-queue order (the serial prefix of the
+ * queue again as ordinary kernel nodes ahead of it); a workgroup runs exactly one tile: it
+ * looks up its operator, waits until the completion flags of the operator's predecessors
+ * carry this launch's number, runs the tile with the operator's own body and counts it; the
+ * workgroup that counts an operator's last tile raises the operator's flags.  The hand-off
+ * is the persistent executor's (same assumptions about write-through stores, stated there).
+ * What differs: workgroups are dispatched in increasing block order and every predecessor's
+ * blocks come before its consumers' blocks, so the lowest unfinished block can always run:
+ * the launch drains with whatever number of workgroups the device holds at a time, beside
+ * other kernels too (no residency assumption).  And because a body is straight-line code
+ * behind the wait, the kernel holds every 256-thread body, the quad-coalesced contractions
+ * included (kernel plan: the one of OPARA_FUSED's group nodes).
+ * workspace: device memory, caller-owned, 256-byte aligned, at least
+ * opara_chained_workspace_bytes() bytes, exclusively this executor's until it is destroyed.
+ * opara_persistent_status / _reset / _info / _prefix / _time_kernel / _set_trace serve a
+ * chained executor too (work items = workgroups = blocks of the launch; 32 bytes of trace
+ * per block).  Errors: as opara_capture_persistent.  Replay with opara_replay.
+ */
+int opara_chained_workspace_bytes(const opara_dag *g, uint64_t *bytes);
+int opara_capture_chained(opara_dag *g, void *workspace, uint64_t workspace_bytes, opara_exec **out);
+
+/*
  * For callers that cannot allocate device memory (code running under a stream capture of
  * their own, tight serving loops, harnesses that forbid hipMalloc): one pass over the DAG
  * through the persistent executor, as opara_capture_persistent + opara_replay run it, but

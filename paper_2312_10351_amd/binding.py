@@ -69,7 +69,7 @@ EXPORTS = ["opara_build_dag", "opara_elide_concats", "opara_assign_streams", "op
            "opara_persistent_workspace_bytes", "opara_capture_persistent", "opara_persistent_status",
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
            "opara_persistent_set_trace",
-           "opara_run_persistent_noalloc",
+           "opara_run_persistent_noalloc", "opara_chained_workspace_bytes", "opara_capture_chained",
            "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_fused_plan", "opara_fused_time_nodes", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
@@ -106,6 +106,8 @@ def load():
     lib.opara_persistent_workspace_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.opara_capture_persistent.argtypes = [vp, vp, C.c_uint64, C.c_int32, C.POINTER(vp)]
     lib.opara_persistent_status.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
+    lib.opara_chained_workspace_bytes.argtypes = [vp, C.POINTER(C.c_uint64)]
+    lib.opara_capture_chained.argtypes = [vp, vp, C.c_uint64, C.POINTER(vp)]
     lib.opara_persistent_reset.argtypes = [vp, vp, C.c_uint32]
     lib.opara_persistent_info.argtypes = [vp, i32p, i32p]
     lib.opara_persistent_plan.argtypes = [vp, i32p, i32p]
@@ -261,6 +263,18 @@ def opara_capture_persistent(dag, workspace_ptr, workspace_bytes, n_workgroups=0
     out = C.c_void_p()
     _check(load().opara_capture_persistent(dag, C.c_void_p(workspace_ptr), workspace_bytes, n_workgroups,
                                            C.byref(out)))
+    return out
+
+
+def opara_chained_workspace_bytes(dag):
+    n = C.c_uint64()
+    _check(load().opara_chained_workspace_bytes(dag, C.byref(n)))
+    return n.value
+
+
+def opara_capture_chained(dag, workspace_ptr, workspace_bytes):
+    out = C.c_void_p()
+    _check(load().opara_capture_chained(dag, C.c_void_p(workspace_ptr), workspace_bytes, C.byref(out)))
     return out
 
 

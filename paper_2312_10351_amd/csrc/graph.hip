@@ -26,6 +26,9 @@ struct opara_exec {
   opara::PersistArgs persist_args{};   // the persistent kernel's launch: arguments, element type, LDS
   bool persist_f16 = false;
   uint32_t persist_lds = 0;
+  // chained executor (the loop-free form of the persistent one): shares the fields above
+  bool chained = false, chain_light = false;
+  opara::ChainArgs chain_args{};
   // fused executor only: the chain of nodes (single operators and groups) and where each operator went
   struct FusedNode {
     bool is_group = false, f16 = false, light = false;
@@ -726,6 +729,137 @@ fail:
   return OPARA_EHIP;
 }
 
+namespace {
+
+struct ChainLayout { size_t block_op, rec, bytes; };
+
+// Header, counters and flags sit where the persistent executor has them (persist_layout),
+// so status, reset and tracing serve both; then the block table and the operator records.
+ChainLayout chain_layout(int32_t n, int64_t total_blocks) {
+  ChainLayout l;
+  l.block_op = persist_layout(n).begin;
+  l.rec = align_up(l.block_op + sizeof(int32_t) * (size_t)total_blocks, 256);
+  l.bytes = align_up(l.rec + sizeof(ChainRec) * (size_t)n, 256);
+  return l;
+}
+
+int64_t chain_blocks_of(const KernelPlan &p) {
+  const int64_t t = (int64_t)p.gx * p.gy * p.gz;
+  return (t + kGroupAlign - 1) / kGroupAlign * kGroupAlign;
+}
+
+}  // namespace
+
+extern "C" int opara_chained_workspace_bytes(const opara_dag *g, uint64_t *bytes) {
+  if (!g || !bytes) { set_error("opara_chained_workspace_bytes: null pointer"); return OPARA_EINVAL; }
+  int64_t total = 0;
+  for (int32_t v = 0; v < g->n; ++v) total += chain_blocks_of(g->plan_group[v]);
+  *bytes = chain_layout(g->n, total).bytes;
+  return OPARA_OK;
+}
+
+extern "C" int opara_capture_chained(opara_dag *g, void *workspace, uint64_t workspace_bytes, opara_exec **out) {
+  if (!g || !workspace || !out) { set_error("opara_capture_chained: bad argument"); return OPARA_EINVAL; }
+  *out = nullptr;
+  if (g->order.empty()) { set_error("opara_capture_chained: call opara_order_launch first"); return OPARA_ESTATE; }
+  const int32_t n = g->n;
+  const int32_t prefix = serial_prefix(g);
+  const int32_t np_ops = n - prefix;
+  if (n > 65535) { set_error("opara_capture_chained: more than 65535 operators"); return OPARA_EUNSUPPORTED; }
+  int64_t total = 0;
+  for (int32_t i = 0; i < np_ops; ++i) total += chain_blocks_of(g->plan_group[g->order[prefix + i]]);
+  if (total > (int64_t)1 << 30) { set_error("opara_capture_chained: %lld workgroups in one launch", (long long)total); return OPARA_EUNSUPPORTED; }
+  const ChainLayout lay = chain_layout(n, total);
+  const PersistLayout play = persist_layout(n);
+  if (workspace_bytes < lay.bytes || ((uintptr_t)workspace & 255u)) {
+    set_error("opara_capture_chained: workspace of %llu bytes (need %llu, 256-byte aligned)",
+              (unsigned long long)workspace_bytes, (unsigned long long)lay.bytes);
+    return OPARA_EINVAL;
+  }
+  std::vector<unsigned char> host(lay.bytes, 0);
+  PersistHeader *hdr = (PersistHeader *)host.data();
+  hdr->spin_limit = kPersistDefaultSpinLimit;
+  hdr->epoch = 1;
+  int32_t *block_op = (int32_t *)(host.data() + lay.block_op);
+  ChainRec *rec = (ChainRec *)(host.data() + lay.rec);
+  std::vector<int32_t> pos_of(n, -1);
+  std::vector<char> in_prefix((size_t)n, 0);
+  for (int32_t q = 0; q < prefix; ++q) in_prefix[g->order[q]] = 1;
+  bool all_light = true, f16 = false;
+  uint32_t lds = 16;
+  int64_t at = 0;
+  for (int32_t i = 0; i < np_ops; ++i) {
+    const int32_t v = g->order[prefix + i];
+    const KernelPlan &p = g->plan_group[v];
+    bool light = true;
+    if (!chain_kernel_ok(p.kernel, &light)) { set_error("opara_capture_chained: operator %d has no 256-thread kernel", v); return OPARA_EUNSUPPORTED; }
+    if (i == 0) f16 = kernel_is_f16(p.kernel);
+    if (kernel_is_f16(p.kernel) != f16) { set_error("opara_capture_chained: mixed element types"); return OPARA_EUNSUPPORTED; }
+    all_light = all_light && light;
+    lds = std::max(lds, kKernelResources[p.kernel].lds_bytes);
+    pos_of[v] = i;
+    const int64_t tiles = (int64_t)p.gx * p.gy * p.gz, blocks = chain_blocks_of(p);
+    ChainRec &r = rec[i];
+    r.kernel = p.kernel + (g->ops[v].op_type == OPARA_BGEMM ? kPersistActivationB : 0);
+    r.gx = (int32_t)p.gx; r.gy = (int32_t)p.gy; r.gz = (int32_t)p.gz;
+    r.begin = (int32_t)at;
+    r.tiles = (int32_t)tiles;
+    r.args = p.args;
+    for (int64_t b = 0; b < blocks; ++b) block_op[at + b] = b < tiles ? i : -1;
+    at += blocks;
+    const int32_t np = g->pred_off[v + 1] - g->pred_off[v];
+    if (np > kPersistMaxPreds) { set_error("opara_capture_chained: operator %d has %d predecessors (limit %d)", v, np, kPersistMaxPreds); return OPARA_EUNSUPPORTED; }
+    int32_t kept = 0;
+    for (int32_t j = 0; j < np; ++j) {
+      const int32_t pu = g->pred[g->pred_off[v] + j];
+      if (pos_of[pu] >= 0) { r.preds[kept++] = (uint16_t)pos_of[pu]; continue; }
+      if (!in_prefix[pu]) { set_error("opara_capture_chained: launch queue is not topological"); return OPARA_ESTATE; }
+    }
+    r.n_preds = (uint16_t)kept;
+  }
+  opara_exec *e = new (std::nothrow) opara_exec();
+  if (!e) { set_error("out of memory"); return OPARA_ENOMEM; }
+  {
+    HIP_TRY(chain_max_lds(lds));
+    HIP_TRY(hipMemcpy(workspace, host.data(), lay.bytes, hipMemcpyHostToDevice));
+    unsigned char *ws = (unsigned char *)workspace;
+    ChainArgs ca;
+    ca.hdr = (PersistHeader *)ws;
+    ca.done = (uint32_t *)(ws + play.done);
+    ca.flags = (uint32_t *)(ws + play.flags);
+    ca.block_op = (const int32_t *)(ws + lay.block_op);
+    ca.rec = (const ChainRec *)(ws + lay.rec);
+    ca.n = np_ops;
+    ca.total = (int32_t)total;
+    hipGraphNode_t node = nullptr, last = nullptr;
+    HIP_TRY(hipGraphCreate(&e->graph, 0));
+    for (int32_t q = 0; q < prefix; ++q) {
+      HIP_TRY(add_plan_node(e->graph, g->plan[g->order[q]], last ? &last : nullptr, last ? 1 : 0, &node));
+      last = node;
+    }
+    HIP_TRY(add_chain_node(e->graph, f16, all_light, ca, lds, last ? &last : nullptr, last ? 1 : 0, &node));
+    HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
+    e->n_nodes = prefix + 1;
+    e->n_edges = prefix;
+    e->workspace = workspace;
+    e->persist_prefix = prefix;
+    e->persist_f16 = f16;
+    e->persist_lds = lds;
+    e->persist_ops = n;
+    e->persist_items = (int32_t)total;
+    e->persist_workgroups = (int32_t)total;
+    e->chained = true;
+    e->chain_light = all_light;
+    e->chain_args = ca;
+  }
+  *out = e;
+  return OPARA_OK;
+fail:
+  (void)hipGetLastError();
+  destroy_exec(e);
+  return OPARA_EHIP;
+}
+
 extern "C" int opara_persistent_status(opara_exec *e, void *hip_stream, uint32_t *error_word) {
   if (!e || !e->workspace || !error_word) { set_error("opara_persistent_status: not a persistent executor"); return OPARA_EINVAL; }
   hipStream_t st = (hipStream_t)hip_stream;
@@ -761,8 +895,10 @@ extern "C" int opara_persistent_time_kernel(opara_exec *e, void *hip_stream, int
   HIP_TRY(hipEventCreate(&t1));
   HIP_TRY(hipStreamSynchronize(st));
   HIP_TRY(hipEventRecord(t0, st));
-  for (int32_t i = 0; i < launches; ++i)
-    HIP_TRY(launch_persist(e->persist_f16, e->persist_args, (uint32_t)e->persist_workgroups, e->persist_lds, st));
+  for (int32_t i = 0; i < launches; ++i) {
+    if (e->chained) HIP_TRY(launch_chain(e->persist_f16, e->chain_light, e->chain_args, e->persist_lds, st));
+    else HIP_TRY(launch_persist(e->persist_f16, e->persist_args, (uint32_t)e->persist_workgroups, e->persist_lds, st));
+  }
   HIP_TRY(hipEventRecord(t1, st));
   HIP_TRY(hipEventSynchronize(t1));
   HIP_TRY(hipEventElapsedTime(&ms, t0, t1));

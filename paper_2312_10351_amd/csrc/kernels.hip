@@ -1896,6 +1896,183 @@ extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f16_heavy(Gro
 extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f32_light(GroupArgs) { group_body<false, true>(); }
 extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f32_heavy(GroupArgs) { group_body<false, false>(); }
 
+// ---------------------------------------------------------------------------------
+// Chained executor: every workgroup runs one tile of one operator behind a wait for the
+// operator's predecessors (see ChainArgs).  Same hand-off as the persistent kernel (results
+// through device-coherent stores, completion counters and replicated flags, one cache
+// invalidate per workgroup), but no loop: a body is straight-line code behind the wait, so
+// nothing is hoisted across bodies, the quad-coalesced contractions can be held, and the
+// launch does not depend on all its workgroups being resident at once.
+// ---------------------------------------------------------------------------------
+template <bool F16, bool LIGHT>
+__device__ __forceinline__ void chain_body(const ChainArgs &pa) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
+  __shared__ int32_t ctl[2];
+  typedef const int32_t __attribute__((address_space(4))) *CI;
+  const int blk = (int)blockIdx.x;
+  const int pos = __builtin_amdgcn_readfirstlane(((CI)(uintptr_t)pa.block_op)[blk]);
+  if (pos < 0) return;                                            // padding of an operator's block range
+  typedef const ChainRec __attribute__((address_space(4))) CR;
+  CR &r = *(CR *)(uintptr_t)(pa.rec + pos);
+  const int tid = threadIdx.x;
+  uint64_t *trace = nullptr;
+  uint64_t t_begin = 0, t_ready = 0;
+  uint32_t epoch = 0;
+  if (tid == 0) {
+    trace = (uint64_t *)__hip_atomic_load(&pa.hdr->trace, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (trace) t_begin = wall_clock64();
+    const uint32_t limit = __hip_atomic_load(&pa.hdr->spin_limit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    epoch = __hip_atomic_load(&pa.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t copy = ((uint32_t)blk % kPersistReplicas) * kPersistFlagStride;
+    const int np = r.n_preds;
+    uint32_t spins = 0;
+    int ok = 1;
+    for (int j = 0; j < np && ok; ++j) {
+      const uint32_t *f = pa.flags + (size_t)r.preds[j] * (kPersistReplicas * kPersistFlagStride) + copy;
+      while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != epoch) {
+        if (++spins > limit) {
+          __hip_atomic_store(&pa.hdr->error, (uint32_t)pos + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = 0;
+          break;
+        }
+        if ((spins & 31u) == 0 && __hip_atomic_load(&pa.hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    ctl[0] = ok;
+    if (trace) t_ready = wall_clock64();
+  }
+  if (tid < 64) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // after the wait (thread 0 is in this wavefront)
+  __syncthreads();
+  if (!ctl[0]) return;                                            // a wait ran out somewhere: leave, publish nothing
+  Blk b;
+  b.gx = r.gx; b.gy = r.gy;
+  b.remap = true;
+  const int tile = blk - r.begin;
+  b.x = tile % b.gx;
+  const int rest = tile / b.gx;
+  b.y = rest % b.gy;
+  b.z = rest / b.gy;
+  unsigned char *lds = dyn_lds;
+#define CCASE_(label, Args, call)                             \
+  case label: {                                               \
+    typedef const Args __attribute__((address_space(4))) CA;  \
+    CA &a = *(CA *)&r.args;                                   \
+    call;                                                     \
+  } break;
+#define CCASE(name, Args, call) CCASE_(K_##name, Args, call)
+#define CCASEW(name, Args, call) CCASE_(K_##name + kPersistActivationB, Args, call)
+  constexpr int A = kCohStore, AW = kCohStore;
+  if constexpr (F16) {
+    switch (r.kernel) {
+      CCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, A>(a, b, lds)))
+      CCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, A>(a, b, lds)))
+      CCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, A>(a, b, lds)))
+      CCASEW(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, AW>(a, b, lds)))
+      CCASEW(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, AW>(a, b, lds)))
+      CCASEW(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, AW>(a, b, lds)))
+      CCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, A>(a, b, lds)))
+      CCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, A>(a, b, lds)))
+      CCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, A>(a, b, lds)))
+      CCASE(gap_f16, GapArgs, (gap_body<half_t, A>(a, b, lds)))
+      CCASE(layernorm_f16_wave, RowArgs, (row_cached_body<half_t, true, 64, 2, A>(a, b, lds)))
+      CCASE(layernorm_f16_block, RowArgs, (row_cached_body<half_t, true, 256, kRowCacheChunks, A>(a, b, lds)))
+      CCASE(layernorm_f16_generic, RowArgs, (row_generic_body<half_t, true, A>(a, b, lds)))
+      CCASE(softmax_f16_wave, RowArgs, (row_cached_body<half_t, false, 64, 2, A>(a, b, lds)))
+      CCASE(softmax_f16_block, RowArgs, (row_cached_body<half_t, false, 256, kRowCacheChunks, A>(a, b, lds)))
+      CCASE(softmax_f16_generic, RowArgs, (row_generic_body<half_t, false, A>(a, b, lds)))
+      CCASE(elt_f16_vec, EltArgs, (elt_body<half_t, 8, A>(a, b, lds)))
+      CCASE(elt_f16_scalar, EltArgs, (elt_body<half_t, 1, A>(a, b, lds)))
+      CCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, A>(a, b, lds)))
+      CCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, A>(a, b, lds)))
+      default:
+        if constexpr (!LIGHT) {
+          switch (r.kernel) {
+            CCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, A>(a, b, lds)))
+            CCASE(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, A>(a, b, lds)))
+            CCASE(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, A>(a, b, lds)))
+            CCASEW(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, AW>(a, b, lds)))
+            CCASEW(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, AW>(a, b, lds)))
+            CCASEW(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, AW>(a, b, lds)))
+            default: break;
+          }
+        }
+        break;
+    }
+  } else {
+    switch (r.kernel) {
+      CCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, A>(a, b, lds)))
+      CCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, A>(a, b, lds)))
+      CCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, A>(a, b, lds)))
+      CCASEW(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, AW>(a, b, lds)))
+      CCASEW(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, AW>(a, b, lds)))
+      CCASEW(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, AW>(a, b, lds)))
+      CCASE(gemv_f32, IgemmArgs, (gemv_body<float, A>(a, b, lds)))
+      CCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, A>(a, b, lds)))
+      CCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, A>(a, b, lds)))
+      CCASE(gap_f32, GapArgs, (gap_body<float, A>(a, b, lds)))
+      CCASE(layernorm_f32_wave, RowArgs, (row_cached_body<float, true, 64, 2, A>(a, b, lds)))
+      CCASE(layernorm_f32_block, RowArgs, (row_cached_body<float, true, 256, kRowCacheChunks, A>(a, b, lds)))
+      CCASE(layernorm_f32_generic, RowArgs, (row_generic_body<float, true, A>(a, b, lds)))
+      CCASE(softmax_f32_wave, RowArgs, (row_cached_body<float, false, 64, 2, A>(a, b, lds)))
+      CCASE(softmax_f32_block, RowArgs, (row_cached_body<float, false, 256, kRowCacheChunks, A>(a, b, lds)))
+      CCASE(softmax_f32_generic, RowArgs, (row_generic_body<float, false, A>(a, b, lds)))
+      CCASE(elt_f32_vec, EltArgs, (elt_body<float, 4, A>(a, b, lds)))
+      CCASE(elt_f32_scalar, EltArgs, (elt_body<float, 1, A>(a, b, lds)))
+      CCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, A>(a, b, lds)))
+      CCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, A>(a, b, lds)))
+      default:
+        if constexpr (!LIGHT) {
+          switch (r.kernel) {
+            CCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, A>(a, b, lds)))
+            CCASE(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, A>(a, b, lds)))
+            CCASE(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, A>(a, b, lds)))
+            CCASEW(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, AW>(a, b, lds)))
+            CCASEW(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, AW>(a, b, lds)))
+            CCASEW(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, AW>(a, b, lds)))
+            default: break;
+          }
+        }
+        break;
+    }
+  }
+#undef CCASE
+#undef CCASEW
+#undef CCASE_
+  __builtin_amdgcn_s_waitcnt(0x0F70);                            // vmcnt(0): this wavefront's stores are complete
+  __syncthreads();                                               // ... for every wavefront of the workgroup
+  if (tid == 0) {
+    uint32_t *d = pa.done + (size_t)pos * kPersistCounterStride;
+    const uint32_t before = __hip_atomic_fetch_add(d, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (before + 1u == (uint32_t)r.tiles) {                      // the operator's last tile: raise its flags
+      __hip_atomic_store(d, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t *f = pa.flags + (size_t)pos * (kPersistReplicas * kPersistFlagStride);
+#pragma unroll
+      for (int q = 0; q < kPersistReplicas; ++q)
+        __hip_atomic_store(f + q * kPersistFlagStride, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // the last operator to complete advances the launch number for the next replay
+      const uint32_t ops = __hip_atomic_fetch_add(&pa.hdr->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ops + 1u == (uint32_t)pa.n) {
+        __hip_atomic_store(&pa.hdr->exited, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&pa.hdr->epoch, epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    if (trace) {
+      uint64_t *rec = trace + 4 * (uint64_t)blk;
+      rec[0] = t_begin; rec[1] = t_ready; rec[2] = wall_clock64();
+      rec[3] = ((uint64_t)(uint32_t)pos << 32) | (uint32_t)blk;
+    }
+  }
+}
+
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_chain_f16_light(ChainArgs pa) { chain_body<true, true>(pa); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_chain_f16_heavy(ChainArgs pa) { chain_body<true, false>(pa); }
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_chain_f32_light(ChainArgs pa) { chain_body<false, true>(pa); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_chain_f32_heavy(ChainArgs pa) { chain_body<false, false>(pa); }
+
 // Dependency self-check: done-tokens per operator and a violation counter, in static
 // device memory (nothing is allocated).
 static __device__ int g_verify_tok[opara::kVerifyMaxOps];
@@ -2059,6 +2236,49 @@ hipError_t launch_group(bool f16, bool light, const GroupArgs &ga, uint32_t n_bl
   } else {
     if (light) hipLaunchKernelGGL(opara_k_group_f32_light, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
     else hipLaunchKernelGGL(opara_k_group_f32_heavy, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
+  }
+  return hipGetLastError();
+}
+
+namespace {
+void *chain_func(bool f16, bool light) {
+  return f16 ? (light ? (void *)opara_k_chain_f16_light : (void *)opara_k_chain_f16_heavy)
+             : (light ? (void *)opara_k_chain_f32_light : (void *)opara_k_chain_f32_heavy);
+}
+}  // namespace
+
+bool chain_kernel_ok(int id, bool *light) { return group_kernel_ok(id, light); }
+
+hipError_t chain_max_lds(uint32_t lds_bytes) {
+  for (int f16 = 0; f16 < 2; ++f16)
+    for (int light = 0; light < 2; ++light) {
+      hipError_t err = hipFuncSetAttribute(chain_func(f16, light), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (err != hipSuccess) return err;
+    }
+  return hipSuccess;
+}
+
+hipError_t add_chain_node(hipGraph_t graph, bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes,
+                          const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
+  ChainArgs args = a;
+  void *kparams[1] = {&args};
+  hipKernelNodeParams np = {};
+  np.func = chain_func(f16, light);
+  np.gridDim = dim3((uint32_t)a.total);
+  np.blockDim = dim3(256);
+  np.sharedMemBytes = lds_bytes;
+  np.kernelParams = kparams;
+  return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
+}
+
+hipError_t launch_chain(bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes, hipStream_t s) {
+  const dim3 grid((uint32_t)a.total), block(256);
+  if (f16) {
+    if (light) hipLaunchKernelGGL(opara_k_chain_f16_light, grid, block, lds_bytes, s, a);
+    else hipLaunchKernelGGL(opara_k_chain_f16_heavy, grid, block, lds_bytes, s, a);
+  } else {
+    if (light) hipLaunchKernelGGL(opara_k_chain_f32_light, grid, block, lds_bytes, s, a);
+    else hipLaunchKernelGGL(opara_k_chain_f32_heavy, grid, block, lds_bytes, s, a);
   }
   return hipGetLastError();
 }

@@ -96,6 +96,36 @@ hipError_t add_persist_node(hipGraph_t graph, bool f16, const PersistArgs &a, ui
 // The same kernel as an ordinary launch on `s` (for timing it apart from the graph it belongs to).
 hipError_t launch_persist(bool f16, const PersistArgs &a, uint32_t n_workgroups, uint32_t lds_bytes, hipStream_t s);
 
+// ---- Chained executor: the persistent executor without a work-item loop ----------------
+// One launch whose grid is the sum of all operators' grids in launch-queue order (each
+// operator's block range padded to a multiple of the XCD count).  A workgroup runs exactly
+// one tile: it looks up its operator, waits for the completion flags of the operator's
+// predecessors, runs the tile and publishes it.  Workgroups are dispatched in increasing
+// block order, predecessors have lower block numbers than their consumers, so the lowest
+// unfinished block never waits for a block that has not been dispatched: the launch drains
+// whatever number of workgroups the device holds at a time.
+struct ChainRec {                 // one operator, read through the constant address space
+  int32_t kernel, gx, gy, gz;     // body (KernelId, + kPersistActivationB for two-activation contractions) and grid
+  int32_t begin, tiles;           // first block of the operator, gx * gy * gz
+  uint16_t n_preds, reserved;
+  uint16_t preds[kPersistMaxPreds];   // queue positions of the predecessors inside the kernel
+  int32_t pad[3];
+  KernelArgs args;
+};
+struct ChainArgs {
+  PersistHeader *hdr;             // `exited` counts completed operators here
+  uint32_t *done;                 // as in PersistArgs
+  uint32_t *flags;
+  const int32_t *block_op;        // [total] queue position of the operator a block belongs to, -1 = padding
+  const ChainRec *rec;            // [n]
+  int32_t n, total;
+};
+bool chain_kernel_ok(int kernel_id, bool *light);
+hipError_t chain_max_lds(uint32_t lds_bytes);
+hipError_t add_chain_node(hipGraph_t graph, bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes,
+                          const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
+hipError_t launch_chain(bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes, hipStream_t s);
+
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter
 

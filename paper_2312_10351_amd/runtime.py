@@ -276,6 +276,21 @@ class Session:
         self.execs.append(exe)
         return exe
 
+    def capture_chained(self, policy=B.ORDER_ALG2):
+        """Capture the DAG as one loop-free kernel (one tile per workgroup, blocks in launch-queue
+        order, dependencies through completion flags).  The workspace is a torch allocation kept
+        alive by the session."""
+        import torch
+        B.opara_order_launch_policy(self.dag, policy)
+        nbytes = B.opara_chained_workspace_bytes(self.dag)
+        ws = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.device)
+        ptr = (ws.data_ptr() + 255) // 256 * 256
+        torch.cuda.synchronize()
+        exe = B.opara_capture_chained(self.dag, ptr, nbytes)
+        self._workspaces.append(ws)
+        self.execs.append(exe)
+        return exe
+
     def run_persistent_noalloc(self, policy=B.ORDER_ALG2):
         """One pass through the persistent executor on the library's static workspace (no graph,
         no allocation).  Returns the kernel's error word."""
