@@ -64,6 +64,7 @@ void destroy_exec(opara_exec *e) {
 
 constexpr int kCaptureAttempts = 4;      // instances of one graph tried before opara_capture gives up
 constexpr int kValidationReplays = 2;
+constexpr int kMaxGraphFanOut = 4;       // successors per node of the multi-stream graph; more go through relay nodes
 
 // Stream capture is used for fork-join plans only: every stream other than the origin
 // (the stream of the first queue entry) waits exactly once, at its first operator, on one
@@ -102,18 +103,54 @@ hipError_t assemble_parallel(const opara_dag *g, const std::vector<uint8_t> &kee
   const int32_t n = g->n;
   std::vector<hipGraphNode_t> last_on_stream((size_t)g->n_streams, nullptr), deps;
   int32_t n_sinks = 0;
+  // No node gets more than kMaxGraphFanOut successors: the consumers of a producer with more
+  // hang off a chain of relay nodes without work (producer -> 3 consumers + relay -> 3
+  // consumers + relay ...).  Every instance of a graph in which some node had 7-15
+  // successors either started a successor early or crashed the runtime on the host; graphs
+  // whose nodes have at most 4 (the CNNs, BERT) never did, with or without relays.
+  std::vector<int> outdeg(n, 0);
+  {
+    std::vector<int32_t> prev((size_t)g->n_streams, -1);
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t v = g->order[i], sv = g->stream_of[v];
+      if (prev[sv] >= 0) ++outdeg[prev[sv]];
+      prev[sv] = v;
+      for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j)
+        if (g->stream_of[g->pred[j]] != sv && keep_edge[j]) ++outdeg[g->pred[j]];
+    }
+  }
+  const int fan_cap = kMaxGraphFanOut;
+  std::vector<hipGraphNode_t> handle(n, nullptr);
+  std::vector<int> fan(n, 0), left(outdeg);
+  auto dep_on = [&](int32_t u, hipError_t *err) -> hipGraphNode_t {
+    if (!handle[u]) handle[u] = (*node_of)[u];
+    if (fan[u] == fan_cap - 1 && left[u] > 1) {     // the last free slot of this handle, and more than one consumer to go
+      hipGraphNode_t r = nullptr;
+      const hipError_t e2 = add_noop_node(graph, &handle[u], 1, &r);
+      if (e2 != hipSuccess) *err = e2;
+      handle[u] = r;
+      fan[u] = 0;
+    }
+    ++fan[u];
+    --left[u];
+    return handle[u];
+  };
+  std::vector<int32_t> last_op_on_stream((size_t)g->n_streams, -1);
   for (int32_t i = 0; i < n; ++i) {
     const int32_t v = g->order[i], sv = g->stream_of[v];
     deps.clear();
-    if (last_on_stream[sv]) deps.push_back(last_on_stream[sv]);
+    hipError_t rerr = hipSuccess;
+    if (last_on_stream[sv]) deps.push_back(dep_on(last_op_on_stream[sv], &rerr));
+    last_op_on_stream[sv] = v;
     TokenNodeArgs t = {};
     t.real = g->plan[v].args;
     t.tok.epoch = 1; t.tok.self = v; t.tok.delay = 4;
     for (int32_t j = g->pred_off[v]; j < g->pred_off[v + 1]; ++j) {
       const int32_t u = g->pred[j];
       if (t.tok.n_preds < kVerifyMaxPreds) t.tok.preds[t.tok.n_preds++] = u;
-      if (g->stream_of[u] != sv && keep_edge[j]) deps.push_back((*node_of)[u]);
+      if (g->stream_of[u] != sv && keep_edge[j]) deps.push_back(dep_on(u, &rerr));
     }
+    if (rerr != hipSuccess) return rerr;
     hipError_t err = tokens ? add_token_node(graph, t, deps.empty() ? nullptr : deps.data(), deps.size(), &(*node_of)[v])
                             : add_plan_node(graph, g->plan[v], deps.empty() ? nullptr : deps.data(), deps.size(), &(*node_of)[v]);
     if (err != hipSuccess) return err;
@@ -322,7 +359,7 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
     if (n > kVerifyMaxOps) { set_error("opara_capture: more than %d operators", kVerifyMaxOps); delete e; return OPARA_EUNSUPPORTED; }
     std::vector<hipGraphNode_t> node_of(n, nullptr);
     bool swap_in_place = true;                     // false once the runtime has refused to switch a node's kernel
-    int violations = 0;
+    int violations = 0, bad_op = -1, bad_pred = -1;
     for (int attempt = 1; attempt <= kCaptureAttempts; ++attempt) {
       e->attempts = attempt;
       if (e->exec) { (void)hipGraphExecDestroy(e->exec); e->exec = nullptr; }
@@ -332,11 +369,12 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
       HIP_TRY(hipGraphInstantiate(&e->exec, e->graph, nullptr, nullptr, 0));
       violations = 0;
       for (int rep = 0; rep < kValidationReplays; ++rep) {
-        int viol = 0;
+        int viol = 0, vop = -1, vpred = -1;
         HIP_TRY(verify_reset(origin));
         HIP_TRY(hipGraphLaunch(e->exec, origin));
-        HIP_TRY(verify_read(origin, &viol));
+        HIP_TRY(verify_read(origin, &viol, &vop, &vpred));
         violations += viol;
+        if (viol) { bad_op = vop; bad_pred = vpred; }
       }
       if (violations != 0) continue;               // this instance drops a dependency: build another
       if (swap_in_place) {
@@ -359,8 +397,9 @@ extern "C" int opara_capture(opara_dag *g, void *const *hip_streams, int32_t n_s
     }
     if (e->validation == OPARA_NOT_VALIDATED) {
       set_error("opara_capture: the graph runtime started operators before their predecessors in %d of %d instances "
-                "of this graph (last one: %d violations); no graph is handed out", kCaptureAttempts, kCaptureAttempts,
-                violations);
+                "of this graph (last one: %d violations, e.g. operator %d before its predecessor %d, which has %d "
+                "successors); no graph is handed out", kCaptureAttempts, kCaptureAttempts, violations, bad_op, bad_pred,
+                bad_pred >= 0 ? g->succ_off[bad_pred + 1] - g->succ_off[bad_pred] : 0);
       destroy_exec(e);
       return OPARA_EGRAPH;
     }

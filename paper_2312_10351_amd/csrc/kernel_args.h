@@ -108,7 +108,11 @@ struct ConcatArgs {
   X(concat_f16_vec, ConcatArgs)         \
   X(concat_f16_scalar, ConcatArgs)      \
   X(concat_f32_vec, ConcatArgs)         \
-  X(concat_f32_scalar, ConcatArgs)
+  X(concat_f32_scalar, ConcatArgs)      \
+  X(igemm_f16_direct4s, IgemmArgs)      \
+  X(igemm_f16_quad4s, IgemmArgs)        \
+  X(igemm_f32_direct4s, IgemmArgs)      \
+  X(igemm_f32_quad4s, IgemmArgs)
 
 enum KernelId : int32_t {
 #define X(name, T) K_##name,
@@ -163,6 +167,8 @@ constexpr int kQuad64MinTiles = 128;             // GEMM-shaped operands with at
 constexpr double kQuad64MaxFlops = 4.0e10;       // ... up to this weight (measured up to 1.7e10)
 constexpr int kQuadFourWaveTiles = 128;          // from this many 32 x 32 tiles on, four wavefronts per tile whatever K is
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
+constexpr int kSmallTile = 16;        // ... of their small-tile forms, for operators with few 32 x 32 tiles
+constexpr int kSmallTileMaxTiles32 = 80;   // at most this many 32 x 32 tiles: take 16 x 16 ones (four times as many workgroups)
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)
 constexpr int kRowGroupBlock = 256;   // block variant

@@ -127,7 +127,7 @@ hipError_t add_chain_node(hipGraph_t graph, bool f16, bool light, const ChainArg
 hipError_t launch_chain(bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes, hipStream_t s);
 
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
-hipError_t verify_read(hipStream_t s, int *viol);  // synchronises s, returns the counter
+hipError_t verify_read(hipStream_t s, int *viol, int *op = nullptr, int *pred = nullptr);  // synchronises s; the counter and the last violation
 
 // Workspace of the persistent executor for callers that cannot allocate: a static device
 // array inside the library (one copy per GPU).  Returns its device address on the current

@@ -155,6 +155,19 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelP
       if (group) waves = 4;                                    // one workgroup size inside a group kernel
       else if (quad) waves = (cdiv(a.K, 16 * ve) <= 8 || tiles32 >= (int64_t)kQuadFourWaveTiles) ? 4 : 8;   // 256-byte steps
       else waves = cdiv(a.K, 8 * ve) <= 16 ? 4 : 8;            // 128-byte steps
+      // Few tiles (the 14 x 14 and 7 x 7 stages of the CNNs): the load rate of ONE compute unit
+      // bounds a workgroup, so 16 x 16 tiles on four times as many compute units finish sooner
+      // although they move twice the operand bytes in total.
+      static const int small_ids[2][2] = {{K_igemm_f32_direct4s, K_igemm_f32_quad4s}, {K_igemm_f16_direct4s, K_igemm_f16_quad4s}};
+      if (!persistent && tiles32 <= kSmallTileMaxTiles32) {
+        out->kernel = small_ids[f16][quad ? 1 : 0];
+        out->gx = cdiv(a.M, kSmallTile);
+        out->gy = cdiv(a.N, kSmallTile);
+        out->gz = (uint32_t)batch;
+        out->block = 256;
+        out->args.igemm = a;
+        return OPARA_OK;
+      }
       out->kernel = ids[f16][(quad ? 2 : 0) + (waves == 8 ? 1 : 0)];
       out->gx = cdiv(a.M, kDirectTile);
       out->gy = cdiv(a.N, kDirectTile);

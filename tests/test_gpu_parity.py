@@ -173,8 +173,8 @@ def test_deep_contractions_take_the_quad_coalesced_kernels():
             names = [B.opara_kernel_info(d.kernel_id)[0] for d in B.opara_get_demands(s.dag)]
         finally:
             s.close()
-        first = "quad4" if dtype == "f16" else "quad8"       # K = 648: six or eleven 256-byte steps
-        assert names == [f"igemm_{dtype}_{first}", f"igemm_{dtype}_quad8", f"igemm_{dtype}_direct4",
+        # few 32 x 32 tiles: the 16 x 16-tile forms (deep K: quad-coalesced, shallow K: fragment-loading)
+        assert names == [f"igemm_{dtype}_quad4s", f"igemm_{dtype}_quad4s", f"igemm_{dtype}_direct4s",
                          f"igemm_{dtype}_quad64x4"], names        # 128 tiles of 64 x 64
 
 
