@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libopara.so")
+DEMO = os.path.join(HERE, "abi_demo")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(HERE, "..", "include"), "-I", BUILD, "-I", CSRC]
@@ -79,6 +80,10 @@ def build(verbose=False):
         _run([HIPCC, "-x", "c++", *COMMON, "-Wall", "-c", os.path.join(CSRC, src), "-o", o])
         objs.append(o)
     _run([HIPCC, f"--offload-arch={ARCH}", "-shared", "-fPIC", "-o", LIB, *objs])
+    # A plain C caller of the ABI (no Python, no PyTorch), run by the GPU tests.
+    _run(["gcc", "-O1", "-std=c11", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(HERE, "..", "include"),
+          "-I", "/opt/rocm/include", os.path.join(CSRC, "abi_demo.c"), "-o", DEMO, "-L", HERE, "-lopara",
+          "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib"])
     if verbose:
         for n in names:
             print(n, res["opara_k_" + n])

@@ -168,7 +168,7 @@ constexpr double kQuad64MaxFlops = 4.0e10;       // ... up to this weight (measu
 constexpr int kQuadFourWaveTiles = 128;          // from this many 32 x 32 tiles on, four wavefronts per tile whatever K is
 constexpr int kDirectTile = 32;       // output tile edge of the latency-oriented kernels
 constexpr int kSmallTile = 16;        // ... of their small-tile forms, for operators with few 32 x 32 tiles
-constexpr int kSmallTileMaxTiles32 = 80;   // at most this many 32 x 32 tiles: take 16 x 16 ones (four times as many workgroups)
+constexpr int kSmallTileMaxTiles32 = 100;   // at most this many 32 x 32 tiles: take 16 x 16 ones (four times as many workgroups)
 
 constexpr int kRowGroupWave = 64;     // threads cooperating on one row (wave variant)
 constexpr int kRowGroupBlock = 256;   // block variant

@@ -73,10 +73,14 @@ __device__ __forceinline__ void stg(P *p, const V &v) {
   if constexpr (!COH) {
     *(V *)p = v;
   } else if constexpr (sizeof(V) == 16) {
-    uint64_t q[2];
-    __builtin_memcpy(q, &v, 16);
-    __hip_atomic_store((uint64_t *)p, q[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store((uint64_t *)p + 1, q[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // One 16-byte write-through store (what a relaxed agent-scope atomic store compiles to for
+    // 8 bytes, `global_store_dwordx2 ... sc1`, in its four-dword form): the language has no
+    // 16-byte atomic, and two 8-byte ones reach memory as two partial-line writes.  The nop
+    // covers the wait state a store of more than 8 bytes needs before its data registers
+    // may be overwritten.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 q = __builtin_bit_cast(u32x4, v);
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(q) : "memory");
   } else if constexpr (sizeof(V) == 8) {
     uint64_t q;
     __builtin_memcpy(&q, &v, 8);
