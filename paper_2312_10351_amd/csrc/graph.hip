@@ -64,6 +64,7 @@ void destroy_exec(opara_exec *e) {
 
 constexpr int kCaptureAttempts = 4;      // instances of one graph tried before opara_capture gives up
 constexpr int kValidationReplays = 2;
+constexpr int64_t kFusedSplitLightBlocks = 2048;  // four times what a heavy group kernel keeps resident (2 workgroups per CU)
 constexpr int kMaxGraphFanOut = 4;       // successors per node of the multi-stream graph; more go through relay nodes
 
 // Stream capture is used for fork-join plans only: every stream other than the origin
@@ -233,6 +234,35 @@ int capture_fused(opara_dag *g, opara_exec **out) {
       members.clear();
     };
     int64_t blocks = 0;
+    // A wave that mixes heavy bodies (two workgroups per CU) with much light work runs as two
+    // nodes, heavy members first: inside one heavy group kernel the light members would run
+    // at the heavy flavour's occupancy, which streaming operators of several MB pay for
+    // dearly (random wide DAG: 3355 -> 2740 us), while a second node costs one more kernel
+    // boundary (Inception-v3-like: 345 -> 358 us when every mixed wave is split).  The light
+    // members must hold more workgroups than the heavy flavour keeps resident at once.
+    {
+      std::vector<int32_t> hv, lt;
+      int64_t light_blocks = 0;
+      bool groupable = wave.size() > 1;
+      for (int32_t v : wave) {
+        const KernelPlan &p = g->plan_group[v];
+        bool l = true;
+        groupable = groupable && group_kernel_ok(p.kernel, &l) && kernel_is_f16(p.kernel) == kernel_is_f16(g->plan_group[wave[0]].kernel);
+        (l ? lt : hv).push_back(v);
+        if (l) light_blocks += (int64_t)p.gx * p.gy * p.gz;
+      }
+      if (groupable && !hv.empty() && !lt.empty() && light_blocks > kFusedSplitLightBlocks) {
+        for (int pass = 0; pass < 2; ++pass) {
+          const std::vector<int32_t> &part = pass ? lt : hv;
+          for (size_t i = 0; i < part.size(); ++i) {
+            if (members.size() == (size_t)kGroupMaxOps) flush();
+            members.push_back(part[i]);
+          }
+          flush();
+        }
+        continue;
+      }
+    }
     for (int32_t v : wave) {
       const KernelPlan &p = g->plan_group[v];
       bool light = true;
