@@ -320,7 +320,9 @@ int32_t opara_num_ops(const opara_dag *g);
  *                           several becomes a group node: ONE kernel whose grid is the sum
  *                           of the members' grids, each workgroup running its operator's
  *                           own body (at most 16 operators per node, a larger wave is
- *                           split).  All nodes form one chain.  Needs a launch queue only
+ *                           split; a wave that mixes register-heavy contractions with
+ *                           more than 2,048 workgroups of lighter work is cut between
+ *                           the two, so that the lighter operators keep their occupancy).  All nodes form one chain.  Needs a launch queue only
  *                           (ESTATE); streams play no part, hip_streams is not read beyond
  *                           the argument check.  Operators inside a group run the
  *                           four-wavefront form of their kernel, so results can differ
@@ -499,11 +501,11 @@ int opara_run_persistent_noalloc(opara_dag *g, void *hip_stream, uint32_t *error
  * Fused executor (OPARA_FUSED): the node of the chain every operator runs in (host
  * int32[n_ops], nodes numbered in execution order), the number of nodes, and the kernel of
  * every node (host int32[n_nodes]: a kernel id of the kernel table for a single operator,
- * OPARA_GROUP_KERNEL_LIGHT / _HEAVY for a group node: the group kernel that holds the bodies
- * with at most 128 vector registers, or all bodies); each may be NULL.  Operators that
- * share a node run concurrently inside one kernel.
+ * OPARA_GROUP_KERNEL_STREAM / _LIGHT / _HEAVY for a group node: the group kernel that holds
+ * the bodies with at most 64 vector registers, at most 128, or all bodies); each may be
+ * NULL.  Operators that share a node run concurrently inside one kernel.
  */
-enum { OPARA_GROUP_KERNEL_LIGHT = -1, OPARA_GROUP_KERNEL_HEAVY = -2 };
+enum { OPARA_GROUP_KERNEL_LIGHT = -1, OPARA_GROUP_KERNEL_HEAVY = -2, OPARA_GROUP_KERNEL_STREAM = -3 };
 int opara_fused_plan(const opara_exec *e, int32_t *node_of, int32_t *n_nodes, int32_t *node_kernel);
 /*
  * Measurement aid: launches every node of a fused executor by itself (an ordinary launch

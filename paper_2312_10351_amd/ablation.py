@@ -53,6 +53,8 @@ def order_ablation(index, replays):
             row[name + "_us"] = replay_latency(s, s.capture(B.PARALLEL, policy=pid), replays)
         for pid, name in enumerate(B.ORDER_POLICY_NAMES):      # the same queues as work-item orders
             row["persistent_" + name + "_us"] = replay_latency(s, s.capture_persistent(policy=pid), replays)
+        for pid, name in enumerate(B.ORDER_POLICY_NAMES):      # ... and as the order inside the fused executor's waves
+            row["fused_" + name + "_us"] = replay_latency(s, s.capture(B.FUSED, policy=pid), replays)
         return row
     finally:
         s.close()
@@ -70,8 +72,10 @@ def batch_sweep(batch, replays):
         seq = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
         par = replay_latency(s, s.capture(B.PARALLEL), replays)
         per = replay_latency(s, s.capture_persistent(), replays)
+        fus = replay_latency(s, s.capture(B.FUSED), replays)
         return {"ablation": "batch_sweep", "workload": wl.name, "batch": batch, "sequential_us": seq,
-                "parallel_us": par, "persistent_us": per, "speedup": seq / par, "speedup_persistent": seq / per,
+                "parallel_us": par, "persistent_us": per, "fused_us": fus, "speedup": seq / par, "speedup_persistent": seq / per,
+                "speedup_fused": seq / fus, "fused_images_per_s": batch * 1e6 / fus,
                 "parallel_images_per_s": batch * 1e6 / par, "persistent_images_per_s": batch * 1e6 / per,
                 "sequential_images_per_s": batch * 1e6 / seq}
     finally:
@@ -93,7 +97,8 @@ def concat_ablation(index, replays):
                 out["elided"] = len(s.elided)
             out[tag] = {"sequential_us": replay_latency(s, s.capture(B.SEQUENTIAL), replays),
                         "multi_stream_graph_us": replay_latency(s, s.capture(B.PARALLEL), replays),
-                        "persistent_us": replay_latency(s, s.capture_persistent(), replays)}
+                        "persistent_us": replay_latency(s, s.capture_persistent(), replays),
+                        "fused_us": replay_latency(s, s.capture(B.FUSED), replays)}
         finally:
             s.close()
     return out
@@ -156,6 +161,7 @@ def interference(kind_a, kind_b, replays):
         row["sequential_us"] = replay_latency(s, s.capture(B.SEQUENTIAL), replays)
         row["parallel_us"] = replay_latency(s, s.capture(B.PARALLEL), replays)
         row["persistent_us"] = replay_latency(s, s.capture_persistent(), replays)
+        row["fused_us"] = replay_latency(s, s.capture(B.FUSED), replays)
     finally:
         s.close()
     for tag, kind in (("a", kind_a), ("b", kind_b)):
@@ -180,35 +186,36 @@ def render_markdown(records):
     by = lambda kind: [r for r in records if r["ablation"] == kind]
     pol = list(B.ORDER_POLICY_NAMES)
     if by("launch_order"):
-        for title, prefix in (("Launch order, multi-stream graph", ""), ("Launch order, persistent executor", "persistent_")):
+        for title, prefix in (("Launch order, multi-stream graph", ""), ("Launch order, persistent executor", "persistent_"),
+                              ("Launch order, fused executor", "fused_")):
             out += ["", f"### {title}", "", "| workload | sequential graph | " + " | ".join(pol) + " |", "|---|---|" + "---|" * len(pol)]
             for r in by("launch_order"):
                 out.append(f"| {r['workload']} ({r['n_ops']}) | {r['sequential_us']:.1f} | " +
                            " | ".join(f"{r[prefix + n + '_us']:.1f}" for n in pol) + " |")
     if by("interference"):
         out += ["", "### Interference pairs", "",
-                "| pair | A alone | B alone | one stream, back to back | two streams (graph) | gain | persistent executor |",
-                "|---|---|---|---|---|---|---|"]
+                "| pair | A alone | B alone | one stream, back to back | two streams (graph) | gain | persistent executor | fused executor (one kernel) |",
+                "|---|---|---|---|---|---|---|---|"]
         for r in by("interference"):
             out.append(f"| {r['pair']} | {r['alone_a_us']:.1f} | {r['alone_b_us']:.1f} | {r['sequential_us']:.1f} | "
-                       f"{r['parallel_us']:.1f} | {r['overlap_gain']:.2f}x | {r['persistent_us']:.1f} |")
+                       f"{r['parallel_us']:.1f} | {r['overlap_gain']:.2f}x | {r['persistent_us']:.1f} | {r['fused_us']:.1f} |")
     if by("batch_sweep"):
         out += ["", "### Batch sweep", "",
-                "| batch | sequential us | multi-stream graph us | persistent us | graph speed-up | persistent speed-up | best images/s |",
-                "|---:|---:|---:|---:|---:|---:|---:|"]
+                "| batch | sequential us | multi-stream graph us | persistent us | fused us | graph speed-up | persistent speed-up | fused speed-up | best images/s |",
+                "|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]
         for r in by("batch_sweep"):
-            best = max(r["parallel_images_per_s"], r["persistent_images_per_s"], r["sequential_images_per_s"])
-            out.append(f"| {r['batch']} | {r['sequential_us']:.0f} | {r['parallel_us']:.0f} | {r['persistent_us']:.0f} | "
-                       f"{r['speedup']:.2f} | {r['speedup_persistent']:.2f} | {best:,.0f} |")
+            best = max(r["parallel_images_per_s"], r["persistent_images_per_s"], r["sequential_images_per_s"], r["fused_images_per_s"])
+            out.append(f"| {r['batch']} | {r['sequential_us']:.0f} | {r['parallel_us']:.0f} | {r['persistent_us']:.0f} | {r['fused_us']:.0f} | "
+                       f"{r['speedup']:.2f} | {r['speedup_persistent']:.2f} | {r['speedup_fused']:.2f} | {best:,.0f} |")
     if by("zero_copy_concat"):
         out += ["", "### Zero-copy concatenation", "",
-                "| workload | concats | elided | layout | sequential graph | multi-stream graph | persistent executor |",
-                "|---|---|---|---|---|---|---|"]
+                "| workload | concats | elided | layout | sequential graph | multi-stream graph | persistent executor | fused executor |",
+                "|---|---|---|---|---|---|---|---|"]
         for r in by("zero_copy_concat"):
             for tag in ("explicit", "zero_copy"):
                 t = r[tag]
                 out.append(f"| {r['workload']} | {r['concats']} | {r['elided']} | {tag} | {t['sequential_us']:.0f} | "
-                           f"{t['multi_stream_graph_us']:.0f} | {t['persistent_us']:.0f} |")
+                           f"{t['multi_stream_graph_us']:.0f} | {t['persistent_us']:.0f} | {t['fused_us']:.0f} |")
     if by("stream_policy"):
         out += ["", "### Stream policies and synchronisation pruning", "",
                 "| workload | ops | sequential | policy | streams | alloc us | syncs | after pruning | graph edges | graph us | pruned graph us |",

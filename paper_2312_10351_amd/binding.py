@@ -336,7 +336,7 @@ def opara_exec_info(exe):
     return a.value, b.value
 
 
-GROUP_KERNEL_LIGHT, GROUP_KERNEL_HEAVY = -1, -2
+GROUP_KERNEL_LIGHT, GROUP_KERNEL_HEAVY, GROUP_KERNEL_STREAM = -1, -2, -3
 
 
 def opara_fused_plan(exe, n_ops):
@@ -352,8 +352,8 @@ def opara_fused_node_kernels(exe, dtype):
     _check(load().opara_fused_plan(exe, None, C.byref(n), None))
     k = (C.c_int32 * n.value)()
     _check(load().opara_fused_plan(exe, None, None, k))
-    return [f"group_{dtype}_light" if i == GROUP_KERNEL_LIGHT else f"group_{dtype}_heavy" if i == GROUP_KERNEL_HEAVY
-            else opara_kernel_info(i)[0] for i in k]
+    group = {GROUP_KERNEL_LIGHT: "light", GROUP_KERNEL_HEAVY: "heavy", GROUP_KERNEL_STREAM: "stream"}
+    return [f"group_{dtype}_{group[i]}" if i in group else opara_kernel_info(i)[0] for i in k]
 
 
 def opara_fused_time_nodes(exe, stream_handle, launches):

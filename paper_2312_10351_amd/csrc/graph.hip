@@ -31,7 +31,8 @@ struct opara_exec {
   opara::ChainArgs chain_args{};
   // fused executor only: the chain of nodes (single operators and groups) and where each operator went
   struct FusedNode {
-    bool is_group = false, f16 = false, light = false;
+    bool is_group = false, f16 = false;
+    int flavor = 0;                      // group kernel flavour: 0 stream, 1 light, 2 heavy
     int32_t op = -1;                     // single operator (ordinary kernel of the graph executors' plan)
     uint32_t blocks = 0, lds = 0;
     opara::GroupArgs ga;                 // group: the launch record
@@ -206,15 +207,13 @@ int capture_fused(opara_dag *g, opara_exec **out) {
         node.op = members[0];
       } else {
         node.is_group = true;
-        node.light = true;
+        node.flavor = 0;
         std::memset(&node.ga, 0, sizeof node.ga);
         node.ga.n = (int32_t)members.size();
         int64_t end = 0;
         for (size_t i = 0; i < members.size(); ++i) {
           const KernelPlan &p = g->plan_group[members[i]];
-          bool light = true;
-          group_kernel_ok(p.kernel, &light);
-          node.light = node.light && light;
+          node.flavor = std::max(node.flavor, group_flavor(p.kernel));
           node.f16 = kernel_is_f16(p.kernel);
           const int64_t tiles = (int64_t)p.gx * p.gy * p.gz;
           end += (tiles + kGroupAlign - 1) / kGroupAlign * kGroupAlign;
@@ -234,32 +233,39 @@ int capture_fused(opara_dag *g, opara_exec **out) {
       members.clear();
     };
     int64_t blocks = 0;
-    // A wave that mixes heavy bodies (two workgroups per CU) with much light work runs as two
-    // nodes, heavy members first: inside one heavy group kernel the light members would run
-    // at the heavy flavour's occupancy, which streaming operators of several MB pay for
-    // dearly (random wide DAG: 3355 -> 2740 us), while a second node costs one more kernel
-    // boundary (Inception-v3-like: 345 -> 358 us when every mixed wave is split).  The light
-    // members must hold more workgroups than the heavy flavour keeps resident at once.
+    // A wave that mixes bodies of several flavours is cut between flavours, the heavier
+    // members first, wherever the lighter side holds much work: inside a heavier group kernel
+    // the lighter members would run at its occupancy (2 or 4 instead of 8 wavefronts per
+    // SIMD), which streaming operators of several MB pay for dearly (random wide DAG: 3355 ->
+    // 2740 us), while every extra node costs one more kernel boundary (Inception-v3-like:
+    // 345 -> 358 us when every mixed wave is split).  The lighter side must hold more
+    // workgroups than kFusedSplitLightBlocks.
     {
-      std::vector<int32_t> hv, lt;
-      int64_t light_blocks = 0;
+      std::vector<int32_t> by_flavor[3];
       bool groupable = wave.size() > 1;
       for (int32_t v : wave) {
         const KernelPlan &p = g->plan_group[v];
-        bool l = true;
-        groupable = groupable && group_kernel_ok(p.kernel, &l) && kernel_is_f16(p.kernel) == kernel_is_f16(g->plan_group[wave[0]].kernel);
-        (l ? lt : hv).push_back(v);
-        if (l) light_blocks += (int64_t)p.gx * p.gy * p.gz;
+        const int f = group_flavor(p.kernel);
+        groupable = groupable && f >= 0 && kernel_is_f16(p.kernel) == kernel_is_f16(g->plan_group[wave[0]].kernel);
+        if (f >= 0) by_flavor[f].push_back(v);
       }
-      if (groupable && !hv.empty() && !lt.empty() && light_blocks > kFusedSplitLightBlocks) {
-        for (int pass = 0; pass < 2; ++pass) {
-          const std::vector<int32_t> &part = pass ? lt : hv;
-          for (size_t i = 0; i < part.size(); ++i) {
+      int64_t below[3] = {0, 0, 0};                    // workgroups of all members lighter than flavour f
+      for (int f = 1; f < 3; ++f) {
+        below[f] = below[f - 1];
+        for (int32_t v : by_flavor[f - 1]) below[f] += (int64_t)g->plan_group[v].gx * g->plan_group[v].gy * g->plan_group[v].gz;
+      }
+      const bool cut2 = !by_flavor[2].empty() && below[2] > kFusedSplitLightBlocks;                       // heavy | rest
+      const bool cut1 = !by_flavor[1].empty() && !by_flavor[0].empty() && below[1] > kFusedSplitLightBlocks &&
+                        (cut2 || by_flavor[2].empty());                                                   // light | stream
+      if (groupable && (cut1 || cut2)) {
+        for (int f = 2; f >= 0; --f) {
+          for (int32_t v : by_flavor[f]) {
             if (members.size() == (size_t)kGroupMaxOps) flush();
-            members.push_back(part[i]);
+            members.push_back(v);
           }
-          flush();
+          if ((f == 2 && cut2) || (f == 1 && cut1)) flush();
         }
+        flush();
         continue;
       }
     }
@@ -291,7 +297,7 @@ int capture_fused(opara_dag *g, opara_exec **out) {
     HIP_TRY(hipGraphCreate(&e->graph, 0));
     for (const opara_exec::FusedNode &fn : e->fused) {
       if (fn.is_group)
-        HIP_TRY(add_group_node(e->graph, fn.f16, fn.light, fn.ga, fn.blocks, fn.lds, last ? &last : nullptr, last ? 1 : 0, &node));
+        HIP_TRY(add_group_node(e->graph, fn.f16, fn.flavor, fn.ga, fn.blocks, fn.lds, last ? &last : nullptr, last ? 1 : 0, &node));
       else
         HIP_TRY(add_plan_node(e->graph, g->plan[fn.op], last ? &last : nullptr, last ? 1 : 0, &node));
       last = node;
@@ -1036,7 +1042,7 @@ extern "C" int opara_fused_plan(const opara_exec *e, int32_t *node_of, int32_t *
   if (node_kernel)
     for (size_t i = 0; i < e->fused.size(); ++i) {
       const opara_exec::FusedNode &fn = e->fused[i];
-      node_kernel[i] = fn.is_group ? (fn.light ? OPARA_GROUP_KERNEL_LIGHT : OPARA_GROUP_KERNEL_HEAVY) : e->dag->plan[fn.op].kernel;
+      node_kernel[i] = fn.is_group ? (fn.flavor == 0 ? OPARA_GROUP_KERNEL_STREAM : fn.flavor == 1 ? OPARA_GROUP_KERNEL_LIGHT : OPARA_GROUP_KERNEL_HEAVY) : e->dag->plan[fn.op].kernel;
     }
   return OPARA_OK;
 }
@@ -1052,7 +1058,7 @@ extern "C" int opara_fused_time_nodes(opara_exec *e, void *hip_stream, int32_t l
     float ms = 0.f;
     for (int32_t k = -2; k < launches; ++k) {       // two untimed launches first
       if (k == 0) HIP_TRY(hipEventRecord(t0, st));
-      if (fn.is_group) HIP_TRY(launch_group(fn.f16, fn.light, fn.ga, fn.blocks, fn.lds, st));
+      if (fn.is_group) HIP_TRY(launch_group(fn.f16, fn.flavor, fn.ga, fn.blocks, fn.lds, st));
       else HIP_TRY(launch_plan(e->dag->plan[fn.op], st));
     }
     HIP_TRY(hipEventRecord(t1, st));

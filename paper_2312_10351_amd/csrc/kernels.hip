@@ -1824,12 +1824,13 @@ extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f32(Persist
 // A workgroup finds its operator from the block ranges in the argument record, rebuilds
 // its position in that operator's own grid and runs the operator's ordinary body on the
 // operator's arguments, which it reads from the kernel-argument segment like any kernel
-// does.  No flags, no coherent accesses: kernel boundaries order the groups.  Two flavours
-// per element type: "light" holds the bodies that need at most 128 vector registers
-// (four wavefronts per SIMD stay resident, which the streaming bodies want), "heavy" all
-// 256-thread bodies.
+// does.  No flags, no coherent accesses: kernel boundaries order the groups.  Three flavours
+// per element type, by the registers their bodies need: "stream" (at most 64: pooling,
+// row-wise, element-wise, concatenation, matrix-vector; eight wavefronts per SIMD stay
+// resident, which streaming wants), "light" (at most 128: those plus the fragment-loading
+// and 16 x 16-tile contractions; four per SIMD), "heavy" (all 256-thread bodies; two).
 // ---------------------------------------------------------------------------------
-template <bool F16, bool LIGHT>
+template <bool F16, int FLAVOR>
 __device__ __forceinline__ void group_body() {
   // The record is the kernel's only argument and therefore starts the kernel-argument
   // segment.  It is read in place through the segment pointer: indexing the by-value
@@ -1860,11 +1861,6 @@ __device__ __forceinline__ void group_body() {
   } break;
   if constexpr (F16) {
     switch (ga.kernel[i]) {
-      GCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
-      GCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 2, 2>(a, b, lds)))
-      GCASE(igemm_f16_direct4s, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 1, 1>(a, b, lds)))
-      GCASE(igemm_f16_quad4s, IgemmArgs, (igemm_quad_body<half_t, 4, 0, 1, 1>(a, b, lds)))
-      GCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
       GCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
       GCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, 0>(a, b, lds)))
       GCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, 0>(a, b, lds)))
@@ -1880,23 +1876,29 @@ __device__ __forceinline__ void group_body() {
       GCASE(concat_f16_vec, ConcatArgs, (concat_body<half_t, 8, 0>(a, b, lds)))
       GCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, 0>(a, b, lds)))
       default:
-        if constexpr (!LIGHT) {
+        if constexpr (FLAVOR >= 1) {
           switch (ga.kernel[i]) {
-            GCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, 0>(a, b, lds)))
-            GCASE(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, 0, 2, 2>(a, b, lds)))
-            GCASE(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
-            default: break;
+            GCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
+            GCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 2, 2>(a, b, lds)))
+            GCASE(igemm_f16_direct4s, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 1, 1>(a, b, lds)))
+            GCASE(igemm_f16_quad4s, IgemmArgs, (igemm_quad_body<half_t, 4, 0, 1, 1>(a, b, lds)))
+            GCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
+            default:
+              if constexpr (FLAVOR >= 2) {
+                switch (ga.kernel[i]) {
+                  GCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+                  GCASE(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, 0, 2, 2>(a, b, lds)))
+                  GCASE(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
+                  default: break;
+                }
+              }
+              break;
           }
         }
         break;
     }
   } else {
     switch (ga.kernel[i]) {
-      GCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
-      GCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 2, 2>(a, b, lds)))
-      GCASE(igemm_f32_direct4s, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 1, 1>(a, b, lds)))
-      GCASE(igemm_f32_quad4s, IgemmArgs, (igemm_quad_body<float, 4, 0, 1, 1>(a, b, lds)))
-      GCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
       GCASE(gemv_f32, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
       GCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, 0>(a, b, lds)))
       GCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, 0>(a, b, lds)))
@@ -1912,12 +1914,23 @@ __device__ __forceinline__ void group_body() {
       GCASE(concat_f32_vec, ConcatArgs, (concat_body<float, 4, 0>(a, b, lds)))
       GCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, 0>(a, b, lds)))
       default:
-        if constexpr (!LIGHT) {
+        if constexpr (FLAVOR >= 1) {
           switch (ga.kernel[i]) {
-            GCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
-            GCASE(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, 0, 2, 2>(a, b, lds)))
-            GCASE(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
-            default: break;
+            GCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
+            GCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 2, 2>(a, b, lds)))
+            GCASE(igemm_f32_direct4s, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 1, 1>(a, b, lds)))
+            GCASE(igemm_f32_quad4s, IgemmArgs, (igemm_quad_body<float, 4, 0, 1, 1>(a, b, lds)))
+            GCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
+            default:
+              if constexpr (FLAVOR >= 2) {
+                switch (ga.kernel[i]) {
+                  GCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
+                  GCASE(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, 0, 2, 2>(a, b, lds)))
+                  GCASE(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
+                  default: break;
+                }
+              }
+              break;
           }
         }
         break;
@@ -1926,10 +1939,12 @@ __device__ __forceinline__ void group_body() {
 #undef GCASE
 }
 
-extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f16_light(GroupArgs) { group_body<true, true>(); }
-extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f16_heavy(GroupArgs) { group_body<true, false>(); }
-extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f32_light(GroupArgs) { group_body<false, true>(); }
-extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f32_heavy(GroupArgs) { group_body<false, false>(); }
+extern "C" __global__ void __launch_bounds__(256, 8) opara_k_group_f16_stream(GroupArgs) { group_body<true, 0>(); }
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f16_light(GroupArgs) { group_body<true, 1>(); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f16_heavy(GroupArgs) { group_body<true, 2>(); }
+extern "C" __global__ void __launch_bounds__(256, 8) opara_k_group_f32_stream(GroupArgs) { group_body<false, 0>(); }
+extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f32_light(GroupArgs) { group_body<false, 1>(); }
+extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f32_heavy(GroupArgs) { group_body<false, 2>(); }
 
 // ---------------------------------------------------------------------------------
 // Chained executor: every workgroup runs one tile of one operator behind a wait for the
@@ -2232,42 +2247,52 @@ hipError_t add_token_node(hipGraph_t graph, const TokenNodeArgs &t, const hipGra
 }
 
 namespace {
-void *group_func(bool f16, bool light) {
-  return f16 ? (light ? (void *)opara_k_group_f16_light : (void *)opara_k_group_f16_heavy)
-             : (light ? (void *)opara_k_group_f32_light : (void *)opara_k_group_f32_heavy);
+void *group_func(bool f16, int flavor) {
+  static void *const f[2][3] = {
+      {(void *)opara_k_group_f32_stream, (void *)opara_k_group_f32_light, (void *)opara_k_group_f32_heavy},
+      {(void *)opara_k_group_f16_stream, (void *)opara_k_group_f16_light, (void *)opara_k_group_f16_heavy}};
+  return f[f16 ? 1 : 0][flavor < 0 ? 0 : flavor > 2 ? 2 : flavor];
 }
 }  // namespace
 
-bool group_kernel_ok(int id, bool *light) {
+int group_flavor(int id) {
   switch (id) {
     case K_igemm_f16_t128x64: case K_igemm_f32_t128x64: case K_igemm_f16_quad4: case K_igemm_f32_quad4:
     case K_igemm_f16_quad64x4: case K_igemm_f32_quad64x4:
-      *light = false;
-      return true;
+      return 2;
     case K_igemm_f16_direct8: case K_igemm_f32_direct8: case K_igemm_f16_quad8: case K_igemm_f32_quad8:
-      return false;                       // 512-thread bodies
+      return -1;                          // 512-thread bodies
+    case K_igemm_f16_t64x64: case K_igemm_f32_t64x64: case K_igemm_f16_direct4: case K_igemm_f32_direct4:
+    case K_igemm_f16_direct4s: case K_igemm_f32_direct4s: case K_igemm_f16_quad4s: case K_igemm_f32_quad4s:
+    case K_igemm_f16_t64x64_scalar: case K_igemm_f32_t64x64_scalar:
+      return 1;
     default:
-      *light = true;
-      return id >= 0 && id < K_COUNT;
+      return id >= 0 && id < K_COUNT ? 0 : -1;
   }
+}
+
+bool group_kernel_ok(int id, bool *light) {
+  const int f = group_flavor(id);
+  *light = f >= 0 && f < 2;
+  return f >= 0;
 }
 
 hipError_t group_prepare(uint32_t max_lds_bytes) {
   for (int f16 = 0; f16 < 2; ++f16)
-    for (int light = 0; light < 2; ++light) {
-      hipError_t err = hipFuncSetAttribute(group_func(f16, light), hipFuncAttributeMaxDynamicSharedMemorySize,
+    for (int flavor = 0; flavor < 3; ++flavor) {
+      hipError_t err = hipFuncSetAttribute(group_func(f16, flavor), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)max_lds_bytes);
       if (err != hipSuccess) return err;
     }
   return hipSuccess;
 }
 
-hipError_t add_group_node(hipGraph_t graph, bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks,
+hipError_t add_group_node(hipGraph_t graph, bool f16, int flavor, const GroupArgs &ga, uint32_t n_blocks,
                           uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node) {
   GroupArgs args = ga;
   void *kparams[1] = {&args};
   hipKernelNodeParams np = {};
-  np.func = group_func(f16, light);
+  np.func = group_func(f16, flavor);
   np.gridDim = dim3(n_blocks);
   np.blockDim = dim3(256);
   np.sharedMemBytes = lds_bytes;
@@ -2275,15 +2300,10 @@ hipError_t add_group_node(hipGraph_t graph, bool f16, bool light, const GroupArg
   return hipGraphAddKernelNode(node, graph, deps, n_deps, &np);
 }
 
-hipError_t launch_group(bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s) {
-  if (f16) {
-    if (light) hipLaunchKernelGGL(opara_k_group_f16_light, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
-    else hipLaunchKernelGGL(opara_k_group_f16_heavy, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
-  } else {
-    if (light) hipLaunchKernelGGL(opara_k_group_f32_light, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
-    else hipLaunchKernelGGL(opara_k_group_f32_heavy, dim3(n_blocks), dim3(256), lds_bytes, s, ga);
-  }
-  return hipGetLastError();
+hipError_t launch_group(bool f16, int flavor, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s) {
+  GroupArgs args = ga;
+  void *kparams[1] = {&args};
+  return hipLaunchKernel(group_func(f16, flavor), dim3(n_blocks), dim3(256), kparams, lds_bytes, s);
 }
 
 namespace {

@@ -16,9 +16,11 @@ hipError_t add_noop_node(hipGraph_t graph, const hipGraphNode_t *deps, size_t n_
 // Group nodes (fused executor): whether a kernel's body can run inside a group kernel at
 // all (256-thread bodies) and inside the light flavour (at most 128 vector registers).
 bool group_kernel_ok(int kernel_id, bool *light);
-hipError_t add_group_node(hipGraph_t graph, bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks,
+// Flavour of group kernel a body needs: 0 stream (at most 64 vector registers), 1 light (128), 2 heavy; -1 none.
+int group_flavor(int kernel_id);
+hipError_t add_group_node(hipGraph_t graph, bool f16, int flavor, const GroupArgs &ga, uint32_t n_blocks,
                           uint32_t lds_bytes, const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
-hipError_t launch_group(bool f16, bool light, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s);
+hipError_t launch_group(bool f16, int flavor, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s);
 hipError_t group_prepare(uint32_t max_lds_bytes);   // raises the dynamic LDS limit of the group kernels once
 
 // Dependency self-check (see opara_verify_dependencies): a token node marks its
