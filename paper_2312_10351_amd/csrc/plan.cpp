@@ -147,7 +147,15 @@ int plan_igemm(const opara_op_desc &op, const void *const *in, int kind, KernelP
       // variant that loads MFMA fragments as they are.
       static const int ids[2][4] = {{K_igemm_f32_direct4, K_igemm_f32_direct8, K_igemm_f32_quad4, K_igemm_f32_quad8},
                                     {K_igemm_f16_direct4, K_igemm_f16_direct8, K_igemm_f16_quad4, K_igemm_f16_quad8}};
-      const bool quad = !persistent && (int64_t)a.K * (f16 ? 2 : 4) >= kQuadMinRowBytes;
+      // Convolutions with a tile or more for every other compute unit and rows of K up to 2 KiB
+      // keep the fragment-loading kernel: with that many workgroups its four resident
+      // workgroups per CU (105 registers against 211) hide more latency than the faster
+      // loads of the quad-coalesced one save (GoogLeNet-like stem 3x3: 10.6 -> 9.2 us).  GEMMs
+      // of that shape are better off with the quad-coalesced kernel (BERT-like FFN: measured).
+      const int64_t row_bytes = (int64_t)a.K * (f16 ? 2 : 4);
+      const int64_t tiles32q = (int64_t)cdiv(a.M, kDirectTile) * cdiv(a.N, kDirectTile) * batch;
+      const bool quad = !persistent && row_bytes >= kQuadMinRowBytes &&
+                        !(a.gather && tiles32q >= kQuadFourWaveTiles && row_bytes <= 2 * kQuadMinRowBytes);
       int waves;
       // Deep K on few tiles: eight wavefronts share it (latency).  With a tile or more per
       // compute unit, four: more workgroups per CU overlap better than longer ones.
