@@ -284,7 +284,12 @@ int32_t opara_num_ops(const opara_dag *g);
  *                           has its nodes switched to the operators' kernels, in place.
  *                           After a violation a fresh instance of the SAME graph is
  *                           tried, up to four; the streams and the launch queue are never
- *                           replaced.  EGRAPH if no instance passes.
+ *                           replaced.  EGRAPH if no instance passes.  No node is given
+ *                           more than four successors: further consumers of a producer
+ *                           depend on it through a chain of relay nodes without work
+ *                           (every failure seen involved nodes with 7-15 successors), so
+ *                           the graph can hold more nodes and edges than the plan has
+ *                           operators and dependencies (opara_exec_info).
  *   OPARA_PARALLEL_CAPTURE  obtains the same graph the paper's way: the streams are put
  *                           into one stream capture, every operator is launched on its
  *                           stream in launch-queue order with event record / wait on
