@@ -88,6 +88,14 @@ def test_error_paths():
     out = C.c_void_p()
     assert lib.opara_capture(dag, handles, 1, B.PARALLEL, C.byref(out)) == B.ESTATE
     assert b"opara_assign_streams" in lib.opara_last_error()
+    assert lib.opara_capture(dag, handles, 1, B.FUSED, C.byref(out)) == B.ESTATE        # needs a launch queue
+    assert lib.opara_capture(dag, handles, 1, 99, C.byref(out)) == B.EINVAL
+    ws = C.c_uint64()
+    assert lib.opara_chained_workspace_bytes(dag, C.byref(ws)) == B.OK and ws.value % 256 == 0
+    assert lib.opara_capture_chained(dag, C.c_void_p(0x100000), ws.value, C.byref(out)) == B.ESTATE
+    assert lib.opara_wave_of(dag, None, None) == B.EINVAL
+    assert lib.opara_elide_concats(None, 1, None, 0, None, None, None, None, None) == B.EINVAL
+    assert lib.opara_run_persistent_noalloc(dag, None, None) == B.ESTATE
     B.opara_dag_destroy(dag)
 
 
