@@ -344,6 +344,45 @@ def test_fused_executor_splits_wide_waves_and_keeps_single_operators_as_kernel_n
         s.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_degenerate_dags_in_every_executor(dtype):
+    """One operator; a pure chain (no two operators can run together: the fused executor has
+    one node per operator); seventeen independent operators (one more than a group node holds)."""
+    b = Builder("single", dtype)
+    b.conv(b.ext((8, 5, 5)), 8, 3, pad=1)
+    run_modes(b.build(1, random_bias=True), modes=("eager", "seq", "par", "persist", "chain", "fused"))
+
+    b = Builder("chain", dtype)
+    x = b.ext((16, 9, 9))
+    for i in range(6):
+        x = b.conv(x, 16, 3 if i % 2 else 1, pad=i % 2)
+    x = b.gavgpool(x)
+    wl = b.build(2, he_init=True)
+    run_modes(wl, modes=("seq", "par", "persist", "chain", "fused"))
+    s = Session(wl)
+    try:
+        exe = s.capture(B.FUSED)
+        assert B.opara_fused_plan(exe, len(wl.ops))[1] == len(wl.ops) and B.opara_wave_of(s.dag)[1] == len(wl.ops)
+        assert s.schedule()[1] == 1                      # one stream, no synchronisation
+    finally:
+        s.close()
+
+    b = Builder("seventeen", dtype)
+    m = b.ext((33, 72))
+    for i in range(17):
+        b.rowwise(("relu", "gelu", "softmax", "layernorm", "add")[i % 5], [m], 33, 72, {"eps": 1e-5})
+    wl = b.build(3)
+    run_modes(wl, modes=("seq", "par", "persist", "chain", "fused"))
+    s = Session(wl)
+    try:
+        exe = s.capture(B.FUSED)
+        node_of, nodes = B.opara_fused_plan(exe, 17)
+        assert nodes == 2 and node_of.count(0) == 16 and node_of.count(1) == 1
+        assert B.opara_fused_node_kernels(exe, dtype)[0] == f"group_{dtype}_stream"
+    finally:
+        s.close()
+
+
 # ------------------------------------------------------------------ graph structure
 def test_graph_structure_and_replay_determinism():
     wl = googlenet_like()
