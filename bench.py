@@ -252,6 +252,10 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
         else:
             kern = res["dominant_graph_kernel"]
         res["roofline"] = kern
+        # ---- overlap measured inside the kernels (operator timeline: no profiler attached)
+        from paper_2312_10351_amd.timeline import operator_overlap
+        res["operator_overlap"] = {name: operator_overlap(s.operator_trace(mode))
+                                   for name, mode in (("sequential", B.SEQUENTIAL), ("multi_stream_graph", B.PARALLEL), ("fused", B.FUSED))}
         # ---- the oracle on the host cores, and the timed executor's result against it
         if cpu_budget_s > 0:
             block, ref = oracle_pass(wl, cpu_budget_s, one_thread=index == 1)

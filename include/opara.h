@@ -534,6 +534,23 @@ int opara_replay(opara_exec *e, void *hip_stream);
 int opara_exec_info(const opara_exec *e, int32_t *n_nodes, int32_t *n_edges);
 
 /*
+ * Operator timeline (tracing; what the paper reads off a profiler's timeline, Sec. 5.2,
+ * taken inside the kernels so that the measurement does not move them).  Executors that are
+ * CAPTURED while a buffer is set (sequential graph, multi-stream graph, fused executor), and
+ * eager launches made meanwhile, hand the buffer to their kernels as an argument: the
+ * operator's first workgroup then folds the 100 MHz device clock at its start into word
+ * 2*op (minimum) and its last eight workgroups, in dispatch order, the clock at their end
+ * into word 2*op + 1 (maximum; uint64 each; op = the operator's id in its DAG).  Executors captured while no buffer is set carry a
+ * null pointer and pay one scalar compare per workgroup.
+ * device_buffer: device memory, caller-owned, 16 bytes per operator, initialised by the
+ * caller to (all ones, zero) before every replay it wants stamped, valid as long as any
+ * executor captured with it is replayed; NULL ends the setting for later captures.  The
+ * setting is per process.  No HIP call.  The persistent and chained executors have their
+ * own per-tile timeline (opara_persistent_set_trace).
+ */
+int opara_set_operator_trace(void *device_buffer);
+
+/*
  * Launch ONE operator's kernel, or all operators in topological order, eagerly on a
  * stream (no graph).  Used for profiling an operator in isolation (paper Sec. 3.2:
  * profile once) and for debugging.

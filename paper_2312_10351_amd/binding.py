@@ -70,7 +70,7 @@ EXPORTS = ["opara_build_dag", "opara_elide_concats", "opara_assign_streams", "op
            "opara_persistent_reset", "opara_persistent_info", "opara_persistent_plan", "opara_persistent_prefix", "opara_persistent_time_kernel",
            "opara_persistent_set_trace",
            "opara_run_persistent_noalloc", "opara_chained_workspace_bytes", "opara_capture_chained",
-           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_fused_plan", "opara_fused_time_nodes", "opara_launch_op", "opara_run_eager",
+           "opara_replay", "opara_verify_dependencies", "opara_exec_info", "opara_exec_validation", "opara_set_operator_trace", "opara_fused_plan", "opara_fused_time_nodes", "opara_launch_op", "opara_run_eager",
            "opara_kernel_count", "opara_kernel_info", "opara_kernel_device_attrs",
            "opara_exec_destroy", "opara_dag_destroy", "opara_last_error"]
 
@@ -117,6 +117,7 @@ def load():
     lib.opara_verify_dependencies.argtypes = [vp, vp, i32p]
     lib.opara_exec_info.argtypes = [vp, i32p, i32p]
     lib.opara_exec_validation.argtypes = [vp, i32p, i32p]
+    lib.opara_set_operator_trace.argtypes = [vp]
     lib.opara_fused_plan.argtypes = [vp, i32p, i32p, i32p]
     lib.opara_fused_time_nodes.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_float)]
     lib.opara_run_persistent_noalloc.argtypes = [vp, vp, C.POINTER(C.c_uint32)]
@@ -363,6 +364,10 @@ def opara_fused_time_nodes(exe, stream_handle, launches):
     us = (C.c_float * n.value)()
     _check(load().opara_fused_time_nodes(exe, C.c_void_p(stream_handle), launches, us))
     return list(us)
+
+
+def opara_set_operator_trace(device_ptr):
+    _check(load().opara_set_operator_trace(C.c_void_p(device_ptr)))
 
 
 def opara_exec_validation(exe):

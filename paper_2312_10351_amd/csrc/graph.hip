@@ -210,6 +210,7 @@ int capture_fused(opara_dag *g, opara_exec **out) {
         node.flavor = 0;
         std::memset(&node.ga, 0, sizeof node.ga);
         node.ga.n = (int32_t)members.size();
+        node.ga.trace = (unsigned long long *)current_op_trace();
         int64_t end = 0;
         for (size_t i = 0; i < members.size(); ++i) {
           const KernelPlan &p = g->plan_group[members[i]];
@@ -221,6 +222,7 @@ int capture_fused(opara_dag *g, opara_exec **out) {
           node.ga.kernel[i] = p.kernel;
           node.ga.gx[i] = (int32_t)p.gx; node.ga.gy[i] = (int32_t)p.gy;
           node.ga.tiles[i] = (int32_t)tiles;
+          node.ga.tag[i] = members[i];
           node.ga.args[i] = p.args;
           node.lds = std::max(node.lds, kKernelResources[p.kernel].lds_bytes);
         }
@@ -1074,6 +1076,12 @@ fail:
   if (t0) (void)hipEventDestroy(t0);
   if (t1) (void)hipEventDestroy(t1);
   return OPARA_EHIP;
+}
+
+extern "C" int opara_set_operator_trace(void *device_buffer) {
+  hipError_t err = set_op_trace(device_buffer);
+  if (err != hipSuccess) { set_error("opara_set_operator_trace: %s", hipGetErrorString(err)); (void)hipGetLastError(); return OPARA_EHIP; }
+  return OPARA_OK;
 }
 
 extern "C" int opara_exec_validation(const opara_exec *e, int32_t *kind, int32_t *attempts) {

@@ -135,6 +135,7 @@ struct KernelPlan {
   int32_t kernel;
   uint32_t gx, gy, gz;
   uint32_t block;
+  int32_t tag;                  // operator id: second kernel argument, slot of the operator timeline
   KernelArgs args;
 };
 
@@ -152,6 +153,8 @@ struct GroupArgs {
   int32_t kernel[kGroupMaxOps];                    // KernelId of the operator's body
   int32_t gx[kGroupMaxOps], gy[kGroupMaxOps];     // the operator's own grid (x, y; z follows)
   int32_t tiles[kGroupMaxOps];                     // gx * gy * gz
+  int32_t tag[kGroupMaxOps];                       // operator ids (slots of the operator timeline)
+  unsigned long long *trace;                       // operator-timeline buffer, null = off
   KernelArgs args[kGroupMaxOps];
 };
 

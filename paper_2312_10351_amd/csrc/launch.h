@@ -128,6 +128,10 @@ hipError_t add_chain_node(hipGraph_t graph, bool f16, bool light, const ChainArg
                           const hipGraphNode_t *deps, size_t n_deps, hipGraphNode_t *node);
 hipError_t launch_chain(bool f16, bool light, const ChainArgs &a, uint32_t lds_bytes, hipStream_t s);
 
+// Operator timeline: device buffer of two 64-bit words per operator id, or nullptr to switch it off.
+hipError_t set_op_trace(void *device_buffer);
+void *current_op_trace();
+
 hipError_t verify_reset(hipStream_t s);            // clears tokens and the violation counter
 hipError_t verify_read(hipStream_t s, int *viol, int *op = nullptr, int *pred = nullptr);  // synchronises s; the counter and the last violation
 

@@ -153,6 +153,7 @@ extern "C" int opara_build_dag(const opara_op_desc *ops, int32_t n_ops, void *co
       if (rc == OPARA_OK) rc = plan_op(op, in, kPlanPersistent, &g->plan_persist[v]);
       if (rc == OPARA_OK) rc = plan_op(op, in, kPlanGroup, &g->plan_group[v]);
       if (rc != OPARA_OK) { delete g; return rc; }
+      g->plan[v].tag = g->plan_persist[v].tag = g->plan_group[v].tag = v;
       const KernelPlan &p = g->plan[v];
       const KernelResource &r = kKernelResources[p.kernel];
       opara_demand &d = g->dem[v];

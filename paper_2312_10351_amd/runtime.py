@@ -318,6 +318,33 @@ class Session:
         pos = (raw[:, 3:4] >> 32) + B.opara_persistent_prefix(exe)
         return np.concatenate([t, pos, (raw[:, 3:4] & 0xffffffff)], axis=1)
 
+    def operator_trace(self, mode, policy=B.ORDER_ALG2, replays=3):
+        """Capture the sequential / multi-stream / fused executor with the operator timeline on and
+        replay it.  Returns an int64 array [library operators, 2]: earliest start and latest end of
+        every operator's kernel in the last replay, ns from the first start (-1: no stamp)."""
+        import torch
+        n = len(self.lib_ops)
+        buf = torch.empty(n, 2, dtype=torch.int64, device=self.device)
+        torch.cuda.synchronize()
+        B.opara_set_operator_trace(buf.data_ptr())
+        try:
+            exe = self.capture(mode, policy=policy)
+        finally:
+            B.opara_set_operator_trace(0)
+        for _ in range(replays):
+            buf[:, 0] = -1                              # all ones: the minimum folds into it
+            buf[:, 1] = 0
+            torch.cuda.synchronize()
+            self.replay(exe)
+        raw = buf.cpu().numpy()
+        self._keep.append(buf)                          # the executor keeps the address
+        ok = (raw[:, 0] != -1) & (raw[:, 1] != 0)
+        t = raw.astype(np.int64) * 10                   # 100 MHz ticks -> ns
+        t0 = t[ok, 0].min() if ok.any() else 0
+        t = t - t0
+        t[~ok] = -1
+        return t
+
     def persistent_status(self, exe):
         return B.opara_persistent_status(exe, self.make_streams(1).handles[0])
 

@@ -8,6 +8,11 @@ busy fraction of the workgroups).  It is the counterpart of a kernel-trace timel
 multi-stream graph (paper Sec. 5.3 looks at the same thing through SM utilisation).
 
   python -m paper_2312_10351_amd.timeline [--config 1] [--policy alg2] [--rows 200] [--zero-copy-concat]
+  python -m paper_2312_10351_amd.timeline --executor par|seq|fused [--config 1] ...
+
+With --executor par / seq / fused it prints the operator timeline of a graph executor instead:
+every operator kernel stamps its own start and end (opara_set_operator_trace), so the
+overlap of the multi-stream graph is measured without a profiler attached.
 """
 import argparse
 import json
@@ -70,6 +75,53 @@ def timeline_summary(session, exe):
                 median_wait_for_predecessors_us=float(np.median(tr[:, 1] - tr[:, 0])) / 1e3)
 
 
+def operator_overlap(t):
+    """Concurrency of operator kernels from an operator timeline ([ops, 2] start / end in ns,
+    Session.operator_trace): span, share of the span with 0, 1, 2, ... operators in flight,
+    mean and peak."""
+    iv = t[(t[:, 0] >= 0) & (t[:, 1] > t[:, 0])]
+    if len(iv) == 0:
+        return dict(operators_stamped=0)
+    ev = sorted([(int(a), 1) for a in iv[:, 0]] + [(int(b), -1) for b in iv[:, 1]])
+    t0, t1 = ev[0][0], max(int(b) for b in iv[:, 1])
+    cur, peak, prev, hist = 0, 0, t0, {}
+    for when, d in ev:
+        hist[cur] = hist.get(cur, 0) + (when - prev)
+        prev, cur = when, cur + d
+        peak = max(peak, cur)
+    span = max(t1 - t0, 1)
+    busy = int((iv[:, 1] - iv[:, 0]).sum())
+    return dict(operators_stamped=int(len(iv)), span_us=span / 1e3, sum_of_operator_durations_us=busy / 1e3,
+                operators_in_flight_peak=peak, operators_in_flight_mean=busy / span,
+                time_share_by_operators_in_flight={str(k): round(v / span, 4) for k, v in sorted(hist.items())},
+                share_with_two_or_more=round(sum(v for k, v in hist.items() if k >= 2) / span, 4))
+
+
+def graph_timeline(config, mode, zero_copy, rows, policy):
+    """Operator timeline of one replay of the sequential / multi-stream / fused executor."""
+    from . import binding as B
+    from .runtime import Session
+    from workloads import build_config
+    s = Session(build_config(config), zero_copy_concat=zero_copy)
+    try:
+        m = {"seq": B.SEQUENTIAL, "par": B.PARALLEL, "fused": B.FUSED}[mode]
+        t = s.operator_trace(m, policy=policy, replays=5)
+        exe = s.execs[-1]
+        order = sorted(range(len(t)), key=lambda v: t[v, 0])
+        so = B.opara_assign_streams(s.dag)[0]
+        node_of = B.opara_fused_plan(exe, len(s.lib_ops))[0] if mode == "fused" else None
+        print(f"| operator | name | {'node' if mode == 'fused' else 'stream'} | start us | end us | duration us |")
+        print("|---|---|---|---|---|---|")
+        for v in order[:rows]:
+            op = s.wl.ops[s.lib_ops[v]]
+            where = node_of[v] if node_of else so[v]
+            print(f"| {v} | {op.name or op.type} | {where} | {t[v, 0] / 1e3:.2f} | {t[v, 1] / 1e3:.2f} | {(t[v, 1] - t[v, 0]) / 1e3:.2f} |")
+        print()
+        print(json.dumps(dict(workload=s.wl.name, executor=mode, zero_copy_concat=zero_copy, **operator_overlap(t))))
+    finally:
+        s.close()
+
+
 def main():
     from . import binding as B
     from .runtime import Session
@@ -79,8 +131,14 @@ def main():
     ap.add_argument("--policy", default="alg2", choices=list(B.ORDER_POLICY_NAMES))
     ap.add_argument("--rows", type=int, default=200)
     ap.add_argument("--zero-copy-concat", action="store_true")
+    ap.add_argument("--executor", default="persist", choices=["persist", "seq", "par", "fused"],
+                    help="persist: per-tile timeline of the persistent executor; seq / par / fused: operator timeline "
+                         "(start and end of every operator's kernel, stamped inside the kernels) and its overlap summary")
     a = ap.parse_args()
     pol = list(B.ORDER_POLICY_NAMES).index(a.policy)
+    if a.executor != "persist":
+        graph_timeline(a.config, a.executor, a.zero_copy_concat, a.rows, pol)
+        return
     s = Session(build_config(a.config), zero_copy_concat=a.zero_copy_concat)
     try:
         exe = s.capture_persistent(policy=pol)

@@ -426,3 +426,28 @@ def test_kernel_table_matches_loaded_code_objects():
         dvg, dlds = B.opara_kernel_device_attrs(i)
         assert lds == dlds, name
         assert dvg <= vg + 8 and vg <= dvg + 8, (name, vg, dvg)   # allocation granule rounding
+
+
+def test_operator_timeline_respects_the_dag():
+    """The in-kernel operator timeline: every operator leaves a stamp, no operator starts
+    before the last workgroup of each predecessor has ended (up to the stamping delay), the
+    sequential graph never has two operators in flight, and outputs are unchanged."""
+    from paper_2312_10351_amd.timeline import operator_overlap
+    wl = googlenet_like(he_init=True)
+    ref = executor.run_dag(wl)
+    s = Session(wl)
+    try:
+        for mode in (B.SEQUENTIAL, B.PARALLEL, B.FUSED):
+            t = s.operator_trace(mode)
+            assert (t[:, 0] >= 0).all() and (t[:, 1] > t[:, 0]).all()
+            for u, v in wl.edges():
+                assert t[v, 0] + 500 >= t[u, 1], (mode, u, v, t[u], t[v])      # ns; the end stamp precedes the kernel's end
+            ov = operator_overlap(t)
+            assert ov["operators_stamped"] == len(wl.ops)
+            if mode == B.SEQUENTIAL:
+                assert ov["operators_in_flight_peak"] == 1
+            if mode == B.FUSED:
+                assert ov["operators_in_flight_peak"] >= 3
+            assert not compare_all(s, ref, outlier_frac=1e-3)
+    finally:
+        s.close()
