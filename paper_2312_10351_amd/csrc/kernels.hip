@@ -1857,7 +1857,7 @@ extern "C" __global__ void __launch_bounds__(256, 2) opara_k_persist_f32(Persist
 // resident, which streaming wants), "light" (at most 128: those plus the fragment-loading
 // and 16 x 16-tile contractions; four per SIMD), "heavy" (all 256-thread bodies; two).
 // ---------------------------------------------------------------------------------
-template <bool F16, int FLAVOR>
+template <bool F16, int FLAVOR, bool TRACE>
 __device__ __forceinline__ void group_body() {
   // The record is the kernel's only argument and therefore starts the kernel-argument
   // segment.  It is read in place through the segment pointer: indexing the by-value
@@ -1880,8 +1880,10 @@ __device__ __forceinline__ void group_body() {
   b.y = rest % b.gy;
   b.z = rest / b.gy;
   unsigned char *lds = dyn_lds;
-  const int tag = ga.tag[i];
-  const unsigned long long t0 = op_trace_begin();
+  // traced instances are separate kernels: even an unused clock read at the start of this
+  // kernel's chain of dependent scalar loads cost every group node 0.4 us
+  const int tag = TRACE ? ga.tag[i] : 0;
+  const unsigned long long t0 = TRACE ? op_trace_begin() : 0ull;
 #define GCASE(name, Args, call)                               \
   case K_##name: {                                            \
     typedef const Args __attribute__((address_space(4))) CA;  \
@@ -1966,15 +1968,19 @@ __device__ __forceinline__ void group_body() {
     }
   }
 #undef GCASE
-  op_trace_end(ga.trace, tag, t0, (unsigned)tile, (unsigned)ga.tiles[i]);
+  if constexpr (TRACE) op_trace_end(ga.trace, tag, t0, (unsigned)tile, (unsigned)ga.tiles[i]);
 }
 
-extern "C" __global__ void __launch_bounds__(256, 8) opara_k_group_f16_stream(GroupArgs) { group_body<true, 0>(); }
-extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f16_light(GroupArgs) { group_body<true, 1>(); }
-extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f16_heavy(GroupArgs) { group_body<true, 2>(); }
-extern "C" __global__ void __launch_bounds__(256, 8) opara_k_group_f32_stream(GroupArgs) { group_body<false, 0>(); }
-extern "C" __global__ void __launch_bounds__(256, 4) opara_k_group_f32_light(GroupArgs) { group_body<false, 1>(); }
-extern "C" __global__ void __launch_bounds__(256, 2) opara_k_group_f32_heavy(GroupArgs) { group_body<false, 2>(); }
+#define GROUPK(name, waves, F16, FLAVOR)                                                                                          \
+  extern "C" __global__ void __launch_bounds__(256, waves) opara_k_group_##name(GroupArgs) { group_body<F16, FLAVOR, false>(); }     \
+  extern "C" __global__ void __launch_bounds__(256, waves) opara_k_group_##name##_traced(GroupArgs) { group_body<F16, FLAVOR, true>(); }
+GROUPK(f16_stream, 8, true, 0)
+GROUPK(f16_light, 4, true, 1)
+GROUPK(f16_heavy, 2, true, 2)
+GROUPK(f32_stream, 8, false, 0)
+GROUPK(f32_light, 4, false, 1)
+GROUPK(f32_heavy, 2, false, 2)
+#undef GROUPK
 
 // ---------------------------------------------------------------------------------
 // Chained executor: every workgroup runs one tile of one operator behind a wait for the
@@ -2284,11 +2290,13 @@ hipError_t add_token_node(hipGraph_t graph, const TokenNodeArgs &t, const hipGra
 }
 
 namespace {
-void *group_func(bool f16, int flavor) {
-  static void *const f[2][3] = {
-      {(void *)opara_k_group_f32_stream, (void *)opara_k_group_f32_light, (void *)opara_k_group_f32_heavy},
-      {(void *)opara_k_group_f16_stream, (void *)opara_k_group_f16_light, (void *)opara_k_group_f16_heavy}};
-  return f[f16 ? 1 : 0][flavor < 0 ? 0 : flavor > 2 ? 2 : flavor];
+void *group_func(bool f16, int flavor, bool traced) {
+  static void *const f[2][2][3] = {
+      {{(void *)opara_k_group_f32_stream, (void *)opara_k_group_f32_light, (void *)opara_k_group_f32_heavy},
+       {(void *)opara_k_group_f16_stream, (void *)opara_k_group_f16_light, (void *)opara_k_group_f16_heavy}},
+      {{(void *)opara_k_group_f32_stream_traced, (void *)opara_k_group_f32_light_traced, (void *)opara_k_group_f32_heavy_traced},
+       {(void *)opara_k_group_f16_stream_traced, (void *)opara_k_group_f16_light_traced, (void *)opara_k_group_f16_heavy_traced}}};
+  return f[traced ? 1 : 0][f16 ? 1 : 0][flavor < 0 ? 0 : flavor > 2 ? 2 : flavor];
 }
 }  // namespace
 
@@ -2316,11 +2324,12 @@ bool group_kernel_ok(int id, bool *light) {
 
 hipError_t group_prepare(uint32_t max_lds_bytes) {
   for (int f16 = 0; f16 < 2; ++f16)
-    for (int flavor = 0; flavor < 3; ++flavor) {
-      hipError_t err = hipFuncSetAttribute(group_func(f16, flavor), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)max_lds_bytes);
-      if (err != hipSuccess) return err;
-    }
+    for (int flavor = 0; flavor < 3; ++flavor)
+      for (int traced = 0; traced < 2; ++traced) {
+        hipError_t err = hipFuncSetAttribute(group_func(f16, flavor, traced), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)max_lds_bytes);
+        if (err != hipSuccess) return err;
+      }
   return hipSuccess;
 }
 
@@ -2329,7 +2338,7 @@ hipError_t add_group_node(hipGraph_t graph, bool f16, int flavor, const GroupArg
   GroupArgs args = ga;
   void *kparams[1] = {&args};
   hipKernelNodeParams np = {};
-  np.func = group_func(f16, flavor);
+  np.func = group_func(f16, flavor, ga.trace != nullptr);
   np.gridDim = dim3(n_blocks);
   np.blockDim = dim3(256);
   np.sharedMemBytes = lds_bytes;
@@ -2340,7 +2349,7 @@ hipError_t add_group_node(hipGraph_t graph, bool f16, int flavor, const GroupArg
 hipError_t launch_group(bool f16, int flavor, const GroupArgs &ga, uint32_t n_blocks, uint32_t lds_bytes, hipStream_t s) {
   GroupArgs args = ga;
   void *kparams[1] = {&args};
-  return hipLaunchKernel(group_func(f16, flavor), dim3(n_blocks), dim3(256), kparams, lds_bytes, s);
+  return hipLaunchKernel(group_func(f16, flavor, ga.trace != nullptr), dim3(n_blocks), dim3(256), kparams, lds_bytes, s);
 }
 
 namespace {
