@@ -84,7 +84,7 @@ def batch_sweep(batch, replays):
 
 def concat_ablation(index, replays):
     """Zero-copy concatenation (branches write channel slices in place, the concatenation
-    operators disappear) against explicit concatenation kernels, in all three executors."""
+    operators disappear) against explicit concatenation kernels, per executor."""
     from . import binding as B
     from .runtime import Session
     from workloads import build_config
