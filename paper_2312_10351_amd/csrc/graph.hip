@@ -211,6 +211,7 @@ int capture_fused(opara_dag *g, opara_exec **out) {
         std::memset(&node.ga, 0, sizeof node.ga);
         node.ga.n = (int32_t)members.size();
         node.ga.trace = (unsigned long long *)current_op_trace();
+        for (int j = 0; j < kGroupMaxOps; ++j) node.ga.block_end[j] = INT32_MAX;
         int64_t end = 0;
         for (size_t i = 0; i < members.size(); ++i) {
           const KernelPlan &p = g->plan_group[members[i]];
@@ -218,11 +219,12 @@ int capture_fused(opara_dag *g, opara_exec **out) {
           node.f16 = kernel_is_f16(p.kernel);
           const int64_t tiles = (int64_t)p.gx * p.gy * p.gz;
           end += (tiles + kGroupAlign - 1) / kGroupAlign * kGroupAlign;
+          node.ga.meta[i].block_begin = i ? node.ga.block_end[i - 1] : 0;
           node.ga.block_end[i] = (int32_t)end;
-          node.ga.kernel[i] = p.kernel;
-          node.ga.gx[i] = (int32_t)p.gx; node.ga.gy[i] = (int32_t)p.gy;
-          node.ga.tiles[i] = (int32_t)tiles;
-          node.ga.tag[i] = members[i];
+          node.ga.meta[i].kernel = p.kernel;
+          node.ga.meta[i].gx = (int32_t)p.gx; node.ga.meta[i].gy = (int32_t)p.gy;
+          node.ga.meta[i].tiles = (int32_t)tiles;
+          node.ga.meta[i].tag = members[i];
           node.ga.args[i] = p.args;
           node.lds = std::max(node.lds, kKernelResources[p.kernel].lds_bytes);
         }

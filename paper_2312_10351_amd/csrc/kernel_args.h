@@ -146,15 +146,20 @@ struct KernelPlan {
 // t % 8 as in a launch of its own.  The record travels by value as the kernel argument.
 constexpr int kGroupMaxOps = 16;
 constexpr int kGroupAlign = 8;
+struct GroupMeta {                                 // one member: read with one 32-byte scalar load
+  int32_t kernel;                                  // KernelId of the operator's body
+  int32_t gx, gy;                                  // the operator's own grid (x, y; z follows)
+  int32_t tiles;                                   // gx * gy * gz
+  int32_t tag;                                     // operator id (slot of the operator timeline)
+  int32_t block_begin;                             // first block of the member's range
+  int32_t reserved[2];
+};
 struct GroupArgs {
   int32_t n;
-  int32_t reserved[3];
-  int32_t block_end[kGroupMaxOps];
-  int32_t kernel[kGroupMaxOps];                    // KernelId of the operator's body
-  int32_t gx[kGroupMaxOps], gy[kGroupMaxOps];     // the operator's own grid (x, y; z follows)
-  int32_t tiles[kGroupMaxOps];                     // gx * gy * gz
-  int32_t tag[kGroupMaxOps];                       // operator ids (slots of the operator timeline)
+  int32_t reserved;
   unsigned long long *trace;                       // operator-timeline buffer, null = off
+  int32_t block_end[kGroupMaxOps];
+  GroupMeta meta[kGroupMaxOps];
   KernelArgs args[kGroupMaxOps];
 };
 

@@ -1867,13 +1867,25 @@ __device__ __forceinline__ void group_body() {
   CGA &ga = *(CGA *)__builtin_amdgcn_kernarg_segment_ptr();
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_lds[];
   const int blk = (int)blockIdx.x;
+  // The member this block belongs to: all sixteen range ends arrive with one 64-byte load
+  // (unused entries hold INT32_MAX), the member is the number of ends at or below the block.
   int i = 0;
-  while (i + 1 < ga.n && blk >= ga.block_end[i]) ++i;            // uniform: a handful of scalar compares
+#pragma unroll
+  for (int j = 0; j < kGroupMaxOps - 1; ++j) i += blk >= ga.block_end[j] ? 1 : 0;
   i = __builtin_amdgcn_readfirstlane(i);
-  const int tile = blk - (i ? ga.block_end[i - 1] : 0);
-  if (tile >= ga.tiles[i]) return;                                 // padding of the operator's range
+  // One 32-byte load for the member's launch shape; and, in the same round, a touch of every
+  // cache line of its argument record, so that the body's own argument loads (which the
+  // compiler issues only behind the switch below) find it in the scalar cache instead of
+  // paying a third dependent memory round trip.  The touched words only feed a sink.
+  typedef const uint32_t __attribute__((address_space(4))) *CW;
+  const CW rec = (CW)&ga.args[i];
+  const uint32_t touch = (rec[0] ^ rec[16]) + (rec[32] ^ rec[47]);
+  typedef const GroupMeta __attribute__((address_space(4))) CM;
+  CM &me = ga.meta[i];
+  const int tile = blk - me.block_begin;
+  if (tile >= me.tiles) return;                                    // padding of the operator's range
   Blk b;
-  b.gx = ga.gx[i]; b.gy = ga.gy[i];
+  b.gx = me.gx; b.gy = me.gy;
   b.remap = true;
   b.x = tile % b.gx;
   const int rest = tile / b.gx;
@@ -1882,7 +1894,7 @@ __device__ __forceinline__ void group_body() {
   unsigned char *lds = dyn_lds;
   // traced instances are separate kernels: even an unused clock read at the start of this
   // kernel's chain of dependent scalar loads cost every group node 0.4 us
-  const int tag = TRACE ? ga.tag[i] : 0;
+  const int tag = TRACE ? me.tag : 0;
   const unsigned long long t0 = TRACE ? op_trace_begin() : 0ull;
 #define GCASE(name, Args, call)                               \
   case K_##name: {                                            \
@@ -1891,7 +1903,7 @@ __device__ __forceinline__ void group_body() {
     call;                                                     \
   } break;
   if constexpr (F16) {
-    switch (ga.kernel[i]) {
+    switch (me.kernel) {
       GCASE(gemv_f16, IgemmArgs, (gemv_body<half_t, 0>(a, b, lds)))
       GCASE(pool_f16_vec, PoolArgs, (pool_body<half_t, 8, 0>(a, b, lds)))
       GCASE(pool_f16_scalar, PoolArgs, (pool_body<half_t, 1, 0>(a, b, lds)))
@@ -1908,7 +1920,7 @@ __device__ __forceinline__ void group_body() {
       GCASE(concat_f16_scalar, ConcatArgs, (concat_body<half_t, 1, 0>(a, b, lds)))
       default:
         if constexpr (FLAVOR >= 1) {
-          switch (ga.kernel[i]) {
+          switch (me.kernel) {
             GCASE(igemm_f16_t64x64, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, true, 0>(a, b, lds)))
             GCASE(igemm_f16_direct4, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 2, 2>(a, b, lds)))
             GCASE(igemm_f16_direct4s, IgemmArgs, (igemm_direct_body<half_t, 4, 2, 0, 1, 1>(a, b, lds)))
@@ -1916,7 +1928,7 @@ __device__ __forceinline__ void group_body() {
             GCASE(igemm_f16_t64x64_scalar, IgemmArgs, (igemm_body<half_t, 64, 64, 2, 2, false, 0>(a, b, lds)))
             default:
               if constexpr (FLAVOR >= 2) {
-                switch (ga.kernel[i]) {
+                switch (me.kernel) {
                   GCASE(igemm_f16_t128x64, IgemmArgs, (igemm_pipe_body<half_t, 128, 64, 2, 2, 4, 0>(a, b, lds)))
                   GCASE(igemm_f16_quad4, IgemmArgs, (igemm_quad_body<half_t, 4, 0, 2, 2>(a, b, lds)))
                   GCASE(igemm_f16_quad64x4, IgemmArgs, (igemm_quad64_body<half_t, 4, 0>(a, b, lds)))
@@ -1929,7 +1941,7 @@ __device__ __forceinline__ void group_body() {
         break;
     }
   } else {
-    switch (ga.kernel[i]) {
+    switch (me.kernel) {
       GCASE(gemv_f32, IgemmArgs, (gemv_body<float, 0>(a, b, lds)))
       GCASE(pool_f32_vec, PoolArgs, (pool_body<float, 4, 0>(a, b, lds)))
       GCASE(pool_f32_scalar, PoolArgs, (pool_body<float, 1, 0>(a, b, lds)))
@@ -1946,7 +1958,7 @@ __device__ __forceinline__ void group_body() {
       GCASE(concat_f32_scalar, ConcatArgs, (concat_body<float, 1, 0>(a, b, lds)))
       default:
         if constexpr (FLAVOR >= 1) {
-          switch (ga.kernel[i]) {
+          switch (me.kernel) {
             GCASE(igemm_f32_t64x64, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, true, 0>(a, b, lds)))
             GCASE(igemm_f32_direct4, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 2, 2>(a, b, lds)))
             GCASE(igemm_f32_direct4s, IgemmArgs, (igemm_direct_body<float, 4, 2, 0, 1, 1>(a, b, lds)))
@@ -1954,7 +1966,7 @@ __device__ __forceinline__ void group_body() {
             GCASE(igemm_f32_t64x64_scalar, IgemmArgs, (igemm_body<float, 64, 64, 2, 2, false, 0>(a, b, lds)))
             default:
               if constexpr (FLAVOR >= 2) {
-                switch (ga.kernel[i]) {
+                switch (me.kernel) {
                   GCASE(igemm_f32_t128x64, IgemmArgs, (igemm_pipe_body<float, 128, 64, 2, 2, 4, 0>(a, b, lds)))
                   GCASE(igemm_f32_quad4, IgemmArgs, (igemm_quad_body<float, 4, 0, 2, 2>(a, b, lds)))
                   GCASE(igemm_f32_quad64x4, IgemmArgs, (igemm_quad64_body<float, 4, 0>(a, b, lds)))
@@ -1968,7 +1980,8 @@ __device__ __forceinline__ void group_body() {
     }
   }
 #undef GCASE
-  if constexpr (TRACE) op_trace_end(ga.trace, tag, t0, (unsigned)tile, (unsigned)ga.tiles[i]);
+  if constexpr (TRACE) op_trace_end(ga.trace, tag, t0, (unsigned)tile, (unsigned)me.tiles);
+  if (touch == 0x9e3779b9u && blk == 0x7fffffff) lds[0] = 1;       // keeps the touches alive; never true
 }
 
 #define GROUPK(name, waves, F16, FLAVOR)                                                                                          \
