@@ -146,8 +146,11 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
     from paper_2312_10351_amd.timeline import timeline_summary
     from workloads import build_config
     traffic = traffic or {}
+    import torch
     wl = build_config(index)
+    mem0 = torch.cuda.memory_allocated()
     s = Session(wl, zero_copy_concat=bool(zero_copy_concat))
+    mem_session = torch.cuda.memory_allocated() - mem0          # inputs, weights, every operator's output buffer
     if zero_copy_concat == "auto":            # wherever the library finds a concatenation to remove
         zero_copy_concat = len(s.elided) > 0
     tag = "+zero_copy_concat" if zero_copy_concat else ""
@@ -200,7 +203,9 @@ def bench_config(index, steps, warmup, zero_copy_concat="auto", cpu_budget_s=0.0
                    dag_flops=roof["flops"], dag_bytes=roof["bytes"],
                    roofline_us=dict(flops=roof["t_flops_us"], bytes=roof["t_bytes_us"], critical_path=roof["t_cp_us"],
                                     bound=roof["t_roof_us"]),
-                   roofline_fraction=roof["t_roof_us"] / r_best["median_us"])
+                   roofline_fraction=roof["t_roof_us"] / r_best["median_us"],
+                   device_memory_bytes=dict(tensors=int(mem_session), with_executor_workspaces=int(torch.cuda.memory_allocated() - mem0),
+                                            peak_during_run=int(torch.cuda.max_memory_allocated())))
         # ---- kernel-level roofline: the kernel that takes most of the best executor's time
         work = {v: roof["per_op"][s.lib_ops[v]] for v in range(len(s.lib_ops))}
         st = s.make_streams(1)
