@@ -250,7 +250,8 @@ int capture_fused(opara_dag *g, opara_exec **out) {
       for (int32_t v : wave) {
         const KernelPlan &p = g->plan_group[v];
         const int f = group_flavor(p.kernel);
-        groupable = groupable && f >= 0 && kernel_is_f16(p.kernel) == kernel_is_f16(g->plan_group[wave[0]].kernel);
+        groupable = groupable && f >= 0 && kernel_is_f16(p.kernel) == kernel_is_f16(g->plan_group[wave[0]].kernel) &&
+                    (int64_t)p.gx * p.gy * p.gz < (1 << 24);
         if (f >= 0) by_flavor[f].push_back(v);
       }
       int64_t below[3] = {0, 0, 0};                    // workgroups of all members lighter than flavour f
@@ -264,10 +265,12 @@ int capture_fused(opara_dag *g, opara_exec **out) {
       if (groupable && (cut1 || cut2)) {
         for (int f = 2; f >= 0; --f) {
           for (int32_t v : by_flavor[f]) {
-            if (members.size() == (size_t)kGroupMaxOps) flush();
+            const int64_t tiles = (int64_t)g->plan_group[v].gx * g->plan_group[v].gy * g->plan_group[v].gz;
+            if (members.size() == (size_t)kGroupMaxOps || blocks + tiles > (1 << 24)) { flush(); blocks = 0; }
             members.push_back(v);
+            blocks += tiles + kGroupAlign;
           }
-          if ((f == 2 && cut2) || (f == 1 && cut1)) flush();
+          if ((f == 2 && cut2) || (f == 1 && cut1)) { flush(); blocks = 0; }
         }
         flush();
         continue;
